@@ -1,0 +1,190 @@
+/*
+ * sja.h -- C ABI of the batched gap-job fit / slot-grant engine for one
+ * scheduling tick of Scheduler-Driven Job Atomization (MI355X, gfx950).
+ *
+ * One tick of the paper's three-phase protocol (Sec. 3.5), evaluated for every
+ * advertised gap and every waiting job at once:
+ *
+ *   sja_prepare_profiles  per-job running duration / running peak / last safe
+ *                         boundary from the job's progress point (the on-demand
+ *                         evaluation of the envelope U(t), Sec. 3.9)
+ *   sja_fit               job -> scheduler reply for every (gap, job) pair:
+ *                         the longest safe subjob that fits, or decline
+ *                         (Sec. 3.5 phase 2, Sec. 3.8 admissibility, Sec. 3.9)
+ *   sja_select            scheduler policy arg-max per gap (Sec. 3.5 phase 3)
+ *   sja_resolve           grants, with conflicts settled in rounds so that a job
+ *                         holds at most one gap (Sec. 3.1 / 3.5: fragments of a
+ *                         job are sequential from one progress point)
+ *
+ * Conventions
+ *   - Every array argument is a DEVICE pointer owned by the caller, unless the
+ *     comment says "host".  The library never frees or reallocates them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     sja_prepare_profiles, sja_fit and sja_select only enqueue work and
+ *     return; outputs are valid once the stream has been synchronised.
+ *     sja_resolve runs a data-dependent number of rounds and synchronises the
+ *     stream before it returns.
+ *   - The context remembers the pointers and sizes handed to the previous
+ *     call of the sequence prepare -> fit -> select / resolve: the arrays of
+ *     sja_prepare_profiles must stay alive and unchanged until the last
+ *     sja_fit / sja_select / sja_resolve that uses them, and the `cut` matrix
+ *     of sja_fit until the last sja_select / sja_resolve.  Calling out of
+ *     order returns SJA_ERR_STATE.
+ *   - All scratch lives in one caller-owned workspace (sja_set_workspace);
+ *     the library itself allocates no device memory.
+ *   - Return value: SJA_OK (0) or a negative sja_status.  Arguments that can
+ *     be checked on the host (null pointers, negative sizes, bad enum values,
+ *     workspace too small) are rejected before any device work is enqueued.
+ *     No exception or abort crosses this boundary.
+ *
+ * Profile model.  Job j owns segments seg_off[j] .. seg_off[j+1]-1 (CSR).
+ * Segment k lasts dur[k] >= 1 ticks at mem[k] >= 0 MiB.  Boundaries of a job
+ * with L segments are numbered 0..L; boundary b lies before segment b, boundary
+ * L is the job's end.  safe[k] != 0 flags boundary k+1 (within the job) as a
+ * subjob boundary (Sec. 3.7); the end counts as one whatever its flag.
+ * progress[j] in [0, L] is the boundary the job has completed up to.
+ *
+ * Data-dependent preconditions (not checked): seg_off non-decreasing with
+ * seg_off[0] == 0 and seg_off[n_jobs] == n_segments; 0 <= progress[j] <= L_j;
+ * dur >= 1; mem >= 0; per job, the sum of durations fits int32; every policy
+ * score (see sja_params) fits int64.
+ */
+#ifndef SJA_H
+#define SJA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sja_ctx sja_ctx; /* opaque; host-side bookkeeping only */
+
+typedef enum {
+    SJA_OK = 0,
+    SJA_ERR_NULL = -1,      /* a required pointer is NULL                      */
+    SJA_ERR_SIZE = -2,      /* a size is negative or beyond the supported max  */
+    SJA_ERR_POLICY = -3,    /* bad policy enum or policy parameter             */
+    SJA_ERR_STATE = -4,     /* call out of sequence                            */
+    SJA_ERR_OVERFLOW = -5,  /* G*J or a byte count does not fit                */
+    SJA_ERR_WORKSPACE = -6, /* workspace missing, misaligned or too small      */
+    SJA_ERR_HIP = -7,       /* a HIP runtime call failed (see sja_last_error)  */
+    SJA_ERR_NOT_IMPLEMENTED = -8
+} sja_status;
+
+typedef enum {
+    SJA_POLICY_EFFICIENCY = 0, /* key = F                                           */
+    SJA_POLICY_FAIRNESS = 1,   /* key = F * (wait_scale + wait[j])                  */
+    SJA_POLICY_SLA = 2,        /* key = (class-0 tier, F * sla_weight[class[j]])    */
+    SJA_POLICY_MIXED = 3       /* key = (2 - class[j], F * (wait_scale + wait[j]), F) */
+} sja_policy;
+
+/*
+ * Policy parameters (Sec. 3.5: the scheduler "applies its allocation policy";
+ * Sec. 4.2: a lightweight selection among interested jobs).  F is the
+ * capacity-time rectangle a subjob fills: its duration times its peak memory.
+ * Keys compare lexicographically, larger wins, equal keys go to the lower job
+ * id.  The score reported for a candidate is the key's score term (F, or the
+ * weighted F).
+ */
+typedef struct {
+    int32_t policy;          /* sja_policy                                        */
+    int32_t wait_scale;      /* > 0; 1000 reproduces F * (1 + wait/1000) exactly  */
+    int32_t sla_weight[3];   /* >= 0; per SLA class 0,1,2 (class 0 = most urgent) */
+    int32_t class0_override; /* SLA: nonzero = any class-0 job beats other classes */
+    int32_t max_rounds;      /* sja_resolve: >= 0; 0 = run until stable           */
+} sja_params;
+
+/* Largest sizes the library accepts. */
+#define SJA_MAX_JOBS 16777216      /* 2^24 */
+#define SJA_MAX_GAPS 1048576       /* 2^20 */
+#define SJA_MAX_SEGMENTS 2147483647 /* 2^31-1 */
+
+/* Creates a context bound to HIP device `device_id`.  Touches no device.
+ * *out (host) receives the context; free it with sja_destroy. */
+int sja_create(sja_ctx **out, int device_id);
+int sja_destroy(sja_ctx *ctx);
+
+/* Bytes of workspace needed for a tick of this size (0 on invalid sizes). */
+size_t sja_workspace_bytes(int64_t n_gaps, int64_t n_jobs, int64_t n_segments);
+
+/* Hands the library a caller-owned device buffer (256-byte aligned).  It must
+ * stay alive while the context uses it and may be replaced between ticks.
+ * Its contents are private to the library between sja_prepare_profiles and
+ * the last call of that tick. */
+int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes);
+
+/* Static string for a status code; last error text of a context (host). */
+const char *sja_status_string(int status);
+const char *sja_last_error(const sja_ctx *ctx);
+
+/*
+ * Per-job segmented scans from the progress point (Sec. 3.9: segmentation is
+ * evaluated on demand from the job's current state).  For each job j with
+ * p = progress[j] and each boundary b = p+1 .. L_j, at entry k = seg_off[j]+b-1:
+ *   pre_dur[k]   = dur[p] + ... + dur[b-1]            (running duration D_j(b))
+ *   pre_peak[k]  = max(mem[p], ..., mem[b-1])         (running peak P_j(b))
+ *   prev_safe[k] = largest safe boundary in (p, b], or -1 if there is none
+ * Entries of segments before the progress point are not written.
+ * Also builds the library's private per-job tables in the workspace.
+ *   seg_off [n_jobs+1] int64, dur/mem [n_segments] int32, safe [n_segments]
+ *   uint8, progress [n_jobs] int32; outputs [n_segments] int32 each.
+ * Needs a workspace sized for (any n_gaps, n_jobs, n_segments).
+ */
+int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
+                         const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                         const uint8_t *safe, const int32_t *progress, int32_t *pre_dur,
+                         int32_t *pre_peak, int32_t *prev_safe);
+
+/*
+ * Fit evaluation for every (gap, job) pair (Sec. 3.5 phase 2; Sec. 3.8: a
+ * subjob is admissible on capacity C over its lifetime if its demand stays
+ * <= C; Sec. 3.9: max of U over the window <= c, longer fragments preferred).
+ *   cut[g*n_jobs + j] = largest boundary b in (progress[j], L_j] that is safe,
+ *                       with D_j(b) <= W[g] and P_j(b) <= C[g]; -1 = decline.
+ *   interest_bits[g*ceil(n_jobs/32) + j/32] bit (j%32) = (cut >= 0); may be NULL.
+ * W, C [n_gaps] int32 (a negative W or C fits nothing).  Uses the profiles of
+ * the last sja_prepare_profiles.  cut is row-major by gap: one row holds one
+ * gap's replies.
+ */
+int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
+            int32_t *cut, uint32_t *interest_bits);
+
+/*
+ * Policy arg-max per gap over the interested jobs of the last sja_fit
+ * (Sec. 3.5 phase 3).  A job with job_held[j] >= 0 is skipped (job_held may be
+ * NULL = none held); a gap with gap_active[g] == 0 gets no candidate
+ * (gap_active may be NULL = all active).  wait [n_jobs] int32 and sla_class
+ * [n_jobs] uint8 (values 0..2) are required by the policies that read them
+ * (FAIRNESS/MIXED: wait; SLA/MIXED: sla_class) and may be NULL otherwise.
+ *   cand_job[g]   winning job id, or -1 if no candidate
+ *   cand_cut[g]   its cut (-1 if none)
+ *   cand_score[g] its score term (0 if none)
+ */
+int sja_select(sja_ctx *ctx, void *stream, const sja_params *params, const int32_t *wait,
+               const uint8_t *sla_class, const int32_t *job_held, const uint8_t *gap_active,
+               int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score);
+
+/*
+ * Grants with conflict resolution in deterministic rounds (Sec. 3.5: one job
+ * is granted per slot; Sec. 3.1 / 3.5: a job's fragments are sequential, so it
+ * can hold one gap per tick).  Round: every ungranted gap selects among the
+ * jobs no gap holds yet; each selected job keeps the lowest-index gap that
+ * selected it and that grant is final; the other gaps reselect next round.
+ * Ends when a round finds no candidate or leaves no loser, or after
+ * params->max_rounds rounds (then the last round's losers stay ungranted).
+ *   grant_job/grant_cut [n_gaps] int32 (-1 = ungranted), grant_score [n_gaps]
+ *   int64 (0 = ungranted), job_gap [n_jobs] int32 (gap held by the job or -1),
+ *   rounds_used_and_stable [2] int32: rounds in which a selection ran, and 1
+ *   if the process ended by itself (0 if the round cap cut it short).
+ * Synchronises `stream` before returning.
+ */
+int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int32_t *wait,
+                const uint8_t *sla_class, int32_t *grant_job, int32_t *grant_cut,
+                int64_t *grant_score, int32_t *job_gap, int32_t *rounds_used_and_stable);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SJA_H */

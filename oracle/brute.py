@@ -1,0 +1,123 @@
+"""TEST INFRASTRUCTURE: from-scratch brute force in pure Python, tiny inputs only.
+
+An independent restatement of the definitions used to pin oracle/sja_oracle.c:
+nothing is accumulated incrementally, nothing is assumed monotone, every
+candidate boundary is tested on its own, the arg-max is a full sort and the
+conflict rounds are simulated with explicit sets.  Python integers are
+unbounded, so no overflow question arises here.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence, Tuple
+
+EFFICIENCY, FAIRNESS, SLA, MIXED = 0, 1, 2, 3
+
+
+def job_slices(seg_off, arr, j):
+    return [int(x) for x in arr[int(seg_off[j]):int(seg_off[j + 1])]]
+
+
+def fit_one(dur: Sequence[int], mem: Sequence[int], safe: Sequence[int], p: int,
+            W: int, C: int) -> int:
+    """Largest safe boundary b in (p, L] whose subjob [p, b) fits (Sec. 3.8-3.9)."""
+    L = len(dur)
+    for b in range(L, p, -1):                     # every boundary, longest first
+        is_safe = (b == L) or bool(safe[b - 1])
+        if not is_safe:
+            continue
+        total = sum(dur[p:b])                     # recomputed from scratch
+        peak = max(mem[p:b])
+        if total <= W and peak <= C:
+            return b
+    return -1
+
+
+def fit_all(seg_off, dur, mem, safe, progress, W, C) -> List[List[int]]:
+    J = len(seg_off) - 1
+    out = []
+    for g in range(len(W)):
+        row = []
+        for j in range(J):
+            row.append(fit_one(job_slices(seg_off, dur, j), job_slices(seg_off, mem, j),
+                               job_slices(seg_off, safe, j), int(progress[j]),
+                               int(W[g]), int(C[g])))
+        out.append(row)
+    return out
+
+
+def key_of(policy: int, sub_dur: int, sub_peak: int, wait: int, cls: int, wait_scale: int,
+           sla_weight: Sequence[int], class0_override: int) -> Tuple[int, int, int]:
+    F = sub_dur * sub_peak
+    if policy == EFFICIENCY:
+        return (0, F, 0)
+    if policy == FAIRNESS:
+        return (0, F * (wait_scale + wait), 0)
+    if policy == SLA:
+        return (1 if (class0_override and cls == 0) else 0, F * sla_weight[cls], 0)
+    if policy == MIXED:
+        return (2 - cls, F * (wait_scale + wait), F)
+    raise ValueError(policy)
+
+
+def select_gap(cut_row, seg_off, dur, mem, progress, wait, sla_class, policy,
+               wait_scale=1000, sla_weight=(4, 2, 1), class0_override=1,
+               held: Optional[set] = None):
+    """(job, cut, score) for one gap: sort every candidate, take the first."""
+    cands = []
+    for j, c in enumerate(cut_row):
+        if c < 0 or (held is not None and j in held):
+            continue
+        d = job_slices(seg_off, dur, j)
+        m = job_slices(seg_off, mem, j)
+        p = int(progress[j])
+        key = key_of(policy, sum(d[p:c]), max(m[p:c]), int(wait[j]), int(sla_class[j]),
+                     wait_scale, sla_weight, class0_override)
+        cands.append((key, j, c))
+    if not cands:
+        return (-1, -1, 0)
+    cands.sort(key=lambda t: (-t[0][0], -t[0][1], -t[0][2], t[1]))
+    key, j, c = cands[0]
+    return (j, c, key[1])
+
+
+def resolve(cut, seg_off, dur, mem, progress, wait, sla_class, policy, max_rounds=0,
+            wait_scale=1000, sla_weight=(4, 2, 1), class0_override=1):
+    """Literal simulation of the grant rounds with explicit sets."""
+    G = len(cut)
+    J = len(seg_off) - 1
+    grant = {g: None for g in range(G)}
+    held = set()
+    holder = {}
+    cap = max_rounds if max_rounds > 0 else min(G, J) + 1
+    rounds, stable = 0, 0
+    for _ in range(cap):
+        choice = {}
+        for g in range(G):
+            if grant[g] is not None:
+                continue
+            j, c, s = select_gap(cut[g], seg_off, dur, mem, progress, wait, sla_class, policy,
+                                 wait_scale, sla_weight, class0_override, held)
+            if j >= 0:
+                choice[g] = (j, c, s)
+        rounds += 1
+        if not choice:
+            stable = 1
+            break
+        wanted = {}
+        for g, (j, c, s) in choice.items():
+            wanted.setdefault(j, []).append(g)
+        lost = 0
+        for j, gaps in wanted.items():
+            g_star = min(gaps)
+            grant[g_star] = choice[g_star]
+            held.add(j)
+            holder[j] = g_star
+            lost += len(gaps) - 1
+        if lost == 0:
+            stable = 1
+            break
+    grant_job = [grant[g][0] if grant[g] else -1 for g in range(G)]
+    grant_cut = [grant[g][1] if grant[g] else -1 for g in range(G)]
+    grant_score = [grant[g][2] if grant[g] else 0 for g in range(G)]
+    job_gap = [holder.get(j, -1) for j in range(J)]
+    return grant_job, grant_cut, grant_score, job_gap, rounds, stable
