@@ -1,0 +1,175 @@
+"""Thin ctypes binding over libsja.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch is used for
+device memory (tensors) and the current stream.  There is no CPU fallback: if
+the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+from . import build as _build
+
+POLICY_EFFICIENCY, POLICY_FAIRNESS, POLICY_SLA, POLICY_MIXED = 0, 1, 2, 3
+
+_lib = None
+
+
+class SjaError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{text} (status {status})")
+        self.status = status
+
+
+class Params(ctypes.Structure):
+    """Mirror of sja_params."""
+    _fields_ = [("policy", ctypes.c_int32), ("wait_scale", ctypes.c_int32),
+                ("sla_weight", ctypes.c_int32 * 3), ("class0_override", ctypes.c_int32),
+                ("max_rounds", ctypes.c_int32)]
+
+    @classmethod
+    def make(cls, policy: int, wait_scale: int = 1000, sla_weight: Sequence[int] = (4, 2, 1),
+             class0_override: int = 1, max_rounds: int = 0) -> "Params":
+        return cls(policy, wait_scale, (ctypes.c_int32 * 3)(*sla_weight), class0_override,
+                   max_rounds)
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Loads the built library (builds it only if no library is there at all)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or _build.LIB
+    if not os.path.exists(p):
+        _build.build(force=True)
+    if not os.path.exists(p):
+        raise FileNotFoundError(f"{p} is missing: run `python -m paper_2509_19086_amd.build`")
+    lib = ctypes.CDLL(p)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.sja_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
+    lib.sja_create.restype = ctypes.c_int
+    lib.sja_destroy.argtypes = [vp]
+    lib.sja_destroy.restype = ctypes.c_int
+    lib.sja_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.sja_workspace_bytes.restype = ctypes.c_size_t
+    lib.sja_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.sja_set_workspace.restype = ctypes.c_int
+    lib.sja_status_string.argtypes = [ctypes.c_int]
+    lib.sja_status_string.restype = ctypes.c_char_p
+    lib.sja_last_error.argtypes = [vp]
+    lib.sja_last_error.restype = ctypes.c_char_p
+    lib.sja_prepare_profiles.argtypes = [vp, vp, i32, i64] + [vp] * 8
+    lib.sja_prepare_profiles.restype = ctypes.c_int
+    lib.sja_fit.argtypes = [vp, vp, i32] + [vp] * 4
+    lib.sja_fit.restype = ctypes.c_int
+    lib.sja_select.argtypes = [vp, vp, ctypes.POINTER(Params)] + [vp] * 7
+    lib.sja_select.restype = ctypes.c_int
+    lib.sja_resolve.argtypes = [vp, vp, ctypes.POINTER(Params)] + [vp] * 7
+    lib.sja_resolve.restype = ctypes.c_int
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: torch.dtype, n: Optional[int] = None) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not isinstance(t, torch.Tensor) or t.dtype != dtype:
+        raise TypeError(f"expected a {dtype} tensor, got {getattr(t, 'dtype', type(t))}")
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous and on the GPU")
+    if n is not None and t.numel() < n:
+        raise ValueError(f"tensor has {t.numel()} elements, {n} needed")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Engine:
+    """One sja_ctx plus its workspace tensor.  Methods mirror the C entry points."""
+
+    def __init__(self, device: int = 0):
+        self.lib = load_library()
+        self.device = device
+        h = ctypes.c_void_p()
+        self._check(self.lib.sja_create(ctypes.byref(h), device), None)
+        self.h = h
+        self.workspace: Optional[torch.Tensor] = None
+        self.n_jobs = 0
+        self.n_gaps = 0
+
+    def close(self) -> None:
+        if getattr(self, "h", None):
+            self.lib.sja_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int, h) -> None:
+        if rc != 0:
+            text = self.lib.sja_last_error(h).decode() if h else self.lib.sja_status_string(rc).decode()
+            raise SjaError(rc, text)
+
+    def workspace_bytes(self, n_gaps: int, n_jobs: int, n_segments: int) -> int:
+        return int(self.lib.sja_workspace_bytes(n_gaps, n_jobs, n_segments))
+
+    def ensure_workspace(self, n_gaps: int, n_jobs: int, n_segments: int) -> None:
+        need = self.workspace_bytes(n_gaps, n_jobs, n_segments)
+        if need == 0 and (n_gaps or n_jobs or n_segments):
+            raise SjaError(-2, "sizes beyond the library's limits")
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(max(need, 256), dtype=torch.uint8,
+                                         device=f"cuda:{self.device}")
+            self._check(self.lib.sja_set_workspace(self.h, ctypes.c_void_p(self.workspace.data_ptr()),
+                                                   self.workspace.numel()), self.h)
+
+    # -- the four calls --------------------------------------------------
+    def sja_prepare_profiles(self, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe):
+        J = seg_off.numel() - 1
+        S = dur.numel()
+        args = (_ptr(seg_off, torch.int64, J + 1), _ptr(dur, torch.int32, S),
+                _ptr(mem, torch.int32, S), _ptr(safe, torch.uint8, S), _ptr(progress, torch.int32, J),
+                _ptr(pre_dur, torch.int32, S), _ptr(pre_peak, torch.int32, S),
+                _ptr(prev_safe, torch.int32, S))
+        rc = self.lib.sja_prepare_profiles(self.h, _stream(), J, S, *args)
+        self._check(rc, self.h)
+        self.n_jobs = J
+
+    def sja_fit(self, W, C, cut, interest_bits=None):
+        G = W.numel()
+        words = (self.n_jobs + 31) // 32
+        args = (_ptr(W, torch.int32, G), _ptr(C, torch.int32, G),
+                _ptr(cut, torch.int32, G * self.n_jobs), _ptr(interest_bits, torch.int32, G * words))
+        rc = self.lib.sja_fit(self.h, _stream(), G, *args)
+        self._check(rc, self.h)
+        self.n_gaps = G
+
+    def sja_select(self, params: Params, wait, sla_class, job_held, gap_active,
+                   cand_job, cand_cut, cand_score):
+        G, J = self.n_gaps, self.n_jobs
+        args = (_ptr(wait, torch.int32, J), _ptr(sla_class, torch.uint8, J),
+                _ptr(job_held, torch.int32, J), _ptr(gap_active, torch.uint8, G),
+                _ptr(cand_job, torch.int32, G), _ptr(cand_cut, torch.int32, G),
+                _ptr(cand_score, torch.int64, G))
+        rc = self.lib.sja_select(self.h, _stream(), ctypes.byref(params), *args)
+        self._check(rc, self.h)
+
+    def sja_resolve(self, params: Params, wait, sla_class, grant_job, grant_cut, grant_score,
+                    job_gap, rounds_used_and_stable):
+        G, J = self.n_gaps, self.n_jobs
+        args = (_ptr(wait, torch.int32, J), _ptr(sla_class, torch.uint8, J),
+                _ptr(grant_job, torch.int32, G), _ptr(grant_cut, torch.int32, G),
+                _ptr(grant_score, torch.int64, G), _ptr(job_gap, torch.int32, J),
+                _ptr(rounds_used_and_stable, torch.int32, 2))
+        rc = self.lib.sja_resolve(self.h, _stream(), ctypes.byref(params), *args)
+        self._check(rc, self.h)

@@ -1,0 +1,322 @@
+// C ABI of the gap-job fit / slot-grant engine: argument validation, workspace
+// bookkeeping and kernel launches.  See include/sja.h for the contract.
+#include "sja_kernels.h"
+
+#include <new>
+
+using namespace sja;
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceGuard(int dev)
+    {
+        err = hipGetDevice(&prev);
+        if (err == hipSuccess && prev != dev) {
+            err = hipSetDevice(dev);
+            switched = (err == hipSuccess);
+        }
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+int fail(sja_ctx *ctx, int status, const char *what)
+{
+    if (ctx) snprintf(ctx->err, sizeof(ctx->err), "%s: %s", sja_status_string(status), what);
+    return status;
+}
+
+int fail_hip(sja_ctx *ctx, hipError_t e, const char *what)
+{
+    if (ctx) snprintf(ctx->err, sizeof(ctx->err), "HIP error in %s: %s", what, hipGetErrorString(e));
+    return SJA_ERR_HIP;
+}
+
+#define SJA_HIP(call, what)                                        \
+    do {                                                           \
+        hipError_t e__ = (call);                                   \
+        if (e__ != hipSuccess) return fail_hip(ctx, e__, what);    \
+    } while (0)
+
+template <typename T>
+T *ws_ptr(sja_ctx *ctx, size_t off) { return reinterpret_cast<T *>(ctx->ws + off); }
+
+int check_params(sja_ctx *ctx, const sja_params *p, const int32_t *wait, const uint8_t *sla_class)
+{
+    if (!p) return fail(ctx, SJA_ERR_NULL, "params");
+    if (p->policy < SJA_POLICY_EFFICIENCY || p->policy > SJA_POLICY_MIXED)
+        return fail(ctx, SJA_ERR_POLICY, "unknown policy");
+    if (p->wait_scale <= 0) return fail(ctx, SJA_ERR_POLICY, "wait_scale must be > 0");
+    for (int i = 0; i < 3; ++i)
+        if (p->sla_weight[i] < 0) return fail(ctx, SJA_ERR_POLICY, "sla_weight must be >= 0");
+    if (p->max_rounds < 0) return fail(ctx, SJA_ERR_POLICY, "max_rounds must be >= 0");
+    const bool needs_wait = p->policy == SJA_POLICY_FAIRNESS || p->policy == SJA_POLICY_MIXED;
+    const bool needs_class = p->policy == SJA_POLICY_SLA || p->policy == SJA_POLICY_MIXED;
+    if (needs_wait && !wait) return fail(ctx, SJA_ERR_NULL, "wait is required by this policy");
+    if (needs_class && !sla_class) return fail(ctx, SJA_ERR_NULL, "sla_class is required by this policy");
+    return SJA_OK;
+}
+
+PolicyDev to_dev(const sja_params *p)
+{
+    PolicyDev d;
+    d.policy = p->policy;
+    d.wait_scale = p->wait_scale;
+    d.w0 = p->sla_weight[0];
+    d.w1 = p->sla_weight[1];
+    d.w2 = p->sla_weight[2];
+    d.class0_override = p->class0_override;
+    return d;
+}
+
+// Enqueues the two select kernels; outputs may be user or workspace arrays.
+int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const int32_t *wait,
+                  const uint8_t *sla_class, const int32_t *job_held, const uint8_t *gap_active,
+                  int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score)
+{
+    const Layout L = make_layout(ctx->n_gaps, ctx->n_jobs, ctx->n_segments);
+    const int G = ctx->n_gaps, J = ctx->n_jobs;
+    if (G == 0) return SJA_OK;
+    const int job_tiles = (J + kSelBlock - 1) / kSelBlock;
+    if (job_tiles > 0) {
+        const int n_chunks = (G + kSelGapChunk - 1) / kSelGapChunk;
+        const int tiles8 = (job_tiles + 7) / 8 * 8;
+        const unsigned grid = unsigned(tiles8) * unsigned(n_chunks);
+        hipLaunchKernelGGL(k_select_pass, dim3(grid), dim3(kSelBlock), 0, st, J, G, n_chunks,
+                           to_dev(params), ctx->seg_off, ctx->pre_dur, ctx->pre_peak, ctx->cut,
+                           ws_ptr<int32_t>(ctx, L.gap_order), wait, sla_class, job_held, gap_active,
+                           ws_ptr<SelPartial>(ctx, L.sel_part));
+        SJA_HIP(hipGetLastError(), "k_select_pass launch");
+    }
+    hipLaunchKernelGGL(k_select_reduce, dim3((G + 255) / 256), dim3(256), 0, st, G, job_tiles,
+                       ws_ptr<SelPartial>(ctx, L.sel_part), cand_job, cand_cut, cand_score);
+    SJA_HIP(hipGetLastError(), "k_select_reduce launch");
+    return SJA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *sja_status_string(int status)
+{
+    switch (status) {
+    case SJA_OK: return "SJA_OK";
+    case SJA_ERR_NULL: return "SJA_ERR_NULL";
+    case SJA_ERR_SIZE: return "SJA_ERR_SIZE";
+    case SJA_ERR_POLICY: return "SJA_ERR_POLICY";
+    case SJA_ERR_STATE: return "SJA_ERR_STATE";
+    case SJA_ERR_OVERFLOW: return "SJA_ERR_OVERFLOW";
+    case SJA_ERR_WORKSPACE: return "SJA_ERR_WORKSPACE";
+    case SJA_ERR_HIP: return "SJA_ERR_HIP";
+    case SJA_ERR_NOT_IMPLEMENTED: return "SJA_ERR_NOT_IMPLEMENTED";
+    default: return "SJA_ERR_UNKNOWN";
+    }
+}
+
+const char *sja_last_error(const sja_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+int sja_create(sja_ctx **out, int device_id)
+{
+    if (!out) return SJA_ERR_NULL;
+    *out = nullptr;
+    if (device_id < 0) return SJA_ERR_SIZE;
+    sja_ctx *ctx = new (std::nothrow) sja_ctx();
+    if (!ctx) return SJA_ERR_WORKSPACE;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->device = device_id;
+    *out = ctx;
+    return SJA_OK;
+}
+
+int sja_destroy(sja_ctx *ctx)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    delete ctx;
+    return SJA_OK;
+}
+
+size_t sja_workspace_bytes(int64_t n_gaps, int64_t n_jobs, int64_t n_segments)
+{
+    if (n_gaps < 0 || n_jobs < 0 || n_segments < 0) return 0;
+    if (n_gaps > SJA_MAX_GAPS || n_jobs > SJA_MAX_JOBS || n_segments > SJA_MAX_SEGMENTS) return 0;
+    return make_layout(n_gaps, n_jobs, n_segments).total;
+}
+
+int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!dev_ptr && bytes) return fail(ctx, SJA_ERR_NULL, "workspace pointer");
+    if (reinterpret_cast<uintptr_t>(dev_ptr) & 255) return fail(ctx, SJA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    ctx->ws = static_cast<char *>(dev_ptr);
+    ctx->ws_bytes = bytes;
+    ctx->prepared = false;   // private tables lived in the old workspace
+    ctx->fitted = false;
+    return SJA_OK;
+}
+
+int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
+                         const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                         const uint8_t *safe, const int32_t *progress, int32_t *pre_dur,
+                         int32_t *pre_peak, int32_t *prev_safe)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    ctx->prepared = false;
+    ctx->fitted = false;
+    if (n_jobs < 0 || n_jobs > SJA_MAX_JOBS) return fail(ctx, SJA_ERR_SIZE, "n_jobs");
+    if (n_segments < 0 || n_segments > SJA_MAX_SEGMENTS) return fail(ctx, SJA_ERR_SIZE, "n_segments");
+    if (!seg_off || !progress) return fail(ctx, SJA_ERR_NULL, "seg_off / progress");
+    if (n_segments > 0 && (!dur || !mem || !safe || !pre_dur || !pre_peak || !prev_safe))
+        return fail(ctx, SJA_ERR_NULL, "profile or output array");
+    const Layout L = make_layout(0, n_jobs, n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small for prepare");
+
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_jobs > 0) {
+        const int jobs_per_block = 256 / kWave;
+        hipLaunchKernelGGL(k_prepare, dim3((n_jobs + jobs_per_block - 1) / jobs_per_block), dim3(256), 0, st,
+                           n_jobs, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe,
+                           ws_ptr<int32_t>(ctx, L.atom_dur), ws_ptr<int32_t>(ctx, L.atom_peak),
+                           ws_ptr<int32_t>(ctx, L.atom_bnd), ws_ptr<int32_t>(ctx, L.n_atoms));
+        SJA_HIP(hipGetLastError(), "k_prepare launch");
+    }
+    ctx->n_jobs = n_jobs;
+    ctx->n_segments = n_segments;
+    ctx->seg_off = seg_off;
+    ctx->pre_dur = pre_dur;
+    ctx->pre_peak = pre_peak;
+    ctx->prepared = true;
+    return SJA_OK;
+}
+
+int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
+            int32_t *cut, uint32_t *interest_bits)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    ctx->fitted = false;
+    if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_fit before sja_prepare_profiles");
+    if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
+    if (n_gaps > 0 && (!W || !C)) return fail(ctx, SJA_ERR_NULL, "W / C");
+    const int J = ctx->n_jobs;
+    if (n_gaps > 0 && J > 0 && !cut) return fail(ctx, SJA_ERR_NULL, "cut");
+    const Layout L = make_layout(n_gaps, J, ctx->n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small for this many gaps");
+
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_gaps > 0) {
+        int32_t *rank = ws_ptr<int32_t>(ctx, L.gap_rank);
+        hipLaunchKernelGGL(k_fill_i32, dim3((n_gaps + 255) / 256), dim3(256), 0, st, rank, int64_t(n_gaps), 0);
+        SJA_HIP(hipGetLastError(), "k_fill_i32 launch");
+        hipLaunchKernelGGL(k_gap_rank, dim3((n_gaps + 255) / 256, (n_gaps + kRankSpan - 1) / kRankSpan), dim3(256), 0, st,
+                           n_gaps, W, C, rank);
+        SJA_HIP(hipGetLastError(), "k_gap_rank launch");
+        hipLaunchKernelGGL(k_gap_scatter, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, W, C, rank,
+                           ws_ptr<int32_t>(ctx, L.gap_order), ws_ptr<int32_t>(ctx, L.gap_w),
+                           ws_ptr<int32_t>(ctx, L.gap_c));
+        SJA_HIP(hipGetLastError(), "k_gap_scatter launch");
+        if (J > 0) {
+            const int job_tiles = (J + kFitBlock - 1) / kFitBlock;
+            const int tiles8 = (job_tiles + 7) / 8 * 8;
+            const int n_chunks = (n_gaps + kFitGapChunk - 1) / kFitGapChunk;
+            const unsigned grid = unsigned(tiles8) * unsigned(n_chunks);
+            const int words = (J + 31) / 32;
+            hipLaunchKernelGGL(k_fit, dim3(grid), dim3(kFitBlock), 0, st, J, n_gaps, n_chunks, ctx->seg_off,
+                               ws_ptr<int32_t>(ctx, L.atom_dur), ws_ptr<int32_t>(ctx, L.atom_peak),
+                               ws_ptr<int32_t>(ctx, L.atom_bnd), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int32_t>(ctx, L.gap_order), ws_ptr<int32_t>(ctx, L.gap_w),
+                               ws_ptr<int32_t>(ctx, L.gap_c), cut, interest_bits, words);
+            SJA_HIP(hipGetLastError(), "k_fit launch");
+        }
+    }
+    ctx->n_gaps = n_gaps;
+    ctx->cut = cut;
+    ctx->fitted = true;
+    return SJA_OK;
+}
+
+int sja_select(sja_ctx *ctx, void *stream, const sja_params *params, const int32_t *wait,
+               const uint8_t *sla_class, const int32_t *job_held, const uint8_t *gap_active,
+               int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!ctx->fitted) return fail(ctx, SJA_ERR_STATE, "sja_select before sja_fit");
+    int rc = check_params(ctx, params, wait, sla_class);
+    if (rc != SJA_OK) return rc;
+    if (ctx->n_gaps > 0 && (!cand_job || !cand_cut || !cand_score)) return fail(ctx, SJA_ERR_NULL, "candidate outputs");
+    const Layout L = make_layout(ctx->n_gaps, ctx->n_jobs, ctx->n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small");
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    return launch_select(ctx, static_cast<hipStream_t>(stream), params, wait, sla_class, job_held,
+                         gap_active, cand_job, cand_cut, cand_score);
+}
+
+int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int32_t *wait,
+                const uint8_t *sla_class, int32_t *grant_job, int32_t *grant_cut,
+                int64_t *grant_score, int32_t *job_gap, int32_t *rounds_used_and_stable)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!ctx->fitted) return fail(ctx, SJA_ERR_STATE, "sja_resolve before sja_fit");
+    int rc = check_params(ctx, params, wait, sla_class);
+    if (rc != SJA_OK) return rc;
+    const int G = ctx->n_gaps, J = ctx->n_jobs;
+    if (G > 0 && (!grant_job || !grant_cut || !grant_score)) return fail(ctx, SJA_ERR_NULL, "grant outputs");
+    if (J > 0 && !job_gap) return fail(ctx, SJA_ERR_NULL, "job_gap");
+    if (!rounds_used_and_stable) return fail(ctx, SJA_ERR_NULL, "rounds_used_and_stable");
+    const Layout L = make_layout(G, J, ctx->n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small");
+
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    int32_t *cand_job = ws_ptr<int32_t>(ctx, L.res_cand_job);
+    int32_t *cand_cut = ws_ptr<int32_t>(ctx, L.res_cand_cut);
+    int64_t *cand_score = ws_ptr<int64_t>(ctx, L.res_cand_score);
+    uint8_t *active = ws_ptr<uint8_t>(ctx, L.res_active);
+    unsigned long long *claim = ws_ptr<unsigned long long>(ctx, L.res_claim);
+    int32_t *counters = ws_ptr<int32_t>(ctx, L.res_counters);
+
+    const int n_init = G > J ? G : J;
+    if (n_init > 0) {
+        hipLaunchKernelGGL(k_resolve_init, dim3((n_init + 255) / 256), dim3(256), 0, st, G, J, grant_job,
+                           grant_cut, grant_score, job_gap, active, claim);
+        SJA_HIP(hipGetLastError(), "k_resolve_init launch");
+    }
+    const int64_t cap = params->max_rounds > 0 ? params->max_rounds : int64_t(G < J ? G : J) + 1;
+    int32_t result[2] = {0, 0};
+    for (int64_t r = 1; r <= cap; ++r) {
+        ++result[0];
+        int32_t host_counters[2] = {0, 0};
+        if (G > 0) {
+            rc = launch_select(ctx, st, params, wait, sla_class, job_gap, active, cand_job, cand_cut, cand_score);
+            if (rc != SJA_OK) return rc;
+            const dim3 grid((G + 255) / 256), block(256);
+            hipLaunchKernelGGL(k_claim, grid, block, 0, st, G, int(r), active, cand_job, claim, counters);
+            SJA_HIP(hipGetLastError(), "k_claim launch");
+            hipLaunchKernelGGL(k_commit, grid, block, 0, st, G, int(r), active, cand_job, cand_cut, cand_score,
+                               claim, grant_job, grant_cut, grant_score, job_gap, counters);
+            SJA_HIP(hipGetLastError(), "k_commit launch");
+            SJA_HIP(hipMemcpyAsync(host_counters, counters, sizeof(host_counters), hipMemcpyDeviceToHost, st),
+                    "counter readback");
+            SJA_HIP(hipStreamSynchronize(st), "round synchronise");
+        }
+        if (host_counters[0] == 0 || host_counters[1] == 0) { result[1] = 1; break; }
+    }
+    SJA_HIP(hipMemcpyAsync(rounds_used_and_stable, result, sizeof(result), hipMemcpyHostToDevice, st),
+            "rounds writeback");
+    SJA_HIP(hipStreamSynchronize(st), "final synchronise");
+    return SJA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,437 @@
+// Device kernels (gfx950, wave64) for the four steps of a scheduling tick.
+// Integer-only; no matrix cores: nothing here is a dense contraction.
+#pragma once
+
+#include "sja_internal.h"
+
+namespace sja {
+
+// --------------------------------------------------------------------------
+// wave64 helpers
+// --------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ unsigned long long lanes_below(int lane)
+{
+    return lane == 0 ? 0ull : (~0ull >> (64 - lane));
+}
+
+// Inclusive wave scan of (sum, max, max) triples, Hillis-Steele over 64 lanes.
+__device__ __forceinline__ void wave_scan_add_max_max(int &s, int &m, int &l, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int s2 = __shfl_up(s, d, kWave);
+        int m2 = __shfl_up(m, d, kWave);
+        int l2 = __shfl_up(l, d, kWave);
+        if (lane >= d) {
+            s += s2;
+            m = max(m, m2);
+            l = max(l, l2);
+        }
+    }
+}
+
+// --------------------------------------------------------------------------
+// K1  per-job segmented scans from the progress point (Sec. 3.9: evaluate the
+// envelope on demand from the job's current state).  One wave per job walks
+// the remaining segments 64 at a time with coalesced SoA loads and a carry.
+// Besides the caller-visible prefixes it compacts the job's safe boundaries
+// ("atoms": running duration, running peak, boundary index at each safe cut
+// after the progress point) into the workspace at the job's segment base.
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_prepare(
+    int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
+    const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
+    int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
+    int32_t *__restrict__ atom_dur, int32_t *__restrict__ atom_peak,
+    int32_t *__restrict__ atom_bnd, int32_t *__restrict__ n_atoms)
+{
+    const int lane = lane_id();
+    const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (j >= n_jobs) return;
+    const int64_t base = seg_off[j];
+    const int L = int(seg_off[j + 1] - base);
+    int p = progress[j];
+    p = p < 0 ? 0 : (p > L ? L : p);
+
+    int carry_sum = 0, carry_peak = INT32_MIN, carry_last = -1, count = 0;
+    for (int k0 = p; k0 < L; k0 += kWave) {
+        const int k = k0 + lane;
+        const bool valid = k < L;
+        int s = 0, m = INT32_MIN, l = -1;
+        bool flag = false;
+        if (valid) {
+            s = dur[base + k];
+            m = mem[base + k];
+            flag = (safe[base + k] != 0) || (k + 1 == L);
+            l = flag ? k + 1 : -1;
+        }
+        wave_scan_add_max_max(s, m, l, lane);
+        s += carry_sum;
+        m = max(m, carry_peak);
+        l = max(l, carry_last);
+        if (valid) {
+            pre_dur[base + k] = s;
+            pre_peak[base + k] = m;
+            prev_safe[base + k] = l;
+        }
+        const unsigned long long mask = __ballot(flag);
+        if (flag) {
+            const int idx = count + __popcll(mask & lanes_below(lane));
+            atom_dur[base + idx] = s;
+            atom_peak[base + idx] = m;
+            atom_bnd[base + idx] = k + 1;
+        }
+        count += __popcll(mask);
+        carry_sum = __shfl(s, kWave - 1, kWave);
+        carry_peak = __shfl(m, kWave - 1, kWave);
+        carry_last = __shfl(l, kWave - 1, kWave);
+    }
+    if (lane == 0) n_atoms[j] = count;
+}
+
+// --------------------------------------------------------------------------
+// Gap ordering.  Gaps are sorted by (C, W, index) so that a run of sorted
+// positions shares one capacity and has non-decreasing windows.  Rank sort:
+// rank[g] = number of gaps that order before g; exact, deterministic.
+// --------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long gap_key(int w, int c)
+{
+    return (static_cast<unsigned long long>(static_cast<uint32_t>(c) ^ 0x80000000u) << 32) |
+           (static_cast<uint32_t>(w) ^ 0x80000000u);
+}
+
+__global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+constexpr int kRankSpan = 2048;  // gaps compared against per block in k_gap_rank
+
+__global__ __launch_bounds__(256) void k_gap_rank(int n_gaps, const int32_t *__restrict__ W,
+                                                  const int32_t *__restrict__ C,
+                                                  int32_t *__restrict__ rank)
+{
+    __shared__ unsigned long long tile[256];
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    const unsigned long long mine = g < n_gaps ? gap_key(W[g], C[g]) : 0ull;
+    const int h_begin = blockIdx.y * kRankSpan;
+    const int h_end = min(n_gaps, h_begin + kRankSpan);
+    int r = 0;
+    for (int h0 = h_begin; h0 < h_end; h0 += 256) {
+        const int h = h0 + threadIdx.x;
+        __syncthreads();
+        tile[threadIdx.x] = h < h_end ? gap_key(W[h], C[h]) : ~0ull;
+        __syncthreads();
+        const int n = min(256, h_end - h0);
+        for (int t = 0; t < n; ++t) {
+            const unsigned long long other = tile[t];
+            r += (other < mine) || (other == mine && (h0 + t) < g);
+        }
+    }
+    if (g < n_gaps && r) atomicAdd(&rank[g], r);
+}
+
+__global__ void k_gap_scatter(int n_gaps, const int32_t *__restrict__ W,
+                              const int32_t *__restrict__ C, const int32_t *__restrict__ rank,
+                              int32_t *__restrict__ order, int32_t *__restrict__ ws,
+                              int32_t *__restrict__ cs)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_gaps) return;
+    const int r = rank[g];
+    order[r] = g;
+    ws[r] = W[g];
+    cs[r] = C[g];
+}
+
+// --------------------------------------------------------------------------
+// K2  fit for every (gap, job) pair (Sec. 3.8 admissibility in the envelope
+// form of Sec. 3.9; the longest safe fragment is preferred).
+//
+// Over a job's atoms both the running duration and the running peak are
+// non-decreasing, so the answer for gap (W, C) is atom min(#{D <= W}, #{P <= C}) - 1.
+// Lanes run along jobs (coalesced 256-byte row stores); each block walks a
+// chunk of gap positions sorted by (C, W).  Within a run of equal C the count
+// #{P <= C} is fixed and #{D <= W} only grows, so each lane advances a merge
+// pointer through its job's atoms instead of searching; a binary search is
+// only needed at the start of a chunk and where C changes.
+// --------------------------------------------------------------------------
+__device__ __forceinline__ int upper_bound_i32(const int32_t *__restrict__ a, int n, int v)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] <= v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kFitBlock) void k_fit(
+    int n_jobs, int n_gaps, int n_chunks, const int64_t *__restrict__ seg_off,
+    const int32_t *__restrict__ atom_dur, const int32_t *__restrict__ atom_peak,
+    const int32_t *__restrict__ atom_bnd, const int32_t *__restrict__ n_atoms,
+    const int32_t *__restrict__ gap_order, const int32_t *__restrict__ gap_w,
+    const int32_t *__restrict__ gap_c, int32_t *__restrict__ cut,
+    uint32_t *__restrict__ bits, int words)
+{
+    // Blocks that share a job tile sit on one XCD (hardware deals consecutive
+    // block ids round-robin over the 8 XCDs), so the tile's atoms stay in that
+    // XCD's L2 while the gap chunks stream past.
+    const int xcd = blockIdx.x & 7;
+    const int k = blockIdx.x >> 3;
+    const int job_tile = (k / n_chunks) * 8 + xcd;
+    const int chunk = k % n_chunks;
+    const int j = job_tile * kFitBlock + threadIdx.x;
+    if (job_tile * kFitBlock >= n_jobs) return;
+    const bool live = j < n_jobs;
+
+    int64_t base = 0;
+    int n = 0;
+    if (live) {
+        base = seg_off[j];
+        n = n_atoms[j];
+    }
+    const int32_t *aD = atom_dur + base;
+    const int32_t *aP = atom_peak + base;
+    const int32_t *aB = atom_bnd + base;
+
+    const int s_begin = chunk * kFitGapChunk;
+    const int s_end = min(n_gaps, s_begin + kFitGapChunk);
+    const int lane = lane_id();
+    const int word0 = (job_tile * kFitBlock + (threadIdx.x & ~63)) >> 5;
+
+    int n_cap = 0;       // atoms whose running peak fits the current capacity
+    int a = 0;           // atoms whose running duration also fits the current window
+    int cur = -1;        // boundary of atom a-1, or -1
+    int next_d = 0;      // running duration of atom a (valid while a < n_cap)
+    int c_prev = 0;
+    for (int s = s_begin; s < s_end; ++s) {
+        const int w = gap_w[s];
+        const int c = gap_c[s];
+        const int g = gap_order[s];
+        if (s == s_begin || c != c_prev) {
+            c_prev = c;
+            n_cap = (w < 0) ? 0 : upper_bound_i32(aP, n, c);
+            a = upper_bound_i32(aD, n_cap, w);
+            cur = a > 0 ? aB[a - 1] : -1;
+            next_d = a < n_cap ? aD[a] : 0;
+        } else {
+            while (a < n_cap && next_d <= w) {
+                cur = aB[a];
+                ++a;
+                next_d = a < n_cap ? aD[a] : 0;
+            }
+        }
+        if (live) cut[int64_t(g) * n_jobs + j] = cur;
+        if (bits) {
+            const unsigned long long m = __ballot(live && cur >= 0);
+            if (lane == 0 && word0 < words) bits[int64_t(g) * words + word0] = uint32_t(m);
+            if (lane == 32 && word0 + 1 < words) bits[int64_t(g) * words + word0 + 1] = uint32_t(m >> 32);
+        }
+    }
+}
+
+// --------------------------------------------------------------------------
+// K3  policy arg-max per gap (Sec. 3.5 phase 3).  Lanes run along jobs and
+// walk a chunk of gap positions in the sorted order of the last fit, so a
+// job's cut -- and with it F = duration * peak -- rarely changes from one
+// position to the next and is kept in registers.  Per gap each wave reduces
+// its 64 candidates, waves combine through LDS, and each block leaves one
+// partial per (job tile, gap); k_select_reduce finishes the arg-max.
+// Key order: hi desc, lo desc, job asc.
+// --------------------------------------------------------------------------
+struct PolicyDev {
+    int policy;
+    int wait_scale;
+    int w0, w1, w2;
+    int class0_override;
+};
+
+__device__ __forceinline__ bool key_better(unsigned long long hi_a, unsigned long long lo_a, int j_a,
+                                           unsigned long long hi_b, unsigned long long lo_b, int j_b)
+{
+    if (hi_a != hi_b) return hi_a > hi_b;
+    if (lo_a != lo_b) return lo_a > lo_b;
+    return j_a < j_b;
+}
+
+__global__ __launch_bounds__(kSelBlock) void k_select_pass(
+    int n_jobs, int n_gaps, int n_chunks, PolicyDev pol, const int64_t *__restrict__ seg_off,
+    const int32_t *__restrict__ pre_dur, const int32_t *__restrict__ pre_peak,
+    const int32_t *__restrict__ cut, const int32_t *__restrict__ gap_order,
+    const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
+    const int32_t *__restrict__ job_held, const uint8_t *__restrict__ gap_active,
+    SelPartial *__restrict__ part)
+{
+    __shared__ unsigned long long s_hi[kSelBlock / kWave][kSelGapChunk];
+    __shared__ unsigned long long s_lo[kSelBlock / kWave][kSelGapChunk];
+    __shared__ int s_job[kSelBlock / kWave][kSelGapChunk];
+    __shared__ int s_cut[kSelBlock / kWave][kSelGapChunk];
+
+    const int xcd = blockIdx.x & 7;
+    const int k = blockIdx.x >> 3;
+    const int job_tile = (k / n_chunks) * 8 + xcd;
+    const int chunk = k % n_chunks;
+    if (job_tile * kSelBlock >= n_jobs) return;
+    const int j = job_tile * kSelBlock + threadIdx.x;
+    const int wave = threadIdx.x / kWave;
+    const int lane = lane_id();
+
+    bool usable = j < n_jobs;
+    int64_t base = 0;
+    unsigned long long mult = 1, tier = 0;
+    if (usable) {
+        if (job_held && job_held[j] >= 0) usable = false;
+        base = seg_off[j];
+        const int cls = sla_class ? sla_class[j] : 0;
+        const long long wt = wait ? wait[j] : 0;
+        switch (pol.policy) {
+        case SJA_POLICY_FAIRNESS: mult = (unsigned long long)(pol.wait_scale + wt); break;
+        case SJA_POLICY_SLA:
+            mult = (unsigned long long)(cls == 0 ? pol.w0 : (cls == 1 ? pol.w1 : pol.w2));
+            tier = (pol.class0_override && cls == 0) ? 1 : 0;
+            break;
+        case SJA_POLICY_MIXED:
+            mult = (unsigned long long)(pol.wait_scale + wt);
+            tier = (unsigned long long)(2 - cls);
+            break;
+        default: break;
+        }
+    }
+    const bool mixed = pol.policy == SJA_POLICY_MIXED;
+
+    const int s_begin = chunk * kSelGapChunk;
+    const int s_end = min(n_gaps, s_begin + kSelGapChunk);
+    int last_cut = -1;
+    unsigned long long hi = 0, lo = 0;
+    for (int s = s_begin; s < s_end; ++s) {
+        const int g = gap_order[s];
+        const int slot = s - s_begin;
+        if (gap_active && !gap_active[g]) {
+            if (lane == 0) { s_hi[wave][slot] = 0; s_lo[wave][slot] = 0; s_job[wave][slot] = -1; s_cut[wave][slot] = -1; }
+            continue;
+        }
+        int c = usable ? cut[int64_t(g) * n_jobs + j] : -1;
+        if (c >= 0 && c != last_cut) {
+            const unsigned long long F =
+                (unsigned long long)pre_dur[base + c - 1] * (unsigned long long)pre_peak[base + c - 1];
+            hi = ((tier << 62) | (F * mult)) + 1ull;
+            lo = mixed ? F : 0ull;
+            last_cut = c;
+        }
+        unsigned long long bh = c >= 0 ? hi : 0ull;
+        unsigned long long bl = c >= 0 ? lo : 0ull;
+        int bj = c >= 0 ? j : INT32_MAX;
+        int bc = c;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const unsigned long long oh = __shfl_xor(bh, d, kWave);
+            const unsigned long long ol = __shfl_xor(bl, d, kWave);
+            const int oj = __shfl_xor(bj, d, kWave);
+            const int oc = __shfl_xor(bc, d, kWave);
+            if (key_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; bc = oc; }
+        }
+        if (lane == 0) { s_hi[wave][slot] = bh; s_lo[wave][slot] = bl; s_job[wave][slot] = bj; s_cut[wave][slot] = bc; }
+    }
+    __syncthreads();
+    for (int slot = threadIdx.x; slot < s_end - s_begin; slot += kSelBlock) {
+        unsigned long long bh = s_hi[0][slot], bl = s_lo[0][slot];
+        int bj = s_job[0][slot], bc = s_cut[0][slot];
+        if (bh == 0) bj = INT32_MAX;
+#pragma unroll
+        for (int w = 1; w < kSelBlock / kWave; ++w) {
+            const unsigned long long oh = s_hi[w][slot], ol = s_lo[w][slot];
+            const int oj = oh ? s_job[w][slot] : INT32_MAX;
+            if (key_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; bc = s_cut[w][slot]; }
+        }
+        const int g = gap_order[s_begin + slot];
+        SelPartial out;
+        out.hi = bh; out.lo = bl; out.job = bh ? bj : -1; out.cut = bh ? bc : -1; out.pad = 0;
+        part[int64_t(job_tile) * n_gaps + g] = out;
+    }
+}
+
+__global__ void k_select_reduce(int n_gaps, int n_job_tiles, const SelPartial *__restrict__ part,
+                                int32_t *__restrict__ cand_job, int32_t *__restrict__ cand_cut,
+                                int64_t *__restrict__ cand_score)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_gaps) return;
+    unsigned long long bh = 0, bl = 0;
+    int bj = INT32_MAX, bc = -1;
+    for (int t = 0; t < n_job_tiles; ++t) {
+        const SelPartial p = part[int64_t(t) * n_gaps + g];
+        const int pj = p.hi ? p.job : INT32_MAX;
+        if (key_better(p.hi, p.lo, pj, bh, bl, bj)) { bh = p.hi; bl = p.lo; bj = pj; bc = p.cut; }
+    }
+    cand_job[g] = bh ? bj : -1;
+    cand_cut[g] = bh ? bc : -1;
+    cand_score[g] = bh ? int64_t((bh - 1ull) & ((1ull << 62) - 1ull)) : 0;
+}
+
+// --------------------------------------------------------------------------
+// K4  conflict rounds.  A round is: select over the still-active gaps with
+// the held jobs masked (kernels above), k_claim (each candidate job records
+// the lowest-index gap that named it, stamped with the round so that no reset
+// is needed), k_commit (winners become grants, losers stay active).
+// --------------------------------------------------------------------------
+__global__ void k_resolve_init(int n_gaps, int n_jobs, int32_t *grant_job, int32_t *grant_cut,
+                               int64_t *grant_score, int32_t *job_gap, uint8_t *active,
+                               unsigned long long *claim)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_gaps) { grant_job[i] = -1; grant_cut[i] = -1; grant_score[i] = 0; active[i] = 1; }
+    if (i < n_jobs) { job_gap[i] = -1; claim[i] = 0ull; }
+}
+
+__device__ __forceinline__ unsigned long long claim_word(int round, int g)
+{
+    return (static_cast<unsigned long long>(round) << 32) | (0xffffffffu - uint32_t(g));
+}
+
+__global__ void k_claim(int n_gaps, int round, const uint8_t *__restrict__ active,
+                        const int32_t *__restrict__ cand_job, unsigned long long *claim,
+                        int32_t *counters)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g == 0) { counters[0] = 0; counters[1] = 0; }
+    if (g >= n_gaps || !active[g]) return;
+    const int j = cand_job[g];
+    if (j >= 0) atomicMax(&claim[j], claim_word(round, g));
+}
+
+__global__ void k_commit(int n_gaps, int round, uint8_t *active, const int32_t *__restrict__ cand_job,
+                         const int32_t *__restrict__ cand_cut, const int64_t *__restrict__ cand_score,
+                         const unsigned long long *__restrict__ claim, int32_t *grant_job,
+                         int32_t *grant_cut, int64_t *grant_score, int32_t *job_gap,
+                         int32_t *counters)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    bool cand = false, lost = false;
+    if (g < n_gaps && active[g]) {
+        const int j = cand_job[g];
+        if (j >= 0) {
+            cand = true;
+            if (claim[j] == claim_word(round, g)) {
+                grant_job[g] = j;
+                grant_cut[g] = cand_cut[g];
+                grant_score[g] = cand_score[g];
+                job_gap[j] = g;
+                active[g] = 0;
+            } else {
+                lost = true;
+            }
+        }
+    }
+    const unsigned long long mc = __ballot(cand), ml = __ballot(lost);
+    if (lane_id() == 0) {
+        if (mc) atomicAdd(&counters[0], __popcll(mc));
+        if (ml) atomicAdd(&counters[1], __popcll(ml));
+    }
+}
+
+}  // namespace sja

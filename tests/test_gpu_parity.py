@@ -1,0 +1,170 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Everything is integer work, so the bar is bit-exact equality, element by
+element, on the same seeded inputs.
+"""
+import numpy as np
+import pytest
+
+from gen import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def engine():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2509_19086_amd as P
+    return P.Engine(0)
+
+
+def _params(P, wl, max_rounds=None):
+    return P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override,
+                         wl.max_rounds if max_rounds is None else max_rounds)
+
+
+def _oracle_params(O, wl, policy=None, max_rounds=None):
+    return O.Params.make(wl.policy if policy is None else policy, wl.wait_scale, wl.sla_weight,
+                         wl.class0_override, wl.max_rounds if max_rounds is None else max_rounds)
+
+
+def full_tick_check(engine, oracle, wl, policies=None, check_resolve=True):
+    """prepare, fit, select (each policy), resolve: every output equals the oracle's."""
+    import torch
+    import paper_2509_19086_amd as P
+    t = P.DeviceTick(engine, wl)
+    t.prepare()
+    t.fit()
+    torch.cuda.synchronize()
+
+    pd, pp, ps = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    np.testing.assert_array_equal(t.pre_dur.cpu().numpy().astype(np.int64), pd)
+    np.testing.assert_array_equal(t.pre_peak.cpu().numpy().astype(np.int64), pp)
+    np.testing.assert_array_equal(t.prev_safe.cpu().numpy(), ps)
+
+    cut, bits = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C)
+    np.testing.assert_array_equal(t.cut.cpu().numpy(), cut)
+    np.testing.assert_array_equal(t.bits.cpu().numpy().view(np.uint32), bits)
+
+    for policy in (policies if policies is not None else [wl.policy]):
+        par = P.Params.make(policy, wl.wait_scale, wl.sla_weight, wl.class0_override, wl.max_rounds)
+        t.select(par)
+        torch.cuda.synchronize()
+        cj, cc, cs = oracle.select(cut, wl.seg_off, pd, pp, _oracle_params(oracle, wl, policy),
+                                   wl.wait, wl.sla_class)
+        np.testing.assert_array_equal(t.cand_job.cpu().numpy(), cj)
+        np.testing.assert_array_equal(t.cand_cut.cpu().numpy(), cc)
+        np.testing.assert_array_equal(t.cand_score.cpu().numpy(), cs)
+        if check_resolve:
+            t.resolve(par)
+            gj, gc, gs, jg, rounds, stable = oracle.resolve(
+                cut, wl.seg_off, pd, pp, _oracle_params(oracle, wl, policy), wl.wait, wl.sla_class)
+            np.testing.assert_array_equal(t.grant_job.cpu().numpy(), gj)
+            np.testing.assert_array_equal(t.grant_cut.cpu().numpy(), gc)
+            np.testing.assert_array_equal(t.grant_score.cpu().numpy(), gs)
+            np.testing.assert_array_equal(t.job_gap.cpu().numpy(), jg)
+            assert t.rounds.cpu().tolist() == [rounds, stable]
+    return t
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4])
+def test_tiny_all_policies(engine, oracle, seed):
+    full_tick_check(engine, oracle, make_workload("tiny", seed), policies=[0, 1, 2, 3])
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_small_all_policies(engine, oracle, seed):
+    full_tick_check(engine, oracle, make_workload("small", seed), policies=[1, 0, 2, 3])
+
+
+def test_medium(engine, oracle):
+    full_tick_check(engine, oracle, make_workload("medium", 0))
+
+
+@pytest.mark.parametrize("name,G,J", [("large", 300, 1000), ("stress", 777, 2500),
+                                      ("stress", 130, 70), ("medium", 1, 1), ("small", 257, 65)])
+def test_ragged_shapes(engine, oracle, name, G, J):
+    """Sizes that are no multiple of any tile: ragged job tiles, gap chunks, bit words."""
+    wl = make_workload(name, 7, n_gaps=G, n_jobs=J)
+    full_tick_check(engine, oracle, wl, policies=[wl.policy, 3])
+
+
+def test_round_cap(engine, oracle):
+    wl = make_workload("small", 3)
+    for cap in (1, 2, 8):
+        wl.max_rounds = cap
+        full_tick_check(engine, oracle, wl, policies=[0])
+
+
+def test_select_with_held_jobs_and_inactive_gaps(engine, oracle):
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("small", 5)
+    t = P.DeviceTick(engine, wl)
+    t.prepare()
+    t.fit()
+    rng = np.random.default_rng(0)
+    held = np.where(rng.random(wl.n_jobs) < 0.5, 3, -1).astype(np.int32)
+    act = (rng.random(wl.n_gaps) < 0.7).astype(np.uint8)
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cut, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C, False)
+    for policy in (0, 1, 2, 3):
+        par = P.Params.make(policy)
+        t.select(par, torch.from_numpy(held).cuda(), torch.from_numpy(act).cuda())
+        torch.cuda.synchronize()
+        cj, cc, cs = oracle.select(cut, wl.seg_off, pd, pp, oracle.Params.make(policy), wl.wait,
+                                   wl.sla_class, held, act)
+        np.testing.assert_array_equal(t.cand_job.cpu().numpy(), cj)
+        np.testing.assert_array_equal(t.cand_cut.cpu().numpy(), cc)
+        np.testing.assert_array_equal(t.cand_score.cpu().numpy(), cs)
+
+
+def test_degenerate_profiles(engine, oracle):
+    """Empty jobs, finished jobs, monoliths, all-safe jobs, W/C at the int32 limits."""
+    import types
+    rng = np.random.default_rng(1)
+    lens = np.array([0, 5, 1, 0, 64, 65, 128, 3, 200, 0], dtype=np.int64)
+    seg_off = np.zeros(len(lens) + 1, dtype=np.int64)
+    np.cumsum(lens, out=seg_off[1:])
+    S = int(seg_off[-1])
+    dur = rng.integers(1, 50, size=S).astype(np.int32)
+    mem = rng.integers(0, 1000, size=S).astype(np.int32)
+    safe = (rng.random(S) < 0.3).astype(np.uint8)
+    safe[seg_off[4]:seg_off[5]] = 0                    # monolith
+    safe[seg_off[5]:seg_off[6]] = 1                    # every boundary safe
+    progress = np.array([0, 5, 0, 0, 0, 64, 127, 1, 77, 0], dtype=np.int32)  # job 1 finished
+    W = np.array([2**31 - 1, 0, 1, 100, 5000, 2**31 - 1, 300, -5], dtype=np.int32)
+    C = np.array([2**31 - 1, 500, 999, 0, 700, 400, 2**31 - 1, 900], dtype=np.int32)
+    wl = types.SimpleNamespace(
+        seg_off=seg_off, dur=dur, mem=mem, safe=safe, progress=progress, W=W, C=C,
+        wait=rng.integers(0, 100, size=len(lens)).astype(np.int32),
+        sla_class=rng.integers(0, 3, size=len(lens)).astype(np.uint8),
+        policy=3, wait_scale=1000, sla_weight=(4, 2, 1), class0_override=1, max_rounds=0,
+        n_gaps=len(W), n_jobs=len(lens))
+    full_tick_check(engine, oracle, wl, policies=[0, 1, 2, 3])
+
+
+def test_empty_batches(engine):
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("tiny", 0, n_gaps=0, n_jobs=4)
+    t = P.DeviceTick(engine, wl)
+    t.prepare(); t.fit(); t.select(P.Params.make(0)); t.resolve(P.Params.make(0))
+    torch.cuda.synchronize()
+    assert t.rounds.cpu().tolist() == [1, 1] and (t.job_gap.cpu().numpy() == -1).all()
+
+
+def test_repeatable(engine):
+    """Three runs of the whole tick give byte-identical outputs (atomics included)."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("small", 9)
+    outs = []
+    for _ in range(3):
+        t = P.DeviceTick(engine, wl)
+        t.prepare(); t.fit(); t.select(P.Params.make(3)); t.resolve(P.Params.make(3))
+        torch.cuda.synchronize()
+        outs.append([x.cpu().numpy().tobytes() for x in
+                     (t.cut, t.bits, t.cand_job, t.cand_score, t.grant_job, t.grant_score, t.job_gap, t.rounds)])
+    assert outs[0] == outs[1] == outs[2]
