@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of one scheduling tick (prepare -> fit -> select -> resolve) on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that
+is already resident in HBM.  Prints ONE JSON line: gap-job fit evaluations per
+second for the whole step, the fit kernel's roofline figures, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
+
+
+def algorithmic_fit_bytes(wl, n_atoms_total):
+    """Bytes the fit step must move: 4 B cut + 1 bit per pair, one 12-byte atom record
+    (running duration, running peak, boundary) per safe cut after the progress point,
+    8 B per gap."""
+    G, J = wl.n_gaps, wl.n_jobs
+    words = (J + 31) // 32
+    return 4 * G * J + 4 * G * words + 12 * n_atoms_total + 8 * G
+
+
+def count_atoms(wl):
+    """Safe boundaries after each job's progress point (the end always counts)."""
+    import numpy as np
+    flags = wl.safe.astype(np.int64).copy()
+    flags[wl.seg_off[1:] - 1] = 1
+    cs = np.concatenate(([0], np.cumsum(flags)))
+    start = wl.seg_off[:-1] + wl.progress
+    return int((cs[wl.seg_off[1:]] - cs[start]).sum())
+
+
+def cpu_baseline(wl, sample_gaps):
+    """The oracle as it stands, whole hot path, on the first `sample_gaps` gaps x all jobs."""
+    import numpy as np
+    import oracle as O
+    O.build()
+    n = min(sample_gaps, wl.n_gaps)
+    W = np.ascontiguousarray(wl.W[:n])
+    C = np.ascontiguousarray(wl.C[:n])
+    par = O.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, wl.max_rounds)
+    t0 = time.perf_counter()
+    pd, pp, _ = O.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    t1 = time.perf_counter()
+    cut, _ = O.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, W, C)
+    t2 = time.perf_counter()
+    O.select(cut, wl.seg_off, pd, pp, par, wl.wait, wl.sla_class)
+    t3 = time.perf_counter()
+    res = O.resolve(cut, wl.seg_off, pd, pp, par, wl.wait, wl.sla_class)
+    t4 = time.perf_counter()
+    total = t4 - t0
+    return {
+        "value": n * wl.n_jobs / total,
+        "unit": "fit evaluations/s",
+        "cores": O.num_threads(),
+        "kind": "oracle",
+        "sample": f"first {n} of {wl.n_gaps} gaps x all {wl.n_jobs} jobs, whole tick "
+                  f"(prepare {t1 - t0:.2f}s, fit {t2 - t1:.2f}s, select {t3 - t2:.2f}s, "
+                  f"resolve {t4 - t3:.2f}s, {res[4]} rounds)",
+        "fit_only_value": n * wl.n_jobs / (t2 - t1),
+        "seconds": total,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="stress",
+                    help="named config (default: stress, the largest single-GPU config)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-sample-gaps", type=int, default=512)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--max-rounds", type=int, default=None,
+                    help="override the config's resolve round cap (0 = until stable)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this path uses no second GPU, run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2509_19086_amd as P
+    from gen import make_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+
+    t_gen = time.perf_counter()
+    wl = make_workload(args.workload, args.seed)
+    if args.max_rounds is not None:
+        wl.max_rounds = args.max_rounds
+    n_atoms = count_atoms(wl)
+    t_gen = time.perf_counter() - t_gen
+
+    eng = P.Engine(0)
+    tick = P.DeviceTick(eng, wl)
+    par = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, wl.max_rounds)
+    eng.sja_enable_timing(True)
+    torch.cuda.synchronize()
+
+    def step(record=None):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        ev[0].record(); tick.prepare()
+        ev[1].record(); tick.fit()
+        ev[2].record(); tick.select(par)
+        ev[3].record(); tick.resolve(par)
+        ev[4].record()
+        if record is not None:
+            ev[4].synchronize()
+            record["prepare"].append(ev[0].elapsed_time(ev[1]))
+            record["fit"].append(ev[1].elapsed_time(ev[2]))
+            record["select"].append(ev[2].elapsed_time(ev[3]))
+            record["resolve"].append(ev[3].elapsed_time(ev[4]))
+            record["fit_kernel"].append(eng.sja_last_fit_kernel_ms())
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rec = {k: [] for k in ("prepare", "fit", "select", "resolve", "fit_kernel")}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    pairs = wl.n_gaps * wl.n_jobs
+    ms_per_step = 1e3 * elapsed / args.steps
+    mean = lambda xs: sum(xs) / len(xs)
+    fit_kernel_ms = mean(rec["fit_kernel"])
+    alg_bytes = algorithmic_fit_bytes(wl, n_atoms)
+    achieved = alg_bytes / (fit_kernel_ms * 1e-3) / 1e9
+    rounds, stable = tick.rounds.cpu().tolist()
+
+    out = {
+        "metric": "gap-job fit evaluations/sec (whole tick: prepare+fit+select+resolve), 1 GPU",
+        "value": pairs / (elapsed / args.steps),
+        "unit": "fit evaluations/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name} seed {wl.seed}: {wl.n_gaps} gaps x {wl.n_jobs} jobs, "
+                               f"{wl.n_segments} segments, policy {wl.policy}, "
+                               f"max_rounds {wl.max_rounds}",
+                   "pairs": pairs, "atoms": n_atoms},
+        "call_ms": {k: mean(v) for k, v in rec.items()},
+        "fit_evals_per_s": pairs / (mean(rec["fit"]) * 1e-3),
+        "fit_kernel_evals_per_s": pairs / (fit_kernel_ms * 1e-3),
+        "resolve": {"rounds": rounds, "stable": stable,
+                    "grants": int((tick.grant_job >= 0).sum().item())},
+        "interest_density": float((tick.cut >= 0).float().mean().item()) if pairs <= 2**29 else None,
+        "roofline": {"kernel": "k_fit", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": alg_bytes, "kernel_ms": fit_kernel_ms},
+        "gen_seconds": t_gen,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_gaps)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -184,6 +184,16 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
                 const uint8_t *sla_class, int32_t *grant_job, int32_t *grant_cut,
                 int64_t *grant_score, int32_t *job_gap, int32_t *rounds_used_and_stable);
 
+/*
+ * Measurement aid for benchmarks (callers that report the pair-evaluation
+ * kernel's own duration rather than the whole call's).  With timing enabled,
+ * sja_fit brackets its pair-evaluation kernel with HIP events on `stream`;
+ * sja_last_fit_kernel_ms waits for that kernel and stores its duration in
+ * *ms_host (host pointer).  SJA_ERR_STATE if no timed sja_fit has run.
+ */
+int sja_enable_timing(sja_ctx *ctx, int on);
+int sja_last_fit_kernel_ms(sja_ctx *ctx, float *ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -70,6 +70,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_select.restype = ctypes.c_int
     lib.sja_resolve.argtypes = [vp, vp, ctypes.POINTER(Params)] + [vp] * 7
     lib.sja_resolve.restype = ctypes.c_int
+    lib.sja_enable_timing.argtypes = [vp, ctypes.c_int]
+    lib.sja_enable_timing.restype = ctypes.c_int
+    lib.sja_last_fit_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.sja_last_fit_kernel_ms.restype = ctypes.c_int
     if path is None:
         _lib = lib
     return lib
@@ -132,6 +136,14 @@ class Engine:
                                          device=f"cuda:{self.device}")
             self._check(self.lib.sja_set_workspace(self.h, ctypes.c_void_p(self.workspace.data_ptr()),
                                                    self.workspace.numel()), self.h)
+
+    def sja_enable_timing(self, on: bool) -> None:
+        self._check(self.lib.sja_enable_timing(self.h, int(on)), self.h)
+
+    def sja_last_fit_kernel_ms(self) -> float:
+        ms = ctypes.c_float()
+        self._check(self.lib.sja_last_fit_kernel_ms(self.h, ctypes.byref(ms)), self.h)
+        return float(ms.value)
 
     # -- the four calls --------------------------------------------------
     def sja_prepare_profiles(self, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe):

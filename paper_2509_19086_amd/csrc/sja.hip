@@ -138,6 +138,8 @@ int sja_create(sja_ctx **out, int device_id)
 int sja_destroy(sja_ctx *ctx)
 {
     if (!ctx) return SJA_ERR_NULL;
+    if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
+    if (ctx->ev_stop) (void)hipEventDestroy(ctx->ev_stop);
     delete ctx;
     return SJA_OK;
 }
@@ -158,6 +160,24 @@ int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes)
     ctx->ws_bytes = bytes;
     ctx->prepared = false;   // private tables lived in the old workspace
     ctx->fitted = false;
+    return SJA_OK;
+}
+
+int sja_enable_timing(sja_ctx *ctx, int on)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    ctx->timing = on != 0;
+    ctx->timed = false;
+    return SJA_OK;
+}
+
+int sja_last_fit_kernel_ms(sja_ctx *ctx, float *ms_host)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!ms_host) return fail(ctx, SJA_ERR_NULL, "ms_host");
+    if (!ctx->timed) return fail(ctx, SJA_ERR_STATE, "no timed sja_fit has run");
+    SJA_HIP(hipEventSynchronize(ctx->ev_stop), "hipEventSynchronize");
+    SJA_HIP(hipEventElapsedTime(ms_host, ctx->ev_start, ctx->ev_stop), "hipEventElapsedTime");
     return SJA_OK;
 }
 
@@ -202,6 +222,7 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
 {
     if (!ctx) return SJA_ERR_NULL;
     ctx->fitted = false;
+    ctx->timed = false;
     if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_fit before sja_prepare_profiles");
     if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
     if (n_gaps > 0 && (!W || !C)) return fail(ctx, SJA_ERR_NULL, "W / C");
@@ -230,12 +251,23 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
             const int n_chunks = (n_gaps + kFitGapChunk - 1) / kFitGapChunk;
             const unsigned grid = unsigned(tiles8) * unsigned(n_chunks);
             const int words = (J + 31) / 32;
+            if (ctx->timing) {
+                if (!ctx->ev_start) {
+                    SJA_HIP(hipEventCreate(&ctx->ev_start), "hipEventCreate");
+                    SJA_HIP(hipEventCreate(&ctx->ev_stop), "hipEventCreate");
+                }
+                SJA_HIP(hipEventRecord(ctx->ev_start, st), "hipEventRecord");
+            }
             hipLaunchKernelGGL(k_fit, dim3(grid), dim3(kFitBlock), 0, st, J, n_gaps, n_chunks, ctx->seg_off,
                                ws_ptr<int32_t>(ctx, L.atom_dur), ws_ptr<int32_t>(ctx, L.atom_peak),
                                ws_ptr<int32_t>(ctx, L.atom_bnd), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int32_t>(ctx, L.gap_order), ws_ptr<int32_t>(ctx, L.gap_w),
                                ws_ptr<int32_t>(ctx, L.gap_c), cut, interest_bits, words);
             SJA_HIP(hipGetLastError(), "k_fit launch");
+            if (ctx->timing) {
+                SJA_HIP(hipEventRecord(ctx->ev_stop, st), "hipEventRecord");
+                ctx->timed = true;
+            }
         }
     }
     ctx->n_gaps = n_gaps;

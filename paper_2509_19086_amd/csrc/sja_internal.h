@@ -86,6 +86,11 @@ struct sja_ctx {
     const int32_t *pre_dur;
     const int32_t *pre_peak;
 
+    // optional timing of the pair-evaluation kernel
+    bool timing;
+    bool timed;
+    hipEvent_t ev_start, ev_stop;
+
     // state left by sja_fit
     bool fitted;
     int32_t n_gaps;
