@@ -1,0 +1,376 @@
+// K2: fit for every (gap, job) pair (Sec. 3.8 admissibility in the envelope
+// form of Sec. 3.9; the longest safe fragment is preferred), plus the small
+// kernels that order the gaps and plan the launch.
+//
+// Over a job's atoms (its safe cuts after the progress point) both the running
+// duration D and the running peak P are non-decreasing, so for a gap (W, C)
+//     cut = boundary of atom  min(#{D <= W}, #{P <= C}) - 1      (or -1).
+// Gaps are sorted by (C, W).  Inside a run of equal C the second count is a
+// per-job constant and the first only grows with the sorted position, so a
+// lane that owns one job walks a merge pointer through that job's atoms while
+// the wave steps through gap positions and stores one coalesced 256-byte piece
+// of a cut row per step.  The kernel is bound by those row stores; everything
+// else is arranged so that the stepping loop issues no global load:
+//   - the atoms a lane may cross next sit in a small circular LDS window that
+//     is topped up from global memory once per period of steps;
+//   - where a chunk of gap positions starts inside a job's atom list comes from
+//     a table built by k_fit_starts (one sequential walk per job and capacity
+//     class) instead of a per-chunk binary search;
+//   - gap windows and row offsets arrive through wide scalar loads.
+#pragma once
+
+#include "sja_internal.h"
+
+namespace sja {
+
+// --------------------------------------------------------------------------
+// Gap ordering: rank sort by (C, W, index); exact and deterministic.
+// --------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long gap_key(int w, int c)
+{
+    return (static_cast<unsigned long long>(static_cast<uint32_t>(c) ^ 0x80000000u) << 32) |
+           (static_cast<uint32_t>(w) ^ 0x80000000u);
+}
+
+__global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+constexpr int kRankSpan = 2048;  // gaps compared against per block in k_gap_rank
+
+__global__ __launch_bounds__(256) void k_gap_rank(int n_gaps, const int32_t *__restrict__ W,
+                                                  const int32_t *__restrict__ C,
+                                                  int32_t *__restrict__ rank)
+{
+    __shared__ unsigned long long tile[256];
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    const unsigned long long mine = g < n_gaps ? gap_key(W[g], C[g]) : 0ull;
+    const int h_begin = blockIdx.y * kRankSpan;
+    const int h_end = min(n_gaps, h_begin + kRankSpan);
+    int r = 0;
+    for (int h0 = h_begin; h0 < h_end; h0 += 256) {
+        const int h = h0 + threadIdx.x;
+        __syncthreads();
+        tile[threadIdx.x] = h < h_end ? gap_key(W[h], C[h]) : ~0ull;
+        __syncthreads();
+        const int n = min(256, h_end - h0);
+        for (int t = 0; t < n; ++t) {
+            const unsigned long long other = tile[t];
+            r += (other < mine) || (other == mine && (h0 + t) < g);
+        }
+    }
+    if (g < n_gaps && r) atomicAdd(&rank[g], r);
+}
+
+// Sorted copies of the gaps plus, per sorted position, the element offsets of
+// the gap's cut row and interest row.
+__global__ void k_gap_scatter(int n_gaps, int n_jobs, int words, const int32_t *__restrict__ W,
+                              const int32_t *__restrict__ C, const int32_t *__restrict__ rank,
+                              int32_t *__restrict__ order, int32_t *__restrict__ ws,
+                              int32_t *__restrict__ cs, int64_t *__restrict__ row,
+                              int64_t *__restrict__ brow)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_gaps) return;
+    const int r = rank[g];
+    order[r] = g;
+    ws[r] = W[g];
+    cs[r] = C[g];
+    row[r] = int64_t(g) * n_jobs;
+    brow[r] = int64_t(g) * words;
+}
+
+// run_end[s] = first sorted position after s whose capacity differs.
+__global__ void k_gap_run_end(int n_gaps, const int32_t *__restrict__ cs, int32_t *__restrict__ run_end)
+{
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n_gaps) return;
+    const int c = cs[s];
+    int lo = s + 1, hi = n_gaps;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (cs[mid] <= c) lo = mid + 1; else hi = mid;
+    }
+    run_end[s] = lo;
+}
+
+// One block.  Finds the capacity classes (runs of equal C) and cuts the sorted
+// positions into chunks of at most gc.  With at most kMaxClasses classes the
+// chunks never straddle a class and the table-driven path is used; otherwise
+// chunks are plain slices and the fit kernel searches for itself.
+__global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int chunk_bound,
+                                                   const int32_t *__restrict__ cs, int32_t *plan,
+                                                   int32_t *class_begin, int32_t *class_chunk0,
+                                                   int32_t *chunk_begin, int32_t *chunk_end,
+                                                   int32_t *chunk_class)
+{
+    __shared__ int s_cnt[1024];
+    __shared__ int s_classes, s_chunks, s_tabled;
+    const int t = threadIdx.x;
+    const int span = (n_gaps + 1023) / 1024;
+    const int lo = min(n_gaps, t * span), hi = min(n_gaps, lo + span);
+    int cnt = 0;
+    for (int s = lo; s < hi; ++s) cnt += (s == 0) || (cs[s] != cs[s - 1]);
+    s_cnt[t] = cnt;
+    __syncthreads();
+    if (t == 0) {
+        int acc = 0;
+        for (int i = 0; i < 1024; ++i) { const int c = s_cnt[i]; s_cnt[i] = acc; acc += c; }
+        s_classes = acc;
+        s_tabled = acc <= kMaxClasses;
+    }
+    __syncthreads();
+    const int n_classes = s_classes;
+    const bool tabled = s_tabled != 0;
+    if (tabled) {
+        int k = s_cnt[t];
+        for (int s = lo; s < hi; ++s)
+            if ((s == 0) || (cs[s] != cs[s - 1])) class_begin[k++] = s;
+        if (t == 0) class_begin[n_classes] = n_gaps;
+    }
+    __syncthreads();
+    if (t == 0) {
+        int q = 0;
+        if (tabled) {
+            for (int c = 0; c < n_classes; ++c) {
+                class_chunk0[c] = q;
+                q += (class_begin[c + 1] - class_begin[c] + gc - 1) / gc;
+            }
+            class_chunk0[n_classes] = q;
+        } else {
+            q = (n_gaps + gc - 1) / gc;
+        }
+        s_chunks = min(q, chunk_bound);
+        plan[kPlanClasses] = n_classes;
+        plan[kPlanChunks] = s_chunks;
+        plan[kPlanTabled] = tabled ? 1 : 0;
+    }
+    __syncthreads();
+    const int n_chunks = s_chunks;
+    for (int q = t; q < n_chunks; q += 1024) {
+        if (tabled) {
+            int c = 0;
+            while (c + 1 < n_classes && class_chunk0[c + 1] <= q) ++c;
+            const int b = class_begin[c] + (q - class_chunk0[c]) * gc;
+            chunk_begin[q] = b;
+            chunk_end[q] = min(class_begin[c + 1], b + gc);
+            chunk_class[q] = c;
+        } else {
+            chunk_begin[q] = q * gc;
+            chunk_end[q] = min(n_gaps, q * gc + gc);
+            chunk_class[q] = -1;
+        }
+    }
+}
+
+// --------------------------------------------------------------------------
+// Start tables (table-driven path).  Thread (job j, class c) walks the job's
+// atoms once, in order, against the class's chunk thresholds (the window of
+// each chunk's first gap, ascending):
+//   start[q][j] = #atoms usable by the first gap of chunk q
+//   ncap[c][j]  = #atoms any gap of class c can reach (peak <= C_c and
+//                 duration <= the class's largest window)
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fit_starts(
+    int n_jobs, int gc, const int32_t *__restrict__ plan, const int32_t *__restrict__ class_begin,
+    const int32_t *__restrict__ class_chunk0, const int32_t *__restrict__ gap_w,
+    const int32_t *__restrict__ gap_c, const int64_t *__restrict__ seg_off,
+    const int2 *__restrict__ atom_dp, const int32_t *__restrict__ n_atoms,
+    int32_t *__restrict__ start_tab, int32_t *__restrict__ ncap_tab)
+{
+    const int c = blockIdx.y;
+    if (!plan[kPlanTabled] || c >= plan[kPlanClasses]) return;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_jobs) return;
+    const int pos_b = class_begin[c], pos_e = class_begin[c + 1];
+    const int cap = gap_c[pos_b];
+    const int w_max = gap_w[pos_e - 1];
+    const int q0 = class_chunk0[c], qe = class_chunk0[c + 1];
+    const int2 *dp = atom_dp + seg_off[j];
+    const int n = n_atoms[j];
+
+    int q = q0;
+    int w_q = gap_w[pos_b];
+    int reach = n;
+    bool done = false;
+    for (int b0 = 0; b0 < n && !done; b0 += 4) {
+        int2 v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = dp[b0 + t];      // the tables carry 8 entries of padding
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int idx = b0 + t;
+            if (done) continue;
+            if (idx >= n || v[t].y > cap || v[t].x > w_max) {
+                done = true;
+                reach = idx;
+            } else {
+                while (q < qe && v[t].x > w_q) {
+                    start_tab[int64_t(q) * n_jobs + j] = idx;
+                    ++q;
+                    if (q < qe) w_q = gap_w[pos_b + (q - q0) * gc];
+                }
+            }
+        }
+    }
+    for (; q < qe; ++q) start_tab[int64_t(q) * n_jobs + j] = reach;
+    ncap_tab[int64_t(c) * n_jobs + j] = reach;
+}
+
+// --------------------------------------------------------------------------
+// The pair-evaluation kernel.
+// --------------------------------------------------------------------------
+__device__ __forceinline__ int upper_bound_peak(const int2 *__restrict__ a, int n, int v)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid].y <= v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ int upper_bound_dur(const int2 *__restrict__ a, int n, int v)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid].x <= v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// s_waitcnt vmcnt(0): every global load and store of this wave has completed.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+
+template <int BLOCK, int CAP, int PERIOD>
+__global__ __launch_bounds__(BLOCK) void k_fit_main(
+    int n_jobs, int chunk_bound, const int64_t *__restrict__ seg_off,
+    const int2 *__restrict__ atom_dp, const int2 *__restrict__ atom_db,
+    const int32_t *__restrict__ n_atoms, const int32_t *__restrict__ plan,
+    const int32_t *__restrict__ chunk_begin, const int32_t *__restrict__ chunk_end,
+    const int32_t *__restrict__ chunk_class, const int32_t *__restrict__ start_tab,
+    const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ gap_w,
+    const int32_t *__restrict__ gap_c, const int64_t *__restrict__ gap_row,
+    const int64_t *__restrict__ gap_brow, const int32_t *__restrict__ gap_run_end,
+    int32_t *__restrict__ cut, uint32_t *__restrict__ bits, int words)
+{
+    static_assert((CAP & (CAP - 1)) == 0 && PERIOD % 4 == 0 && BLOCK % kWave == 0, "tile shape");
+    constexpr int WAVES = BLOCK / kWave;
+    __shared__ int2 win[CAP][BLOCK];
+    __shared__ unsigned long long bal[kFitMaxChunk][WAVES];
+
+    // Blocks of one job tile sit on one XCD (block ids are dealt round-robin
+    // over the 8 XCDs): its atoms and tables stay in that XCD's L2.
+    const int xcd = blockIdx.x & 7;
+    const int k = blockIdx.x >> 3;
+    const int job_tile = (k / chunk_bound) * 8 + xcd;
+    const int chunk = k % chunk_bound;
+    if (job_tile * BLOCK >= n_jobs || chunk >= plan[kPlanChunks]) return;
+    const bool tabled = plan[kPlanTabled] != 0;
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int j_raw = job_tile * BLOCK + tid;
+    const bool live = j_raw < n_jobs;
+    const int j = live ? j_raw : n_jobs - 1;   // spare lanes shadow the last job: same value, same address
+    const int64_t base = seg_off[j];
+    const int n = n_atoms[j];
+    const int2 *dp = atom_dp + base;
+    const int2 *db = atom_db + base;
+    const int s_begin = chunk_begin[chunk], s_end = chunk_end[chunk];
+
+    int n_cap = 0;   // atoms the current capacity class can reach
+    int a = 0;       // atoms whose running duration fits the current window
+    int hi = 0;      // atoms [a, hi) are staged in the LDS window
+    int cur = -1;    // boundary of atom a-1, or -1
+    int nd = 0, nb = 0;   // atom a (valid while a < hi)
+    int c_cur = 0;
+
+    auto init = [&](int s) {
+        c_cur = gap_c[s];
+        if (tabled) {
+            a = start_tab[int64_t(chunk) * n_jobs + j];
+            n_cap = ncap_tab[int64_t(chunk_class[chunk]) * n_jobs + j];
+        } else {
+            n_cap = upper_bound_peak(dp, n, c_cur);
+            a = upper_bound_dur(dp, n_cap, gap_w[s]);
+        }
+        cur = a > 0 ? db[a - 1].y : -1;
+        hi = a;
+    };
+    auto topup = [&]() {
+        const int want = min(a + CAP, n_cap);
+        int2 v[CAP];
+#pragma unroll
+        for (int t = 0; t < CAP; ++t)
+            if (hi + t < want) v[t] = db[hi + t];
+#pragma unroll
+        for (int t = 0; t < CAP; ++t)
+            if (hi + t < want) win[(hi + t) & (CAP - 1)][tid] = v[t];
+        hi = max(hi, want);
+        if (a < hi) { const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y; }
+    };
+    auto advance = [&](int w) {
+        while (a < hi && nd <= w) {
+            cur = nb;
+            ++a;
+            if (a < hi) {
+                const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y;
+            } else if (a < n_cap) {
+                // the window ran dry inside a period: refill at once (rare)
+                const int want = min(a + CAP, n_cap);
+                for (int idx = hi; idx < want; ++idx) win[idx & (CAP - 1)][tid] = db[idx];
+                hi = want;
+                const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y;
+                wait_vmem();
+            }
+        }
+    };
+    auto emit = [&](int s, int64_t row) {
+        (cut + row)[j] = cur;
+        if (bits) bal[s - s_begin][wave] = __ballot(live && cur >= 0);
+    };
+
+    for (int s0 = s_begin; s0 < s_end; s0 += PERIOD) {
+        const int s1 = min(s_end, s0 + PERIOD);
+        if (s0 == s_begin || gap_c[s0] != c_cur) init(s0);
+        topup();
+        wait_vmem();   // below, until the next period, no global load is pending
+        if (s1 - s0 == PERIOD && gap_run_end[s0] >= s1) {
+#pragma unroll
+            for (int u4 = 0; u4 < PERIOD; u4 += 4) {
+                const int wv[4] = {gap_w[s0 + u4], gap_w[s0 + u4 + 1], gap_w[s0 + u4 + 2], gap_w[s0 + u4 + 3]};
+                const int64_t rv[4] = {gap_row[s0 + u4], gap_row[s0 + u4 + 1], gap_row[s0 + u4 + 2],
+                                       gap_row[s0 + u4 + 3]};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (__any(a < hi && nd <= wv[u])) advance(wv[u]);
+                    emit(s0 + u4 + u, rv[u]);
+                }
+            }
+        } else {
+            for (int s = s0; s < s1; ++s) {
+                if (gap_c[s] != c_cur) { init(s); topup(); wait_vmem(); }
+                advance(gap_w[s]);
+                emit(s, gap_row[s]);
+            }
+        }
+    }
+
+    if (bits) {
+        // one interest row piece per gap position: WAVES * 8 contiguous bytes
+        __syncthreads();
+        constexpr int WPR = 2 * WAVES;
+        const uint32_t *bal32 = reinterpret_cast<const uint32_t *>(&bal[0][0]);
+        const int word0 = (job_tile * BLOCK) >> 5;
+        const int total = (s_end - s_begin) * WPR;
+        for (int i = tid; i < total; i += BLOCK) {
+            const int slot = i / WPR, wi = i % WPR;
+            if (word0 + wi < words) bits[gap_brow[s_begin + slot] + word0 + wi] = bal32[i];
+        }
+    }
+}
+
+}  // namespace sja

@@ -204,8 +204,8 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
         const int jobs_per_block = 256 / kWave;
         hipLaunchKernelGGL(k_prepare, dim3((n_jobs + jobs_per_block - 1) / jobs_per_block), dim3(256), 0, st,
                            n_jobs, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe,
-                           ws_ptr<int32_t>(ctx, L.atom_dur), ws_ptr<int32_t>(ctx, L.atom_peak),
-                           ws_ptr<int32_t>(ctx, L.atom_bnd), ws_ptr<int32_t>(ctx, L.n_atoms));
+                           ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),
+                           ws_ptr<int32_t>(ctx, L.n_atoms));
         SJA_HIP(hipGetLastError(), "k_prepare launch");
     }
     ctx->n_jobs = n_jobs;
@@ -235,22 +235,39 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
     SJA_HIP(guard.err, "hipSetDevice");
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_gaps > 0) {
+        const int words = (J + 31) / 32;
+        const int gc = fit_chunk_len(n_gaps, J);
+        const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
+        const dim3 per_gap((n_gaps + 255) / 256), b256(256);
         int32_t *rank = ws_ptr<int32_t>(ctx, L.gap_rank);
-        hipLaunchKernelGGL(k_fill_i32, dim3((n_gaps + 255) / 256), dim3(256), 0, st, rank, int64_t(n_gaps), 0);
+        int32_t *gw = ws_ptr<int32_t>(ctx, L.gap_w), *gcap = ws_ptr<int32_t>(ctx, L.gap_c);
+        int32_t *plan = ws_ptr<int32_t>(ctx, L.plan);
+        hipLaunchKernelGGL(k_fill_i32, per_gap, b256, 0, st, rank, int64_t(n_gaps), 0);
         SJA_HIP(hipGetLastError(), "k_fill_i32 launch");
-        hipLaunchKernelGGL(k_gap_rank, dim3((n_gaps + 255) / 256, (n_gaps + kRankSpan - 1) / kRankSpan), dim3(256), 0, st,
+        hipLaunchKernelGGL(k_gap_rank, dim3((n_gaps + 255) / 256, (n_gaps + kRankSpan - 1) / kRankSpan), b256, 0, st,
                            n_gaps, W, C, rank);
         SJA_HIP(hipGetLastError(), "k_gap_rank launch");
-        hipLaunchKernelGGL(k_gap_scatter, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, W, C, rank,
-                           ws_ptr<int32_t>(ctx, L.gap_order), ws_ptr<int32_t>(ctx, L.gap_w),
-                           ws_ptr<int32_t>(ctx, L.gap_c));
+        hipLaunchKernelGGL(k_gap_scatter, per_gap, b256, 0, st, n_gaps, J, words, W, C, rank,
+                           ws_ptr<int32_t>(ctx, L.gap_order), gw, gcap,
+                           ws_ptr<int64_t>(ctx, L.gap_row), ws_ptr<int64_t>(ctx, L.gap_brow));
         SJA_HIP(hipGetLastError(), "k_gap_scatter launch");
         if (J > 0) {
+            hipLaunchKernelGGL(k_gap_run_end, per_gap, b256, 0, st, n_gaps, gcap,
+                               ws_ptr<int32_t>(ctx, L.gap_run_end));
+            SJA_HIP(hipGetLastError(), "k_gap_run_end launch");
+            hipLaunchKernelGGL(k_gap_plan, dim3(1), dim3(1024), 0, st, n_gaps, gc, chunk_bound, gcap, plan,
+                               ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0),
+                               ws_ptr<int32_t>(ctx, L.chunk_begin), ws_ptr<int32_t>(ctx, L.chunk_end),
+                               ws_ptr<int32_t>(ctx, L.chunk_class));
+            SJA_HIP(hipGetLastError(), "k_gap_plan launch");
+            hipLaunchKernelGGL(k_fit_starts, dim3((J + 255) / 256, kMaxClasses), b256, 0, st, J, gc, plan,
+                               ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0), gw, gcap,
+                               ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int32_t>(ctx, L.start_tab), ws_ptr<int32_t>(ctx, L.ncap_tab));
+            SJA_HIP(hipGetLastError(), "k_fit_starts launch");
             const int job_tiles = (J + kFitBlock - 1) / kFitBlock;
             const int tiles8 = (job_tiles + 7) / 8 * 8;
-            const int n_chunks = (n_gaps + kFitGapChunk - 1) / kFitGapChunk;
-            const unsigned grid = unsigned(tiles8) * unsigned(n_chunks);
-            const int words = (J + 31) / 32;
+            const unsigned grid = unsigned(tiles8) * unsigned(chunk_bound);
             if (ctx->timing) {
                 if (!ctx->ev_start) {
                     SJA_HIP(hipEventCreate(&ctx->ev_start), "hipEventCreate");
@@ -258,12 +275,15 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
                 }
                 SJA_HIP(hipEventRecord(ctx->ev_start, st), "hipEventRecord");
             }
-            hipLaunchKernelGGL(k_fit, dim3(grid), dim3(kFitBlock), 0, st, J, n_gaps, n_chunks, ctx->seg_off,
-                               ws_ptr<int32_t>(ctx, L.atom_dur), ws_ptr<int32_t>(ctx, L.atom_peak),
-                               ws_ptr<int32_t>(ctx, L.atom_bnd), ws_ptr<int32_t>(ctx, L.n_atoms),
-                               ws_ptr<int32_t>(ctx, L.gap_order), ws_ptr<int32_t>(ctx, L.gap_w),
-                               ws_ptr<int32_t>(ctx, L.gap_c), cut, interest_bits, words);
-            SJA_HIP(hipGetLastError(), "k_fit launch");
+            hipLaunchKernelGGL((k_fit_main<kFitBlock, kFitWindow, kFitPeriod>), dim3(grid), dim3(kFitBlock), 0, st,
+                               J, chunk_bound, ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp),
+                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms), plan,
+                               ws_ptr<int32_t>(ctx, L.chunk_begin), ws_ptr<int32_t>(ctx, L.chunk_end),
+                               ws_ptr<int32_t>(ctx, L.chunk_class), ws_ptr<int32_t>(ctx, L.start_tab),
+                               ws_ptr<int32_t>(ctx, L.ncap_tab), gw, gcap, ws_ptr<int64_t>(ctx, L.gap_row),
+                               ws_ptr<int64_t>(ctx, L.gap_brow), ws_ptr<int32_t>(ctx, L.gap_run_end), cut,
+                               interest_bits, words);
+            SJA_HIP(hipGetLastError(), "k_fit_main launch");
             if (ctx->timing) {
                 SJA_HIP(hipEventRecord(ctx->ev_stop, st), "hipEventRecord");
                 ctx->timed = true;

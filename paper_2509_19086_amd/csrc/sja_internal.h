@@ -14,8 +14,11 @@ namespace sja {
 constexpr int kWave = 64;
 
 // ---- tiling constants shared by host launch code and kernels -------------
-constexpr int kFitBlock = 256;        // threads per fit block, one job per thread
-constexpr int kFitGapChunk = 256;     // sorted gap positions walked by one fit block
+constexpr int kFitBlock = 512;        // threads per fit block, one job per thread
+constexpr int kFitMaxChunk = 256;     // most sorted gap positions one fit block walks
+constexpr int kFitWindow = 8;         // atoms per job staged ahead in LDS (power of two)
+constexpr int kFitPeriod = 16;        // steps between window top-ups (multiple of 4)
+constexpr int kMaxClasses = 64;       // distinct capacities served by the table-driven path
 constexpr int kSelBlock = 256;        // threads per select block, one job per thread
 constexpr int kSelGapChunk = 128;     // sorted gap positions walked by one select block
 
@@ -28,12 +31,21 @@ struct SelPartial {
     int64_t pad;
 };
 
+// Gap plan header written by k_gap_plan (device memory, int32 each).
+enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanWords = 8 };
+
 // Byte offsets of the private tables inside the caller's workspace.
 struct Layout {
-    size_t atom_dur, atom_peak, atom_bnd;  // [S] int32 each: per-job compacted safe cuts
+    size_t atom_dp, atom_db;               // [S+8] int2 each: (dur, peak) and (dur, boundary)
     size_t n_atoms;                        // [J] int32
     size_t gap_rank, gap_order;            // [G] int32
-    size_t gap_w, gap_c;                   // [G] int32, in sorted order
+    size_t gap_w, gap_c, gap_run_end;      // [G+16] int32, in sorted order
+    size_t gap_row, gap_brow;              // [G+16] int64: element offsets of a gap's rows
+    size_t plan;                           // [kPlanWords] int32 header
+    size_t class_begin, class_chunk0;      // [kMaxClasses+1] int32
+    size_t chunk_begin, chunk_end, chunk_class;  // [chunk_bound] int32
+    size_t start_tab;                      // [chunk_bound * J] int32
+    size_t ncap_tab;                       // [kMaxClasses * J] int32
     size_t sel_part;                       // [ceil(J/kSelBlock) * G] SelPartial
     size_t res_cand_job, res_cand_cut;     // [G] int32
     size_t res_cand_score;                 // [G] int64
@@ -45,19 +57,46 @@ struct Layout {
 
 inline size_t align_up(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Sorted gap positions per fit block: large enough to amortise a block's
+// set-up, small enough that a small batch still spreads over the chip.
+inline int fit_chunk_len(int64_t G, int64_t J)
+{
+    const int64_t tiles = (J + kFitBlock - 1) / kFitBlock;
+    int gc = kFitMaxChunk;
+    while (gc > 32 && tiles * ((G + gc - 1) / gc) < 2048) gc >>= 1;
+    return gc;
+}
+
+inline int64_t fit_chunk_bound(int64_t G, int64_t J)
+{
+    const int gc = fit_chunk_len(G, J);
+    return (G + gc - 1) / gc + kMaxClasses;
+}
+
 inline Layout make_layout(int64_t G, int64_t J, int64_t S)
 {
     Layout L;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    L.atom_dur = take(size_t(S) * 4);
-    L.atom_peak = take(size_t(S) * 4);
-    L.atom_bnd = take(size_t(S) * 4);
+    L.atom_dp = take(size_t(S + 8) * 8);
+    L.atom_db = take(size_t(S + 8) * 8);
     L.n_atoms = take(size_t(J) * 4);
     L.gap_rank = take(size_t(G) * 4);
     L.gap_order = take(size_t(G) * 4);
-    L.gap_w = take(size_t(G) * 4);
-    L.gap_c = take(size_t(G) * 4);
+    L.gap_w = take(size_t(G + 16) * 4);
+    L.gap_c = take(size_t(G + 16) * 4);
+    L.gap_run_end = take(size_t(G + 16) * 4);
+    L.gap_row = take(size_t(G + 16) * 8);
+    L.gap_brow = take(size_t(G + 16) * 8);
+    L.plan = take(kPlanWords * 4);
+    L.class_begin = take((kMaxClasses + 1) * 4);
+    L.class_chunk0 = take((kMaxClasses + 1) * 4);
+    const size_t cb = size_t(fit_chunk_bound(G, J));
+    L.chunk_begin = take(cb * 4);
+    L.chunk_end = take(cb * 4);
+    L.chunk_class = take(cb * 4);
+    L.start_tab = take(cb * size_t(J) * 4);
+    L.ncap_tab = take(size_t(kMaxClasses) * size_t(J) * 4);
     size_t job_tiles = size_t((J + kSelBlock - 1) / kSelBlock);
     L.sel_part = take(job_tiles * size_t(G) * sizeof(SelPartial));
     L.res_cand_job = take(size_t(G) * 4);

@@ -37,16 +37,16 @@ __device__ __forceinline__ void wave_scan_add_max_max(int &s, int &m, int &l, in
 // envelope on demand from the job's current state).  One wave per job walks
 // the remaining segments 64 at a time with coalesced SoA loads and a carry.
 // Besides the caller-visible prefixes it compacts the job's safe boundaries
-// ("atoms": running duration, running peak, boundary index at each safe cut
-// after the progress point) into the workspace at the job's segment base.
+// ("atoms": running duration, running peak and boundary index at each safe
+// cut after the progress point) into the workspace at the job's segment base,
+// as (duration, peak) and (duration, boundary) pairs.
 // --------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_prepare(
     int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
-    int32_t *__restrict__ atom_dur, int32_t *__restrict__ atom_peak,
-    int32_t *__restrict__ atom_bnd, int32_t *__restrict__ n_atoms)
+    int2 *__restrict__ atom_dp, int2 *__restrict__ atom_db, int32_t *__restrict__ n_atoms)
 {
     const int lane = lane_id();
     const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
@@ -80,9 +80,8 @@ __global__ __launch_bounds__(256) void k_prepare(
         const unsigned long long mask = __ballot(flag);
         if (flag) {
             const int idx = count + __popcll(mask & lanes_below(lane));
-            atom_dur[base + idx] = s;
-            atom_peak[base + idx] = m;
-            atom_bnd[base + idx] = k + 1;
+            atom_dp[base + idx] = make_int2(s, m);
+            atom_db[base + idx] = make_int2(s, k + 1);
         }
         count += __popcll(mask);
         carry_sum = __shfl(s, kWave - 1, kWave);
@@ -92,148 +91,11 @@ __global__ __launch_bounds__(256) void k_prepare(
     if (lane == 0) n_atoms[j] = count;
 }
 
-// --------------------------------------------------------------------------
-// Gap ordering.  Gaps are sorted by (C, W, index) so that a run of sorted
-// positions shares one capacity and has non-decreasing windows.  Rank sort:
-// rank[g] = number of gaps that order before g; exact, deterministic.
-// --------------------------------------------------------------------------
-__device__ __forceinline__ unsigned long long gap_key(int w, int c)
-{
-    return (static_cast<unsigned long long>(static_cast<uint32_t>(c) ^ 0x80000000u) << 32) |
-           (static_cast<uint32_t>(w) ^ 0x80000000u);
-}
+}  // namespace sja
 
-__global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
-{
-    int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
+#include "k_fit.h"
 
-constexpr int kRankSpan = 2048;  // gaps compared against per block in k_gap_rank
-
-__global__ __launch_bounds__(256) void k_gap_rank(int n_gaps, const int32_t *__restrict__ W,
-                                                  const int32_t *__restrict__ C,
-                                                  int32_t *__restrict__ rank)
-{
-    __shared__ unsigned long long tile[256];
-    const int g = blockIdx.x * 256 + threadIdx.x;
-    const unsigned long long mine = g < n_gaps ? gap_key(W[g], C[g]) : 0ull;
-    const int h_begin = blockIdx.y * kRankSpan;
-    const int h_end = min(n_gaps, h_begin + kRankSpan);
-    int r = 0;
-    for (int h0 = h_begin; h0 < h_end; h0 += 256) {
-        const int h = h0 + threadIdx.x;
-        __syncthreads();
-        tile[threadIdx.x] = h < h_end ? gap_key(W[h], C[h]) : ~0ull;
-        __syncthreads();
-        const int n = min(256, h_end - h0);
-        for (int t = 0; t < n; ++t) {
-            const unsigned long long other = tile[t];
-            r += (other < mine) || (other == mine && (h0 + t) < g);
-        }
-    }
-    if (g < n_gaps && r) atomicAdd(&rank[g], r);
-}
-
-__global__ void k_gap_scatter(int n_gaps, const int32_t *__restrict__ W,
-                              const int32_t *__restrict__ C, const int32_t *__restrict__ rank,
-                              int32_t *__restrict__ order, int32_t *__restrict__ ws,
-                              int32_t *__restrict__ cs)
-{
-    const int g = blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= n_gaps) return;
-    const int r = rank[g];
-    order[r] = g;
-    ws[r] = W[g];
-    cs[r] = C[g];
-}
-
-// --------------------------------------------------------------------------
-// K2  fit for every (gap, job) pair (Sec. 3.8 admissibility in the envelope
-// form of Sec. 3.9; the longest safe fragment is preferred).
-//
-// Over a job's atoms both the running duration and the running peak are
-// non-decreasing, so the answer for gap (W, C) is atom min(#{D <= W}, #{P <= C}) - 1.
-// Lanes run along jobs (coalesced 256-byte row stores); each block walks a
-// chunk of gap positions sorted by (C, W).  Within a run of equal C the count
-// #{P <= C} is fixed and #{D <= W} only grows, so each lane advances a merge
-// pointer through its job's atoms instead of searching; a binary search is
-// only needed at the start of a chunk and where C changes.
-// --------------------------------------------------------------------------
-__device__ __forceinline__ int upper_bound_i32(const int32_t *__restrict__ a, int n, int v)
-{
-    int lo = 0, hi = n;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (a[mid] <= v) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
-__global__ __launch_bounds__(kFitBlock) void k_fit(
-    int n_jobs, int n_gaps, int n_chunks, const int64_t *__restrict__ seg_off,
-    const int32_t *__restrict__ atom_dur, const int32_t *__restrict__ atom_peak,
-    const int32_t *__restrict__ atom_bnd, const int32_t *__restrict__ n_atoms,
-    const int32_t *__restrict__ gap_order, const int32_t *__restrict__ gap_w,
-    const int32_t *__restrict__ gap_c, int32_t *__restrict__ cut,
-    uint32_t *__restrict__ bits, int words)
-{
-    // Blocks that share a job tile sit on one XCD (hardware deals consecutive
-    // block ids round-robin over the 8 XCDs), so the tile's atoms stay in that
-    // XCD's L2 while the gap chunks stream past.
-    const int xcd = blockIdx.x & 7;
-    const int k = blockIdx.x >> 3;
-    const int job_tile = (k / n_chunks) * 8 + xcd;
-    const int chunk = k % n_chunks;
-    const int j = job_tile * kFitBlock + threadIdx.x;
-    if (job_tile * kFitBlock >= n_jobs) return;
-    const bool live = j < n_jobs;
-
-    int64_t base = 0;
-    int n = 0;
-    if (live) {
-        base = seg_off[j];
-        n = n_atoms[j];
-    }
-    const int32_t *aD = atom_dur + base;
-    const int32_t *aP = atom_peak + base;
-    const int32_t *aB = atom_bnd + base;
-
-    const int s_begin = chunk * kFitGapChunk;
-    const int s_end = min(n_gaps, s_begin + kFitGapChunk);
-    const int lane = lane_id();
-    const int word0 = (job_tile * kFitBlock + (threadIdx.x & ~63)) >> 5;
-
-    int n_cap = 0;       // atoms whose running peak fits the current capacity
-    int a = 0;           // atoms whose running duration also fits the current window
-    int cur = -1;        // boundary of atom a-1, or -1
-    int next_d = 0;      // running duration of atom a (valid while a < n_cap)
-    int c_prev = 0;
-    for (int s = s_begin; s < s_end; ++s) {
-        const int w = gap_w[s];
-        const int c = gap_c[s];
-        const int g = gap_order[s];
-        if (s == s_begin || c != c_prev) {
-            c_prev = c;
-            n_cap = (w < 0) ? 0 : upper_bound_i32(aP, n, c);
-            a = upper_bound_i32(aD, n_cap, w);
-            cur = a > 0 ? aB[a - 1] : -1;
-            next_d = a < n_cap ? aD[a] : 0;
-        } else {
-            while (a < n_cap && next_d <= w) {
-                cur = aB[a];
-                ++a;
-                next_d = a < n_cap ? aD[a] : 0;
-            }
-        }
-        if (live) cut[int64_t(g) * n_jobs + j] = cur;
-        if (bits) {
-            const unsigned long long m = __ballot(live && cur >= 0);
-            if (lane == 0 && word0 < words) bits[int64_t(g) * words + word0] = uint32_t(m);
-            if (lane == 32 && word0 + 1 < words) bits[int64_t(g) * words + word0 + 1] = uint32_t(m >> 32);
-        }
-    }
-}
+namespace sja {
 
 // --------------------------------------------------------------------------
 // K3  policy arg-max per gap (Sec. 3.5 phase 3).  Lanes run along jobs and

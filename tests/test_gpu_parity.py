@@ -90,6 +90,18 @@ def test_ragged_shapes(engine, oracle, name, G, J):
     full_tick_check(engine, oracle, wl, policies=[wl.policy, 3])
 
 
+@pytest.mark.parametrize("n_classes", [1, 63, 64, 65, 700])
+def test_many_capacity_classes(engine, oracle, n_classes):
+    """Few distinct capacities take the table-driven fit path, many the searching one."""
+    wl = make_workload("medium", 11, n_gaps=700, n_jobs=900)
+    rng = np.random.default_rng(n_classes)
+    caps = np.sort(rng.choice(np.arange(300, 90000), size=n_classes, replace=False)).astype(np.int32)
+    wl.C = np.ascontiguousarray(caps[rng.integers(0, n_classes, size=wl.n_gaps)])
+    if n_classes == 700:
+        wl.C = np.ascontiguousarray(rng.permutation(caps))          # every gap its own capacity
+    full_tick_check(engine, oracle, wl, policies=[2], check_resolve=False)
+
+
 def test_round_cap(engine, oracle):
     wl = make_workload("small", 3)
     for cap in (1, 2, 8):
