@@ -1,0 +1,99 @@
+"""GPU parity at the full sizes of the two largest configs, in the launch
+configuration bench.py times.  The oracle cannot produce 2^28..2^31 pairs in a
+test's time, so outputs are compared on sampled pairs and on whole sampled gap
+rows that the oracle computes one by one, and the grant invariants (which hold
+at any size) are checked with the oracle evaluating every granted pair."""
+import numpy as np
+import pytest
+
+from gen import make_workload
+
+pytestmark = [pytest.mark.gpu, pytest.mark.slow]
+
+
+def _check_full_size(oracle, name, n_pairs, n_rows, max_rounds):
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload(name, 0)
+    wl.max_rounds = max_rounds
+    G, J = wl.n_gaps, wl.n_jobs
+    eng = P.Engine(0)
+    t = P.DeviceTick(eng, wl)
+    par = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, max_rounds)
+    opar = oracle.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, max_rounds)
+    t.prepare(); t.fit(); t.select(par)
+    torch.cuda.synchronize()
+
+    # prepare: whole arrays (cheap on the CPU)
+    pd, pp, ps = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    np.testing.assert_array_equal(t.pre_dur.cpu().numpy().astype(np.int64), pd)
+    np.testing.assert_array_equal(t.pre_peak.cpu().numpy().astype(np.int64), pp)
+    np.testing.assert_array_equal(t.prev_safe.cpu().numpy(), ps)
+
+    # fit: sampled pairs anywhere in the matrix
+    rng = np.random.default_rng(42)
+    gi = rng.integers(0, G, size=n_pairs).astype(np.int32)
+    ji = rng.integers(0, J, size=n_pairs).astype(np.int32)
+    gi[:4] = [0, G - 1, 0, G - 1]
+    ji[:4] = [0, J - 1, J - 1, 0]
+    want, _, _ = oracle.fit_pairs(gi, ji, wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C)
+    flat = torch.from_numpy(gi.astype(np.int64) * J + ji.astype(np.int64)).cuda()
+    got = t.cut.view(-1)[flat].cpu().numpy()
+    np.testing.assert_array_equal(got, want)
+
+    # fit, interest rows and select: whole rows of sampled gaps (first, last, extremes, random)
+    rows = np.unique(np.concatenate([[0, G - 1, int(np.argmin(wl.W)), int(np.argmax(wl.W))],
+                                     rng.integers(0, G, size=n_rows)])).astype(np.int64)
+    Wr = np.ascontiguousarray(wl.W[rows]); Cr = np.ascontiguousarray(wl.C[rows])
+    cut_r, bits_r = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, Wr, Cr)
+    rows_t = torch.from_numpy(rows).cuda()
+    np.testing.assert_array_equal(t.cut[rows_t].cpu().numpy(), cut_r)
+    np.testing.assert_array_equal(t.bits[rows_t].cpu().numpy().view(np.uint32), bits_r)
+    cj, cc, cs = oracle.select(cut_r, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+    np.testing.assert_array_equal(t.cand_job[rows_t].cpu().numpy(), cj)
+    np.testing.assert_array_equal(t.cand_cut[rows_t].cpu().numpy(), cc)
+    np.testing.assert_array_equal(t.cand_score[rows_t].cpu().numpy(), cs)
+
+    # resolve: invariants that hold at any size, with the oracle evaluating each granted pair
+    t.resolve(par)
+    gj = t.grant_job.cpu().numpy(); gc = t.grant_cut.cpu().numpy(); gs = t.grant_score.cpu().numpy()
+    jg = t.job_gap.cpu().numpy()
+    rounds, stable = t.rounds.cpu().tolist()
+    granted = np.nonzero(gj >= 0)[0]
+    assert len(granted) > 0
+    assert len(np.unique(gj[granted])) == len(granted)                  # no job holds two gaps
+    np.testing.assert_array_equal(jg[gj[granted]], granted)             # job_gap inverts grant_job
+    assert (jg >= 0).sum() == len(granted)
+    ocut, sd, sp = oracle.fit_pairs(granted.astype(np.int32), gj[granted], wl.seg_off, wl.dur,
+                                    wl.mem, wl.safe, wl.progress, wl.W, wl.C)
+    np.testing.assert_array_equal(gc[granted], ocut)                    # an interested pair, same cut
+    assert (ocut >= 0).all()
+    assert (sd <= wl.W[granted]).all() and (sp <= wl.C[granted]).all()  # fits by construction
+    F = sd * sp
+    wait = wl.wait[gj[granted]].astype(np.int64)
+    cls = wl.sla_class[gj[granted]]
+    score = {0: F, 1: F * (wl.wait_scale + wait), 2: F * np.asarray(wl.sla_weight, np.int64)[cls],
+             3: F * (wl.wait_scale + wait)}[wl.policy]
+    np.testing.assert_array_equal(gs[granted], score)
+    assert (gs[gj < 0] == 0).all() and (gc[gj < 0] == -1).all()
+    if 0 in rows:                                                        # gap 0 always keeps its first choice
+        assert gj[0] == cj[0] and gc[0] == cc[0] and gs[0] == cs[0]
+    assert 1 <= rounds <= (max_rounds if max_rounds else min(G, J) + 1)
+    if max_rounds and rounds == max_rounds and stable == 0:
+        pass
+    else:
+        assert stable == 1
+        # stable: a sampled ungranted gap has no un-held interested job left
+        ung = [i for i, g in enumerate(rows) if gj[g] < 0]
+        if ung:
+            sub = cut_r[ung]
+            rj, _, _ = oracle.select(sub, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class, jg)
+            assert (rj == -1).all()
+
+
+def test_large_full_size(oracle):
+    _check_full_size(oracle, "large", n_pairs=400_000, n_rows=24, max_rounds=8)
+
+
+def test_stress_full_size(oracle):
+    _check_full_size(oracle, "stress", n_pairs=300_000, n_rows=12, max_rounds=8)
