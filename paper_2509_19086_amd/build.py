@@ -10,7 +10,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsja.so")
 SOURCES = [os.path.join(CSRC, "sja.hip")]
 HEADERS = [os.path.join(CSRC, "sja_internal.h"), os.path.join(CSRC, "sja_kernels.h"),
-           os.path.join(CSRC, "k_fit.h"),
+           os.path.join(CSRC, "k_fit.h"), os.path.join(CSRC, "k_grant.h"), os.path.join(CSRC, "k_sort.h"),
            os.path.join(os.path.dirname(_HERE), "include", "sja.h")]
 
 

@@ -100,14 +100,17 @@ __global__ void k_gap_run_end(int n_gaps, const int32_t *__restrict__ cs, int32_
 // positions into chunks of at most gc.  With at most kMaxClasses classes the
 // chunks never straddle a class and the table-driven path is used; otherwise
 // chunks are plain slices and the fit kernel searches for itself.
-__global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int chunk_bound,
-                                                   const int32_t *__restrict__ cs, int32_t *plan,
-                                                   int32_t *class_begin, int32_t *class_chunk0,
+__global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int sb, int chunk_bound,
+                                                   int sub_bound, const int32_t *__restrict__ cs,
+                                                   int32_t *plan, int32_t *class_begin,
+                                                   int32_t *class_chunk0, int32_t *class_sub0,
                                                    int32_t *chunk_begin, int32_t *chunk_end,
-                                                   int32_t *chunk_class)
+                                                   int32_t *chunk_class, int32_t *chunk_sub,
+                                                   int32_t *sub_begin, int32_t *sub_end,
+                                                   int32_t *sub_class)
 {
     __shared__ int s_cnt[1024];
-    __shared__ int s_classes, s_chunks, s_tabled;
+    __shared__ int s_classes, s_chunks, s_tabled, s_subs;
     const int t = threadIdx.x;
     const int span = (n_gaps + 1023) / 1024;
     const int lo = min(n_gaps, t * span), hi = min(n_gaps, lo + span);
@@ -132,20 +135,26 @@ __global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int chunk
     }
     __syncthreads();
     if (t == 0) {
-        int q = 0;
+        int q = 0, u = 0;
         if (tabled) {
             for (int c = 0; c < n_classes; ++c) {
                 class_chunk0[c] = q;
-                q += (class_begin[c + 1] - class_begin[c] + gc - 1) / gc;
+                class_sub0[c] = u;
+                const int len = class_begin[c + 1] - class_begin[c];
+                q += (len + gc - 1) / gc;
+                u += (len + sb - 1) / sb;
             }
             class_chunk0[n_classes] = q;
+            class_sub0[n_classes] = u;
         } else {
             q = (n_gaps + gc - 1) / gc;
         }
         s_chunks = min(q, chunk_bound);
+        s_subs = min(u, sub_bound);
         plan[kPlanClasses] = n_classes;
         plan[kPlanChunks] = s_chunks;
         plan[kPlanTabled] = tabled ? 1 : 0;
+        plan[kPlanSubBlocks] = s_subs;
     }
     __syncthreads();
     const int n_chunks = s_chunks;
@@ -157,25 +166,37 @@ __global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int chunk
             chunk_begin[q] = b;
             chunk_end[q] = min(class_begin[c + 1], b + gc);
             chunk_class[q] = c;
+            chunk_sub[q] = class_sub0[c] + (q - class_chunk0[c]) * (gc / sb);
         } else {
             chunk_begin[q] = q * gc;
             chunk_end[q] = min(n_gaps, q * gc + gc);
             chunk_class[q] = -1;
+            chunk_sub[q] = 0;
         }
+    }
+    const int n_subs = s_subs;
+    for (int u = t; u < n_subs; u += 1024) {
+        int c = 0;
+        while (c + 1 < n_classes && class_sub0[c + 1] <= u) ++c;
+        const int b = class_begin[c] + (u - class_sub0[c]) * sb;
+        sub_begin[u] = b;
+        sub_end[u] = min(class_begin[c + 1], b + sb);
+        sub_class[u] = c;
     }
 }
 
 // --------------------------------------------------------------------------
 // Start tables (table-driven path).  Thread (job j, class c) walks the job's
-// atoms once, in order, against the class's chunk thresholds (the window of
-// each chunk's first gap, ascending):
-//   start[q][j] = #atoms usable by the first gap of chunk q
+// atoms once, in order, against the windows of the first gap of each of the
+// class's sub-blocks (runs of `sb` sorted positions; a chunk is a whole number
+// of them), ascending:
+//   start[u][j] = #atoms usable by the first gap of sub-block u
 //   ncap[c][j]  = #atoms any gap of class c can reach (peak <= C_c and
 //                 duration <= the class's largest window)
 // --------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_fit_starts(
-    int n_jobs, int gc, const int32_t *__restrict__ plan, const int32_t *__restrict__ class_begin,
-    const int32_t *__restrict__ class_chunk0, const int32_t *__restrict__ gap_w,
+    int n_jobs, int sb, const int32_t *__restrict__ plan, const int32_t *__restrict__ class_begin,
+    const int32_t *__restrict__ class_sub0, const int32_t *__restrict__ gap_w,
     const int32_t *__restrict__ gap_c, const int64_t *__restrict__ seg_off,
     const int2 *__restrict__ atom_dp, const int32_t *__restrict__ n_atoms,
     int32_t *__restrict__ start_tab, int32_t *__restrict__ ncap_tab)
@@ -187,7 +208,7 @@ __global__ __launch_bounds__(256) void k_fit_starts(
     const int pos_b = class_begin[c], pos_e = class_begin[c + 1];
     const int cap = gap_c[pos_b];
     const int w_max = gap_w[pos_e - 1];
-    const int q0 = class_chunk0[c], qe = class_chunk0[c + 1];
+    const int q0 = class_sub0[c], qe = class_sub0[c + 1];
     const int2 *dp = atom_dp + seg_off[j];
     const int n = n_atoms[j];
 
@@ -210,7 +231,7 @@ __global__ __launch_bounds__(256) void k_fit_starts(
                 while (q < qe && v[t].x > w_q) {
                     start_tab[int64_t(q) * n_jobs + j] = idx;
                     ++q;
-                    if (q < qe) w_q = gap_w[pos_b + (q - q0) * gc];
+                    if (q < qe) w_q = gap_w[pos_b + (q - q0) * sb];
                 }
             }
         }
@@ -251,7 +272,8 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     const int2 *__restrict__ atom_dp, const int2 *__restrict__ atom_db,
     const int32_t *__restrict__ n_atoms, const int32_t *__restrict__ plan,
     const int32_t *__restrict__ chunk_begin, const int32_t *__restrict__ chunk_end,
-    const int32_t *__restrict__ chunk_class, const int32_t *__restrict__ start_tab,
+    const int32_t *__restrict__ chunk_class, const int32_t *__restrict__ chunk_sub,
+    const int32_t *__restrict__ start_tab,
     const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ gap_w,
     const int32_t *__restrict__ gap_c, const int64_t *__restrict__ gap_row,
     const int64_t *__restrict__ gap_brow, const int32_t *__restrict__ gap_run_end,
@@ -291,7 +313,7 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     auto init = [&](int s) {
         c_cur = gap_c[s];
         if (tabled) {
-            a = start_tab[int64_t(chunk) * n_jobs + j];
+            a = start_tab[int64_t(chunk_sub[chunk]) * n_jobs + j];
             n_cap = ncap_tab[int64_t(chunk_class[chunk]) * n_jobs + j];
         } else {
             n_cap = upper_bound_peak(dp, n, c_cur);

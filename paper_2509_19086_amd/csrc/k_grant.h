@@ -1,0 +1,287 @@
+// K4, list-driven: conflict rounds without re-scanning the pair matrix.
+//
+// The rounds are inherently sequential (a round's selections depend on the
+// grants of the round before) and a large batch needs thousands of them, so a
+// round must cost next to nothing.  What a gap needs in a round is "my best job
+// that no gap holds yet".  Every gap ranks jobs by the same per-atom policy key
+// (an atom is a safe cut of a job; the key depends on the job and on the cut,
+// not on the gap), and in sorted gap order an atom is the answer of a job for
+// one contiguous range of positions.  So:
+//   1. all reachable atoms are ranked once by policy key (stable radix sort:
+//      key descending, job id ascending);
+//   2. for every sub-block of <= 64 sorted gap positions the atoms some position
+//      of it would get are listed in rank order, each with the range of lanes
+//      (positions) it applies to;
+//   3. a round is one small kernel: a wave per sub-block, a lane per gap; a lane
+//      that lost walks on through its sub-block's list to the next entry that
+//      covers it and whose job is not held, and claims that job with an
+//      atomicMax of (round, ~gap index); the next round's kernel first checks
+//      who won.  Claims carry the round number, so nothing is ever reset and a
+//      claim made in the current round is not mistaken for a hold.
+#pragma once
+
+#include "k_sort.h"
+
+namespace sja {
+
+struct PolicyDev {
+    int policy;
+    int wait_scale;
+    int w0, w1, w2;
+    int class0_override;
+};
+
+// Per-job multiplier and tier of the policy key: key = (tier, F * mult [, F]).
+__device__ __forceinline__ void job_policy(const PolicyDev &pol, const int32_t *wait,
+                                           const uint8_t *sla_class, int j,
+                                           unsigned long long &mult, unsigned long long &tier)
+{
+    const int cls = sla_class ? sla_class[j] : 0;
+    const long long wt = wait ? wait[j] : 0;
+    mult = 1;
+    tier = 0;
+    switch (pol.policy) {
+    case SJA_POLICY_FAIRNESS: mult = (unsigned long long)(pol.wait_scale + wt); break;
+    case SJA_POLICY_SLA:
+        mult = (unsigned long long)(cls == 0 ? pol.w0 : (cls == 1 ? pol.w1 : pol.w2));
+        tier = (pol.class0_override && cls == 0) ? 1 : 0;
+        break;
+    case SJA_POLICY_MIXED:
+        mult = (unsigned long long)(pol.wait_scale + wt);
+        tier = (unsigned long long)(2 - cls);
+        break;
+    default: break;
+    }
+}
+
+// reach[j] = atoms of job j that some capacity class can reach; reach[n_jobs] = 0.
+__global__ void k_reach(int n_jobs, const int32_t *__restrict__ plan, const int32_t *__restrict__ ncap_tab,
+                        int32_t *__restrict__ reach)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j > n_jobs) return;
+    int r = 0;
+    if (j < n_jobs && plan[kPlanTabled]) {
+        const int n_classes = plan[kPlanClasses];
+        for (int c = 0; c < n_classes; ++c) r = max(r, ncap_tab[int64_t(c) * n_jobs + j]);
+    }
+    reach[j] = r;
+}
+
+// One wave per job: inverted policy keys of its reachable atoms (ascending sort
+// of the inverted key = descending key) and the identity permutation.
+__global__ __launch_bounds__(256) void k_atom_keys(
+    int n_jobs, PolicyDev pol, const int64_t *__restrict__ seg_off, const int2 *__restrict__ atom_dp,
+    const int32_t *__restrict__ abase, const int32_t *__restrict__ wait,
+    const uint8_t *__restrict__ sla_class, unsigned long long *__restrict__ key_hi,
+    unsigned long long *__restrict__ key_lo, uint32_t *__restrict__ perm)
+{
+    const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (j >= n_jobs) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int a0 = abase[j], n = abase[j + 1] - a0;
+    const int2 *dp = atom_dp + seg_off[j];
+    unsigned long long mult, tier;
+    job_policy(pol, wait, sla_class, j, mult, tier);
+    const bool mixed = pol.policy == SJA_POLICY_MIXED;
+    for (int a = lane; a < n; a += kWave) {
+        const int2 v = dp[a];
+        const unsigned long long F = (unsigned long long)v.x * (unsigned long long)v.y;
+        key_hi[a0 + a] = ~((tier << 62) | (F * mult));
+        key_lo[a0 + a] = ~(mixed ? F : 0ull);
+        perm[a0 + a] = uint32_t(a0 + a);
+    }
+}
+
+struct MovePerm {
+    const uint32_t *src;
+    uint32_t *dst;
+    __device__ void operator()(int64_t i, int64_t o) const { dst[o] = src[i]; }
+};
+
+__global__ void k_rank_from_perm(const int32_t *n_ptr, const uint32_t *__restrict__ perm,
+                                 uint32_t *__restrict__ rank)
+{
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < *n_ptr) rank[perm[i]] = uint32_t(i);
+}
+
+// Number of entries of sorted w[0..len) that are < d.
+__device__ __forceinline__ int count_less(const int *w, int len, int d)
+{
+    int lo = 0, hi = len;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (w[mid] < d) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// Entries of the sub-block lists.  Thread (sub-block u, job j) visits the atoms
+// of j that some position of u gets: atom a applies to lanes [lo, hi) where lo
+// is the first position whose window reaches D_a and hi the first one that
+// already reaches atom a+1.  WRITE = false only counts (per sub-block and in
+// total); WRITE = true stores (key = u : rank, job, atom, lo | hi << 8).
+template <bool WRITE>
+__global__ __launch_bounds__(256) void k_list_emit(
+    int n_jobs, int rank_bits, const int32_t *__restrict__ plan, const int32_t *__restrict__ sub_begin,
+    const int32_t *__restrict__ sub_end, const int32_t *__restrict__ sub_class,
+    const int32_t *__restrict__ gap_w, const int64_t *__restrict__ seg_off,
+    const int2 *__restrict__ atom_dp, const int32_t *__restrict__ start_tab,
+    const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ abase,
+    const uint32_t *__restrict__ rank, int32_t *sub_count, int32_t *counters /*[0]=total, [1]=cursor*/,
+    unsigned long long *__restrict__ ekey, uint32_t *__restrict__ ej, uint32_t *__restrict__ ea,
+    uint32_t *__restrict__ el)
+{
+    __shared__ int s_w[64];
+    const int u = blockIdx.y;
+    if (!plan[kPlanTabled] || u >= plan[kPlanSubBlocks]) return;
+    const int b0 = sub_begin[u], len = sub_end[u] - b0;
+    if (threadIdx.x < 64) s_w[threadIdx.x] = threadIdx.x < len ? gap_w[b0 + threadIdx.x] : INT32_MAX;
+    __syncthreads();
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    const bool live = j < n_jobs;
+    int a_first = 0, n_cap = 0;
+    const int2 *dp = atom_dp;
+    if (live) {
+        a_first = start_tab[int64_t(u) * n_jobs + j];
+        n_cap = ncap_tab[int64_t(sub_class[u]) * n_jobs + j];
+        dp = atom_dp + seg_off[j];
+    }
+    const int a_begin = max(a_first - 1, 0);
+
+    auto visit = [&](auto &&sink) {
+        int d_next = a_begin < n_cap ? dp[a_begin].x : 0;
+        for (int a = a_begin; a < n_cap; ++a) {
+            const int d_a = d_next;
+            const int lo = a < a_first ? 0 : count_less(s_w, len, d_a);
+            if (lo >= len) break;
+            int hi = len;
+            if (a + 1 < n_cap) {
+                d_next = dp[a + 1].x;
+                hi = count_less(s_w, len, d_next);
+            }
+            if (hi > lo) sink(a, lo, hi);
+        }
+    };
+
+    int cnt = 0;
+    visit([&](int, int, int) { ++cnt; });
+    // wave-wide totals
+    int incl = cnt;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int t = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += t;
+    }
+    const int wave_total = __shfl(incl, kWave - 1, kWave);
+    if (!WRITE) {
+        if (lane == 0 && wave_total) {
+            atomicAdd(&sub_count[u], wave_total);
+            atomicAdd(&counters[0], wave_total);
+        }
+    } else {
+        int wave_base = 0;
+        if (lane == 0 && wave_total) wave_base = atomicAdd(&counters[1], wave_total);
+        wave_base = __shfl(wave_base, 0, kWave);
+        int64_t slot = int64_t(wave_base) + incl - cnt;
+        const int a0 = live ? abase[j] : 0;
+        visit([&](int a, int lo, int hi) {
+            ekey[slot] = ((unsigned long long)u << rank_bits) | rank[a0 + a];
+            ej[slot] = uint32_t(j);
+            ea[slot] = uint32_t(a);
+            el[slot] = uint32_t(lo | (hi << 8));
+            ++slot;
+        });
+    }
+}
+
+struct MoveEntry {
+    const unsigned long long *k0; const uint32_t *j0, *a0, *l0;
+    unsigned long long *k1; uint32_t *j1, *a1, *l1;
+    __device__ void operator()(int64_t i, int64_t o) const { k1[o] = k0[i]; j1[o] = j0[i]; a1[o] = a0[i]; l1[o] = l0[i]; }
+};
+
+__device__ __forceinline__ unsigned long long claim_of(int round, int g)
+{
+    return (static_cast<unsigned long long>(round) << 32) | (0xffffffffu - uint32_t(g));
+}
+
+// One round.  First the outcome of round k-1: a gap whose candidate's claim word
+// is its own has won (grant is final), otherwise it lost.  Then, if `propose`,
+// every gap that is still active selects again and claims.
+__global__ __launch_bounds__(256) void k_grant_round(
+    int round, int propose, int n_jobs, PolicyDev pol, const int32_t *__restrict__ plan,
+    const int32_t *__restrict__ sub_begin, const int32_t *__restrict__ sub_end,
+    const int32_t *__restrict__ list_off, const int32_t *__restrict__ gap_order,
+    const uint32_t *__restrict__ ej, const uint32_t *__restrict__ ea, const uint32_t *__restrict__ el,
+    unsigned long long *claim, int32_t *st_ptr, int32_t *st_cand, uint8_t *st_flag, int32_t *cnt_lost,
+    int32_t *cnt_cand, const int64_t *__restrict__ seg_off, const int2 *__restrict__ atom_dp,
+    const int2 *__restrict__ atom_db, const int32_t *__restrict__ wait,
+    const uint8_t *__restrict__ sla_class, int32_t *grant_job, int32_t *grant_cut, int64_t *grant_score,
+    int32_t *job_gap)
+{
+    const int u = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (u >= plan[kPlanSubBlocks]) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int b0 = sub_begin[u];
+    const bool valid = lane < sub_end[u] - b0;
+    const int s = b0 + lane;
+    int g = 0, flag = 2, cand_e = -1, e = 0;
+    if (valid) {
+        g = gap_order[s];
+        if (round == 1) { flag = 0; e = list_off[u]; }
+        else { flag = st_flag[s]; cand_e = st_cand[s]; e = st_ptr[s]; }
+    }
+    bool lost = false;
+    if (flag == 0 && cand_e >= 0) {
+        const int j = int(ej[cand_e]);
+        if (claim[j] == claim_of(round - 1, g)) {
+            const int a = int(ea[cand_e]);
+            const int64_t base = seg_off[j];
+            const int2 v = atom_dp[base + a];
+            unsigned long long mult, tier;
+            job_policy(pol, wait, sla_class, j, mult, tier);
+            grant_job[g] = j;
+            grant_cut[g] = atom_db[base + a].y;
+            grant_score[g] = int64_t((unsigned long long)v.x * (unsigned long long)v.y * mult);
+            job_gap[j] = g;
+            st_flag[s] = 1;
+            flag = 1;
+        } else {
+            lost = true;
+        }
+    }
+    bool cand = false;
+    if (flag == 0 && propose) {
+        const int end = list_off[u + 1];
+        int found = -1;
+        while (e < end) {
+            const uint32_t lh = el[e];
+            if (lane >= int(lh & 255u) && lane < int(lh >> 8)) {
+                const uint32_t stamp = uint32_t(claim[ej[e]] >> 32);
+                if (stamp == 0 || stamp >= uint32_t(round)) { found = e; break; }
+            }
+            ++e;
+        }
+        if (found >= 0) {
+            st_cand[s] = found;
+            st_ptr[s] = found + 1;
+            if (round == 1) st_flag[s] = 0;
+            atomicMax(&claim[ej[found]], claim_of(round, g));
+            cand = true;
+        } else {
+            st_cand[s] = -1;
+            st_ptr[s] = end;
+            st_flag[s] = 2;
+        }
+    }
+    const unsigned long long ml = __ballot(lost), mc = __ballot(cand);
+    if (lane == 0) {
+        if (ml) atomicAdd(&cnt_lost[round - 1], __popcll(ml));
+        if (mc) atomicAdd(&cnt_cand[round], __popcll(mc));
+    }
+}
+
+}  // namespace sja

@@ -1,0 +1,171 @@
+// Device-wide building blocks used by the grant path: an exclusive scan and a
+// stable least-significant-digit radix pass (8-bit digits).  Plain, three
+// kernels each; sizes here are tens of millions of items at most.
+#pragma once
+
+#include "sja_internal.h"
+
+namespace sja {
+
+// --------------------------------------------------------------------------
+// Exclusive scan of int32, in place, any length: per-block scan of 2048
+// items, one block scans the block sums, a third kernel adds them back.
+// --------------------------------------------------------------------------
+constexpr int kScanTile = 2048;
+
+__global__ __launch_bounds__(256) void k_scan_tiles(int32_t *data, int64_t n, int32_t *tile_sums)
+{
+    __shared__ int s_part[256];
+    const int64_t base = int64_t(blockIdx.x) * kScanTile + threadIdx.x * 8;
+    int v[8];
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[i] = (base + i < n) ? data[base + i] : 0;
+        sum += v[i];
+    }
+    s_part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {
+        const int add = threadIdx.x >= d ? s_part[threadIdx.x - d] : 0;
+        __syncthreads();
+        s_part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int run = s_part[threadIdx.x] - sum;           // exclusive prefix of this thread
+    if (threadIdx.x == 255) tile_sums[blockIdx.x] = s_part[255];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (base + i < n) data[base + i] = run;
+        run += v[i];
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_scan_sums(int32_t *sums, int n_tiles, int32_t *total)
+{
+    __shared__ int s_part[1024];
+    __shared__ int s_carry;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < n_tiles; b0 += 1024) {
+        const int i = b0 + threadIdx.x;
+        const int mine = i < n_tiles ? sums[i] : 0;
+        s_part[threadIdx.x] = mine;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            const int add = threadIdx.x >= d ? s_part[threadIdx.x - d] : 0;
+            __syncthreads();
+            s_part[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int carry = s_carry;
+        if (i < n_tiles) sums[i] = carry + s_part[threadIdx.x] - mine;
+        __syncthreads();
+        if (threadIdx.x == 1023) s_carry = carry + s_part[1023];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && total) *total = s_carry;
+}
+
+__global__ __launch_bounds__(256) void k_scan_add(int32_t *data, int64_t n, const int32_t *tile_sums)
+{
+    const int add = tile_sums[blockIdx.x];
+    const int64_t base = int64_t(blockIdx.x) * kScanTile + threadIdx.x * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (base + i < n) data[base + i] += add;
+}
+
+// Enqueues an in-place exclusive scan; tile_sums needs ceil(n/2048) ints.
+// total (device, may be null) receives the sum of all items.
+inline hipError_t enqueue_scan(hipStream_t st, int32_t *data, int64_t n, int32_t *tile_sums, int32_t *total)
+{
+    if (n <= 0) return hipSuccess;
+    const int n_tiles = int((n + kScanTile - 1) / kScanTile);
+    hipLaunchKernelGGL(k_scan_tiles, dim3(n_tiles), dim3(256), 0, st, data, n, tile_sums);
+    hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(1024), 0, st, tile_sums, n_tiles, total);
+    hipLaunchKernelGGL(k_scan_add, dim3(n_tiles), dim3(256), 0, st, data, n, tile_sums);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------
+// Stable radix pass.  Items are processed in tiles of 2048 (8 rounds of 256
+// consecutive items); hist is digit-major ([256][n_tiles]) so that one
+// exclusive scan over it yields every (digit, tile) output offset.
+// n lives in device memory (it is produced by earlier kernels).
+// --------------------------------------------------------------------------
+constexpr int kRadixTile = 2048;
+
+// Digit source for sorting a permutation by 64-bit keys it points to.
+struct DigitViaPerm {
+    const unsigned long long *keys;
+    const uint32_t *perm;
+    __device__ unsigned operator()(int64_t i, int shift) const { return unsigned(keys[perm[i]] >> shift) & 255u; }
+};
+// Digit source for items that carry their 64-bit key.
+struct DigitDirect {
+    const unsigned long long *keys;
+    __device__ unsigned operator()(int64_t i, int shift) const { return unsigned(keys[i] >> shift) & 255u; }
+};
+
+template <typename Digit>
+__global__ __launch_bounds__(256) void k_radix_hist(Digit dig, const int32_t *n_ptr, int shift,
+                                                    int32_t *hist, int n_tiles)
+{
+    __shared__ int s_h[256];
+    const int64_t n = *n_ptr;
+    s_h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
+    if (base < n) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int64_t i = base + r * 256 + threadIdx.x;
+            if (i < n) atomicAdd(&s_h[dig(i, shift)], 1);
+        }
+    }
+    __syncthreads();
+    hist[int64_t(threadIdx.x) * n_tiles + blockIdx.x] = s_h[threadIdx.x];
+}
+
+// Payload mover: called once per item with its source and destination index.
+template <typename Digit, typename Mover>
+__global__ __launch_bounds__(256) void k_radix_scatter(Digit dig, Mover mv, const int32_t *n_ptr, int shift,
+                                                       const int32_t *hist, int n_tiles)
+{
+    __shared__ int s_run[256];          // next output slot per digit for this tile
+    __shared__ int s_wave[4][256];      // per-round, per-wave digit counts
+    const int64_t n = *n_ptr;
+    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
+    if (base >= n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    s_run[tid] = hist[int64_t(tid) * n_tiles + blockIdx.x];
+    for (int r = 0; r < 8; ++r) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) s_wave[w][tid] = 0;
+        __syncthreads();
+        const int64_t i = base + r * 256 + tid;
+        const bool valid = i < n;
+        const unsigned d = valid ? dig(i, shift) : 0u;
+        // lanes of this wave with the same digit
+        unsigned long long peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const unsigned long long m = __ballot((d >> b) & 1u);
+            peers &= ((d >> b) & 1u) ? m : ~m;
+        }
+        const int rank_in_wave = __popcll(peers & ((1ull << lane) - 1ull));
+        if (valid && rank_in_wave == 0) s_wave[wave][d] = __popcll(peers);
+        __syncthreads();
+        if (valid) {
+            int off = s_run[d] + rank_in_wave;
+            for (int w = 0; w < wave; ++w) off += s_wave[w][d];
+            mv(i, int64_t(off));
+        }
+        __syncthreads();
+        s_run[tid] += s_wave[0][tid] + s_wave[1][tid] + s_wave[2][tid] + s_wave[3][tid];
+        __syncthreads();
+    }
+}
+
+}  // namespace sja

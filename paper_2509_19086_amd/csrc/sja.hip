@@ -3,6 +3,7 @@
 #include "sja_kernels.h"
 
 #include <new>
+#include <vector>
 
 using namespace sja;
 
@@ -97,6 +98,173 @@ int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const 
     hipLaunchKernelGGL(k_select_reduce, dim3((G + 255) / 256), dim3(256), 0, st, G, job_tiles,
                        ws_ptr<SelPartial>(ctx, L.sel_part), cand_job, cand_cut, cand_score);
     SJA_HIP(hipGetLastError(), "k_select_reduce launch");
+    return SJA_OK;
+}
+
+
+// Radix-sorts `n` (device count, host copy n_host) items on the key bits
+// [0, key_bits) with the given digit source / mover pair per pass; `flip`
+// reports whether the result ended in the second buffer set.
+template <typename MakeDigit, typename MakeMover>
+int radix_sort_bits(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t *n_dev, int64_t n_host,
+                    int first_bit, int last_bit, bool &flip, MakeDigit make_digit, MakeMover make_mover)
+{
+    if (n_host <= 0) return SJA_OK;
+    const int n_tiles = int((n_host + kRadixTile - 1) / kRadixTile);
+    int32_t *hist = ws_ptr<int32_t>(ctx, L.g_hist);
+    int32_t *tmp = ws_ptr<int32_t>(ctx, L.g_scan_tmp);
+    for (int shift = first_bit; shift < last_bit; shift += 8) {
+        auto dig = make_digit(flip);
+        auto mov = make_mover(flip);
+        hipLaunchKernelGGL((k_radix_hist<decltype(dig)>), dim3(n_tiles), dim3(256), 0, st, dig, n_dev, shift, hist, n_tiles);
+        SJA_HIP(hipGetLastError(), "k_radix_hist launch");
+        SJA_HIP(enqueue_scan(st, hist, int64_t(256) * n_tiles, tmp, nullptr), "radix scan launch");
+        hipLaunchKernelGGL((k_radix_scatter<decltype(dig), decltype(mov)>), dim3(n_tiles), dim3(256), 0, st, dig, mov,
+                           n_dev, shift, hist, n_tiles);
+        SJA_HIP(hipGetLastError(), "k_radix_scatter launch");
+        flip = !flip;
+    }
+    return SJA_OK;
+}
+
+int bits_for(int64_t n)
+{
+    int b = 1;
+    while ((int64_t(1) << b) < n) ++b;
+    return b;
+}
+
+// List-driven conflict rounds.  Returns SJA_OK with *done = true when it
+// produced the grants, *done = false when the batch is outside what the lists
+// serve (more than kMaxClasses capacities, or more list entries than the
+// workspace holds) and the caller must take the matrix-scanning rounds.
+int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_params *params,
+                       const int32_t *wait, const uint8_t *sla_class, int32_t *grant_job, int32_t *grant_cut,
+                       int64_t *grant_score, int32_t *job_gap, int64_t cap, int32_t result[2], bool *done)
+{
+    *done = false;
+    const int G = ctx->n_gaps, J = ctx->n_jobs;
+    const int sub_bound = int(fit_sub_bound(G, J));
+    const PolicyDev pol = to_dev(params);
+    int32_t *plan = ws_ptr<int32_t>(ctx, L.plan);
+    int32_t *abase = ws_ptr<int32_t>(ctx, L.g_abase);
+    int32_t *tmp = ws_ptr<int32_t>(ctx, L.g_scan_tmp);
+    int32_t *counters = ws_ptr<int32_t>(ctx, L.res_counters);      // [0] entries, [1] cursor, [2] atoms
+    int32_t *list_off = ws_ptr<int32_t>(ctx, L.g_list_off);
+    const int2 *atom_dp = ws_ptr<int2>(ctx, L.atom_dp);
+    const int2 *atom_db = ws_ptr<int2>(ctx, L.atom_db);
+    const int32_t *sub_begin = ws_ptr<int32_t>(ctx, L.sub_begin), *sub_end = ws_ptr<int32_t>(ctx, L.sub_end);
+    const int32_t *sub_class = ws_ptr<int32_t>(ctx, L.sub_class);
+    const int32_t *start_tab = ws_ptr<int32_t>(ctx, L.start_tab), *ncap_tab = ws_ptr<int32_t>(ctx, L.ncap_tab);
+    const int32_t *gap_w = ws_ptr<int32_t>(ctx, L.gap_w);
+    unsigned long long *key_hi = ws_ptr<unsigned long long>(ctx, L.g_key_hi);
+    unsigned long long *key_lo = ws_ptr<unsigned long long>(ctx, L.g_key_lo);
+    uint32_t *perm[2] = {ws_ptr<uint32_t>(ctx, L.g_perm0), ws_ptr<uint32_t>(ctx, L.g_perm1)};
+    uint32_t *rank = ws_ptr<uint32_t>(ctx, L.g_rank);
+    unsigned long long *ekey[2] = {ws_ptr<unsigned long long>(ctx, L.g_ekey0), ws_ptr<unsigned long long>(ctx, L.g_ekey1)};
+    uint32_t *ej[2] = {ws_ptr<uint32_t>(ctx, L.g_ej0), ws_ptr<uint32_t>(ctx, L.g_ej1)};
+    uint32_t *ea[2] = {ws_ptr<uint32_t>(ctx, L.g_ea0), ws_ptr<uint32_t>(ctx, L.g_ea1)};
+    uint32_t *el[2] = {ws_ptr<uint32_t>(ctx, L.g_el0), ws_ptr<uint32_t>(ctx, L.g_el1)};
+
+    // 1. reachable atoms per job -> compact atom ids; entry counts per sub-block
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, st, counters, int64_t(16), 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3((sub_bound + 2 + 255) / 256), dim3(256), 0, st, list_off, int64_t(sub_bound + 2), 0);
+    hipLaunchKernelGGL(k_reach, dim3((J + 1 + 255) / 256), dim3(256), 0, st, J, plan, ncap_tab, abase);
+    SJA_HIP(hipGetLastError(), "k_reach launch");
+    SJA_HIP(enqueue_scan(st, abase, int64_t(J) + 1, tmp, counters + 2), "atom scan launch");
+    const dim3 emit_grid((J + 255) / 256, sub_bound);
+    hipLaunchKernelGGL((k_list_emit<false>), emit_grid, dim3(256), 0, st, J, 0, plan, sub_begin, sub_end, sub_class,
+                       gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters, ekey[0],
+                       ej[0], ea[0], el[0]);
+    SJA_HIP(hipGetLastError(), "k_list_emit count launch");
+    int32_t host_plan[kPlanWords] = {0}, host_counters[4] = {0};
+    SJA_HIP(hipMemcpyAsync(host_plan, plan, sizeof(host_plan), hipMemcpyDeviceToHost, st), "plan readback");
+    SJA_HIP(hipMemcpyAsync(host_counters, counters, sizeof(host_counters), hipMemcpyDeviceToHost, st), "count readback");
+    SJA_HIP(hipStreamSynchronize(st), "count synchronise");
+    const int64_t n_entries = host_counters[0], n_atoms = host_counters[2];
+    const int n_subs = host_plan[kPlanSubBlocks];
+    if (!host_plan[kPlanTabled] || n_entries < 0 || n_entries > L.entry_cap || n_atoms > L.atom_cap) return SJA_OK;
+
+    // 2. rank the atoms by policy key (descending key, ascending job id)
+    if (n_atoms > 0) {
+        hipLaunchKernelGGL(k_atom_keys, dim3((J + 3) / 4), dim3(256), 0, st, J, pol, ctx->seg_off, atom_dp, abase, wait,
+                           sla_class, key_hi, key_lo, perm[0]);
+        SJA_HIP(hipGetLastError(), "k_atom_keys launch");
+        bool flip = false;
+        auto mover = [&](bool f) { return MovePerm{perm[f ? 1 : 0], perm[f ? 0 : 1]}; };
+        int rc = SJA_OK;
+        if (params->policy == SJA_POLICY_MIXED) {
+            rc = radix_sort_bits(ctx, st, L, counters + 2, n_atoms, 0, 64, flip,
+                                 [&](bool f) { return DigitViaPerm{key_lo, perm[f ? 1 : 0]}; }, mover);
+            if (rc != SJA_OK) return rc;
+        }
+        rc = radix_sort_bits(ctx, st, L, counters + 2, n_atoms, 0, 64, flip,
+                             [&](bool f) { return DigitViaPerm{key_hi, perm[f ? 1 : 0]}; }, mover);
+        if (rc != SJA_OK) return rc;
+        hipLaunchKernelGGL(k_rank_from_perm, dim3(unsigned((n_atoms + 255) / 256)), dim3(256), 0, st, counters + 2,
+                           perm[flip ? 1 : 0], rank);
+        SJA_HIP(hipGetLastError(), "k_rank_from_perm launch");
+    }
+
+    // 3. sub-block lists in rank order
+    const int rank_bits = bits_for(n_atoms > 1 ? n_atoms : 2);
+    const int sub_bits = bits_for(n_subs > 1 ? n_subs : 2);
+    SJA_HIP(enqueue_scan(st, list_off, int64_t(sub_bound) + 2, tmp, nullptr), "list offset scan launch");
+    bool eflip = false;
+    if (n_entries > 0) {
+        hipLaunchKernelGGL((k_list_emit<true>), emit_grid, dim3(256), 0, st, J, rank_bits, plan, sub_begin, sub_end,
+                           sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters,
+                           ekey[0], ej[0], ea[0], el[0]);
+        SJA_HIP(hipGetLastError(), "k_list_emit launch");
+        int rc = radix_sort_bits(ctx, st, L, counters, n_entries, 0, rank_bits + sub_bits, eflip,
+                                 [&](bool f) { return DigitDirect{ekey[f ? 1 : 0]}; },
+                                 [&](bool f) {
+                                     const int a = f ? 1 : 0, b = f ? 0 : 1;
+                                     return MoveEntry{ekey[a], ej[a], ea[a], el[a], ekey[b], ej[b], ea[b], el[b]};
+                                 });
+        if (rc != SJA_OK) return rc;
+    }
+    const int fb = eflip ? 1 : 0;
+
+    // 4. rounds, in batches between looks at the counters
+    int32_t *cnt_lost = ws_ptr<int32_t>(ctx, L.g_cnt_lost), *cnt_cand = ws_ptr<int32_t>(ctx, L.g_cnt_cand);
+    const int64_t rounds_cap = int64_t(G < J ? G : J) + 4;
+    hipLaunchKernelGGL(k_fill_i32, dim3(unsigned((rounds_cap + 255) / 256)), dim3(256), 0, st, cnt_lost, rounds_cap, 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3(unsigned((rounds_cap + 255) / 256)), dim3(256), 0, st, cnt_cand, rounds_cap, 0);
+    SJA_HIP(hipGetLastError(), "counter fill launch");
+    auto launch_round = [&](int64_t k, int propose) {
+        hipLaunchKernelGGL(k_grant_round, dim3((n_subs + 3) / 4), dim3(256), 0, st, int(k), propose, J, pol, plan,
+                           sub_begin, sub_end, list_off, ws_ptr<int32_t>(ctx, L.gap_order), ej[fb], ea[fb], el[fb],
+                           ws_ptr<unsigned long long>(ctx, L.res_claim), ws_ptr<int32_t>(ctx, L.g_ptr),
+                           ws_ptr<int32_t>(ctx, L.g_cand), ws_ptr<uint8_t>(ctx, L.g_flag), cnt_lost, cnt_cand,
+                           ctx->seg_off, atom_dp, atom_db, wait, sla_class, grant_job, grant_cut, grant_score, job_gap);
+        return hipGetLastError();
+    };
+    std::vector<int32_t> h_lost, h_cand;
+    int64_t launched = 0;        // kernels 1..launched have been enqueued
+    int64_t next_check = 1;      // first round whose end is not yet decided
+    bool finished = false;
+    const int64_t batch = 64;
+    while (!finished) {
+        const int64_t upto = (launched + batch < cap) ? launched + batch : cap;
+        for (int64_t k = launched + 1; k <= upto; ++k) SJA_HIP(launch_round(k, 1), "k_grant_round launch");
+        if (upto == cap) SJA_HIP(launch_round(cap + 1, 0), "k_grant_round launch");
+        launched = upto;
+        const int64_t known = (upto == cap) ? cap + 1 : upto;        // kernels that have run
+        h_lost.resize(size_t(known + 1));
+        h_cand.resize(size_t(known + 1));
+        SJA_HIP(hipMemcpyAsync(h_lost.data(), cnt_lost, size_t(known + 1) * 4, hipMemcpyDeviceToHost, st), "round counters");
+        SJA_HIP(hipMemcpyAsync(h_cand.data(), cnt_cand, size_t(known + 1) * 4, hipMemcpyDeviceToHost, st), "round counters");
+        SJA_HIP(hipStreamSynchronize(st), "round synchronise");
+        for (int64_t r = next_check; r <= upto; ++r) {
+            if (h_cand[size_t(r)] == 0) { result[0] = int32_t(r); result[1] = 1; finished = true; break; }
+            if (r + 1 > known) { next_check = r; break; }              // losers of r not counted yet
+            if (h_lost[size_t(r)] == 0) { result[0] = int32_t(r); result[1] = 1; finished = true; break; }
+            if (r == cap) { result[0] = int32_t(cap); result[1] = 0; finished = true; break; }
+            next_check = r + 1;
+        }
+    }
+    *done = true;
     return SJA_OK;
 }
 
@@ -238,6 +406,8 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
         const int words = (J + 31) / 32;
         const int gc = fit_chunk_len(n_gaps, J);
         const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
+        const int sb = fit_sub_len(n_gaps, J);
+        const int sub_bound = int(fit_sub_bound(n_gaps, J));
         const dim3 per_gap((n_gaps + 255) / 256), b256(256);
         int32_t *rank = ws_ptr<int32_t>(ctx, L.gap_rank);
         int32_t *gw = ws_ptr<int32_t>(ctx, L.gap_w), *gcap = ws_ptr<int32_t>(ctx, L.gap_c);
@@ -255,13 +425,15 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
             hipLaunchKernelGGL(k_gap_run_end, per_gap, b256, 0, st, n_gaps, gcap,
                                ws_ptr<int32_t>(ctx, L.gap_run_end));
             SJA_HIP(hipGetLastError(), "k_gap_run_end launch");
-            hipLaunchKernelGGL(k_gap_plan, dim3(1), dim3(1024), 0, st, n_gaps, gc, chunk_bound, gcap, plan,
-                               ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0),
-                               ws_ptr<int32_t>(ctx, L.chunk_begin), ws_ptr<int32_t>(ctx, L.chunk_end),
-                               ws_ptr<int32_t>(ctx, L.chunk_class));
+            hipLaunchKernelGGL(k_gap_plan, dim3(1), dim3(1024), 0, st, n_gaps, gc, sb, chunk_bound, sub_bound, gcap,
+                               plan, ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0),
+                               ws_ptr<int32_t>(ctx, L.class_sub0), ws_ptr<int32_t>(ctx, L.chunk_begin),
+                               ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
+                               ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.sub_begin),
+                               ws_ptr<int32_t>(ctx, L.sub_end), ws_ptr<int32_t>(ctx, L.sub_class));
             SJA_HIP(hipGetLastError(), "k_gap_plan launch");
-            hipLaunchKernelGGL(k_fit_starts, dim3((J + 255) / 256, kMaxClasses), b256, 0, st, J, gc, plan,
-                               ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0), gw, gcap,
+            hipLaunchKernelGGL(k_fit_starts, dim3((J + 255) / 256, kMaxClasses), b256, 0, st, J, sb, plan,
+                               ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_sub0), gw, gcap,
                                ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int32_t>(ctx, L.start_tab), ws_ptr<int32_t>(ctx, L.ncap_tab));
             SJA_HIP(hipGetLastError(), "k_fit_starts launch");
@@ -279,7 +451,8 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
                                J, chunk_bound, ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp),
                                ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms), plan,
                                ws_ptr<int32_t>(ctx, L.chunk_begin), ws_ptr<int32_t>(ctx, L.chunk_end),
-                               ws_ptr<int32_t>(ctx, L.chunk_class), ws_ptr<int32_t>(ctx, L.start_tab),
+                               ws_ptr<int32_t>(ctx, L.chunk_class), ws_ptr<int32_t>(ctx, L.chunk_sub),
+                               ws_ptr<int32_t>(ctx, L.start_tab),
                                ws_ptr<int32_t>(ctx, L.ncap_tab), gw, gcap, ws_ptr<int64_t>(ctx, L.gap_row),
                                ws_ptr<int64_t>(ctx, L.gap_brow), ws_ptr<int32_t>(ctx, L.gap_run_end), cut,
                                interest_bits, words);
@@ -345,9 +518,18 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
                            grant_cut, grant_score, job_gap, active, claim);
         SJA_HIP(hipGetLastError(), "k_resolve_init launch");
     }
-    const int64_t cap = params->max_rounds > 0 ? params->max_rounds : int64_t(G < J ? G : J) + 1;
+    // every round that does not end the process grants at least one job, so it
+    // ends by itself within min(G, J) + 1 rounds: a larger cap changes nothing
+    const int64_t natural = int64_t(G < J ? G : J) + 1;
+    const int64_t cap = (params->max_rounds > 0 && params->max_rounds < natural) ? params->max_rounds : natural;
     int32_t result[2] = {0, 0};
-    for (int64_t r = 1; r <= cap; ++r) {
+    bool done = false;
+    if (G > 0 && J > 0) {
+        rc = resolve_with_lists(ctx, st, L, params, wait, sla_class, grant_job, grant_cut, grant_score, job_gap, cap,
+                                result, &done);
+        if (rc != SJA_OK) return rc;
+    }
+    for (int64_t r = 1; !done && r <= cap; ++r) {
         ++result[0];
         int32_t host_counters[2] = {0, 0};
         if (G > 0) {

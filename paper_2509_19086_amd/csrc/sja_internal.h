@@ -32,7 +32,7 @@ struct SelPartial {
 };
 
 // Gap plan header written by k_gap_plan (device memory, int32 each).
-enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanWords = 8 };
+enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanSubBlocks = 3, kPlanWords = 8 };
 
 // Byte offsets of the private tables inside the caller's workspace.
 struct Layout {
@@ -42,16 +42,30 @@ struct Layout {
     size_t gap_w, gap_c, gap_run_end;      // [G+16] int32, in sorted order
     size_t gap_row, gap_brow;              // [G+16] int64: element offsets of a gap's rows
     size_t plan;                           // [kPlanWords] int32 header
-    size_t class_begin, class_chunk0;      // [kMaxClasses+1] int32
-    size_t chunk_begin, chunk_end, chunk_class;  // [chunk_bound] int32
-    size_t start_tab;                      // [chunk_bound * J] int32
+    size_t class_begin, class_chunk0, class_sub0;   // [kMaxClasses+1] int32
+    size_t chunk_begin, chunk_end, chunk_class, chunk_sub;  // [chunk_bound] int32
+    size_t sub_begin, sub_end, sub_class;  // [sub_bound] int32
+    size_t start_tab;                      // [sub_bound * J] int32
     size_t ncap_tab;                       // [kMaxClasses * J] int32
     size_t sel_part;                       // [ceil(J/kSelBlock) * G] SelPartial
     size_t res_cand_job, res_cand_cut;     // [G] int32
     size_t res_cand_score;                 // [G] int64
     size_t res_active;                     // [G] uint8
     size_t res_claim;                      // [J] uint64
-    size_t res_counters;                   // [4] int32
+    size_t res_counters;                   // [16] int32
+    // list-driven grant path
+    size_t g_abase;                        // [J+2] int32
+    size_t g_scan_tmp;                     // tile sums of the scans
+    size_t g_key_hi, g_key_lo;             // [atom_cap] uint64
+    size_t g_perm0, g_perm1, g_rank;       // [atom_cap] uint32
+    size_t g_hist;                         // [256 * ceil(entry_cap/2048)] int32
+    size_t g_ekey0, g_ekey1;               // [entry_cap] uint64
+    size_t g_ej0, g_ej1, g_ea0, g_ea1, g_el0, g_el1;   // [entry_cap] uint32
+    size_t g_list_off;                     // [sub_bound+2] int32
+    size_t g_ptr, g_cand;                  // [G] int32
+    size_t g_flag;                         // [G] uint8
+    size_t g_cnt_lost, g_cnt_cand;         // [min(G,J)+4] int32
+    int64_t atom_cap, entry_cap;
     size_t total;
 };
 
@@ -73,6 +87,16 @@ inline int64_t fit_chunk_bound(int64_t G, int64_t J)
     return (G + gc - 1) / gc + kMaxClasses;
 }
 
+// Sub-blocks: runs of at most 64 sorted positions inside one capacity class;
+// the start tables and the grant lists are kept per sub-block.
+inline int fit_sub_len(int64_t G, int64_t J) { const int gc = fit_chunk_len(G, J); return gc < 64 ? gc : 64; }
+
+inline int64_t fit_sub_bound(int64_t G, int64_t J)
+{
+    const int sb = fit_sub_len(G, J);
+    return (G + sb - 1) / sb + kMaxClasses;
+}
+
 inline Layout make_layout(int64_t G, int64_t J, int64_t S)
 {
     Layout L;
@@ -91,11 +115,17 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.plan = take(kPlanWords * 4);
     L.class_begin = take((kMaxClasses + 1) * 4);
     L.class_chunk0 = take((kMaxClasses + 1) * 4);
+    L.class_sub0 = take((kMaxClasses + 1) * 4);
     const size_t cb = size_t(fit_chunk_bound(G, J));
+    const size_t ub = size_t(fit_sub_bound(G, J));
     L.chunk_begin = take(cb * 4);
     L.chunk_end = take(cb * 4);
     L.chunk_class = take(cb * 4);
-    L.start_tab = take(cb * size_t(J) * 4);
+    L.chunk_sub = take(cb * 4);
+    L.sub_begin = take(ub * 4);
+    L.sub_end = take(ub * 4);
+    L.sub_class = take(ub * 4);
+    L.start_tab = take(ub * size_t(J) * 4);
     L.ncap_tab = take(size_t(kMaxClasses) * size_t(J) * 4);
     size_t job_tiles = size_t((J + kSelBlock - 1) / kSelBlock);
     L.sel_part = take(job_tiles * size_t(G) * sizeof(SelPartial));
@@ -105,6 +135,33 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.res_active = take(size_t(G));
     L.res_claim = take(size_t(J) * 8);
     L.res_counters = take(64);
+    L.atom_cap = S + 8;
+    L.entry_cap = int64_t(ub) * J + 2 * S + 8;
+    const size_t ac = size_t(L.atom_cap), ec = size_t(L.entry_cap);
+    const size_t hist_ints = 256 * ((ec + 2047) / 2048);
+    L.g_abase = take(size_t(J + 2) * 4);
+    L.g_scan_tmp = take(((hist_ints + 2047) / 2048 + size_t(J) / 2048 + ub / 2048 + 16) * 4);
+    L.g_key_hi = take(ac * 8);
+    L.g_key_lo = take(ac * 8);
+    L.g_perm0 = take(ac * 4);
+    L.g_perm1 = take(ac * 4);
+    L.g_rank = take(ac * 4);
+    L.g_hist = take(hist_ints * 4);
+    L.g_ekey0 = take(ec * 8);
+    L.g_ekey1 = take(ec * 8);
+    L.g_ej0 = take(ec * 4);
+    L.g_ej1 = take(ec * 4);
+    L.g_ea0 = take(ec * 4);
+    L.g_ea1 = take(ec * 4);
+    L.g_el0 = take(ec * 4);
+    L.g_el1 = take(ec * 4);
+    L.g_list_off = take((ub + 2) * 4);
+    L.g_ptr = take(size_t(G) * 4);
+    L.g_cand = take(size_t(G) * 4);
+    L.g_flag = take(size_t(G));
+    const size_t rounds_cap = size_t(G < J ? G : J) + 4;
+    L.g_cnt_lost = take(rounds_cap * 4);
+    L.g_cnt_cand = take(rounds_cap * 4);
     L.total = off;
     return L;
 }

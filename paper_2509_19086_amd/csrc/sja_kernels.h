@@ -94,6 +94,7 @@ __global__ __launch_bounds__(256) void k_prepare(
 }  // namespace sja
 
 #include "k_fit.h"
+#include "k_grant.h"
 
 namespace sja {
 
@@ -106,13 +107,6 @@ namespace sja {
 // partial per (job tile, gap); k_select_reduce finishes the arg-max.
 // Key order: hi desc, lo desc, job asc.
 // --------------------------------------------------------------------------
-struct PolicyDev {
-    int policy;
-    int wait_scale;
-    int w0, w1, w2;
-    int class0_override;
-};
-
 __device__ __forceinline__ bool key_better(unsigned long long hi_a, unsigned long long lo_a, int j_a,
                                            unsigned long long hi_b, unsigned long long lo_b, int j_b)
 {
@@ -149,20 +143,7 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     if (usable) {
         if (job_held && job_held[j] >= 0) usable = false;
         base = seg_off[j];
-        const int cls = sla_class ? sla_class[j] : 0;
-        const long long wt = wait ? wait[j] : 0;
-        switch (pol.policy) {
-        case SJA_POLICY_FAIRNESS: mult = (unsigned long long)(pol.wait_scale + wt); break;
-        case SJA_POLICY_SLA:
-            mult = (unsigned long long)(cls == 0 ? pol.w0 : (cls == 1 ? pol.w1 : pol.w2));
-            tier = (pol.class0_override && cls == 0) ? 1 : 0;
-            break;
-        case SJA_POLICY_MIXED:
-            mult = (unsigned long long)(pol.wait_scale + wt);
-            tier = (unsigned long long)(2 - cls);
-            break;
-        default: break;
-        }
+        job_policy(pol, wait, sla_class, j, mult, tier);
     }
     const bool mixed = pol.policy == SJA_POLICY_MIXED;
 

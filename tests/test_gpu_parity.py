@@ -99,7 +99,7 @@ def test_many_capacity_classes(engine, oracle, n_classes):
     wl.C = np.ascontiguousarray(caps[rng.integers(0, n_classes, size=wl.n_gaps)])
     if n_classes == 700:
         wl.C = np.ascontiguousarray(rng.permutation(caps))          # every gap its own capacity
-    full_tick_check(engine, oracle, wl, policies=[2], check_resolve=False)
+    full_tick_check(engine, oracle, wl, policies=[2, 3])
 
 
 def test_round_cap(engine, oracle):
