@@ -208,15 +208,29 @@ __device__ __forceinline__ unsigned long long claim_of(int round, int g)
     return (static_cast<unsigned long long>(round) << 32) | (0xffffffffu - uint32_t(g));
 }
 
-// One round.  First the outcome of round k-1: a gap whose candidate's claim word
-// is its own has won (grant is final), otherwise it lost.  Then, if `propose`,
-// every gap that is still active selects again and claims.
+// Sorted entries as 16-byte records (job, atom, lo | hi << 8, 0): one load per entry.
+__global__ void k_list_pack(const int32_t *n_ptr, const uint32_t *__restrict__ ej,
+                            const uint32_t *__restrict__ ea, const uint32_t *__restrict__ el,
+                            uint4 *__restrict__ rec)
+{
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < *n_ptr) rec[i] = make_uint4(ej[i], ea[i], el[i], 0u);
+}
+
+// One round, one wave per sub-block, one lane per gap position.  First the
+// outcome of round k-1: a gap whose candidate job carries the gap's own claim
+// word has won (the grant is final), otherwise it lost.  Then, if `propose`,
+// every lane that still needs a job walks on from its own pointer, eight
+// records per memory round trip, to the first entry that covers it and whose
+// job is not held.  state[s] = (pointer, candidate job, candidate atom, flag)
+// with flag 0 = active, 1 = granted, 2 = no candidate left.
+constexpr int kWalk = 8;
+
 __global__ __launch_bounds__(256) void k_grant_round(
     int round, int propose, int n_jobs, PolicyDev pol, const int32_t *__restrict__ plan,
     const int32_t *__restrict__ sub_begin, const int32_t *__restrict__ sub_end,
     const int32_t *__restrict__ list_off, const int32_t *__restrict__ gap_order,
-    const uint32_t *__restrict__ ej, const uint32_t *__restrict__ ea, const uint32_t *__restrict__ el,
-    unsigned long long *claim, int32_t *st_ptr, int32_t *st_cand, uint8_t *st_flag, int32_t *cnt_lost,
+    const uint4 *__restrict__ rec, unsigned long long *claim, int4 *state, int32_t *cnt_lost,
     int32_t *cnt_cand, const int64_t *__restrict__ seg_off, const int2 *__restrict__ atom_dp,
     const int2 *__restrict__ atom_db, const int32_t *__restrict__ wait,
     const uint8_t *__restrict__ sla_class, int32_t *grant_job, int32_t *grant_cut, int64_t *grant_score,
@@ -228,60 +242,82 @@ __global__ __launch_bounds__(256) void k_grant_round(
     const int b0 = sub_begin[u];
     const bool valid = lane < sub_end[u] - b0;
     const int s = b0 + lane;
-    int g = 0, flag = 2, cand_e = -1, e = 0;
+    const int list_end = list_off[u + 1];
+    int g = 0;
+    int4 st = make_int4(list_off[u], -1, -1, valid ? 0 : 2);
     if (valid) {
         g = gap_order[s];
-        if (round == 1) { flag = 0; e = list_off[u]; }
-        else { flag = st_flag[s]; cand_e = st_cand[s]; e = st_ptr[s]; }
+        if (round > 1) st = state[s];
     }
     bool lost = false;
-    if (flag == 0 && cand_e >= 0) {
-        const int j = int(ej[cand_e]);
+    if (st.w == 0 && st.y >= 0) {
+        const int j = st.y;
         if (claim[j] == claim_of(round - 1, g)) {
-            const int a = int(ea[cand_e]);
             const int64_t base = seg_off[j];
-            const int2 v = atom_dp[base + a];
+            const int2 v = atom_dp[base + st.z];
             unsigned long long mult, tier;
             job_policy(pol, wait, sla_class, j, mult, tier);
             grant_job[g] = j;
-            grant_cut[g] = atom_db[base + a].y;
+            grant_cut[g] = atom_db[base + st.z].y;
             grant_score[g] = int64_t((unsigned long long)v.x * (unsigned long long)v.y * mult);
             job_gap[j] = g;
-            st_flag[s] = 1;
-            flag = 1;
+            st.w = 1;
+            state[s].w = 1;
         } else {
             lost = true;
         }
     }
     bool cand = false;
-    if (flag == 0 && propose) {
-        const int end = list_off[u + 1];
-        int found = -1;
-        while (e < end) {
-            const uint32_t lh = el[e];
-            if (lane >= int(lh & 255u) && lane < int(lh >> 8)) {
-                const uint32_t stamp = uint32_t(claim[ej[e]] >> 32);
-                if (stamp == 0 || stamp >= uint32_t(round)) { found = e; break; }
+    int cand_job = -1;
+    if (st.w == 0 && propose) {
+        int e = st.x, found = -1, found_j = -1, found_a = -1;
+        while (e < list_end && found < 0) {
+            uint4 r[kWalk];
+            unsigned long long c[kWalk];
+#pragma unroll
+            for (int t = 0; t < kWalk; ++t) r[t] = rec[min(e + t, list_end - 1)];
+#pragma unroll
+            for (int t = 0; t < kWalk; ++t) {
+                const bool covers = e + t < list_end && lane >= int(r[t].z & 255u) && lane < int(r[t].z >> 8);
+                c[t] = covers ? claim[r[t].x] : ~0ull;        // a huge stamp of an earlier round: "held"
+                if (!covers) r[t].z = 0;
             }
-            ++e;
+#pragma unroll
+            for (int t = 0; t < kWalk; ++t) {
+                const uint32_t stamp = uint32_t(c[t] >> 32);
+                const bool free_job = r[t].z != 0 && (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu));
+                if (found < 0 && free_job) { found = e + t; found_j = int(r[t].x); found_a = int(r[t].y); }
+            }
+            e += kWalk;
         }
         if (found >= 0) {
-            st_cand[s] = found;
-            st_ptr[s] = found + 1;
-            if (round == 1) st_flag[s] = 0;
-            atomicMax(&claim[ej[found]], claim_of(round, g));
+            state[s] = make_int4(found + 1, found_j, found_a, 0);
             cand = true;
+            cand_job = found_j;
         } else {
-            st_cand[s] = -1;
-            st_ptr[s] = end;
-            st_flag[s] = 2;
+            state[s] = make_int4(list_end, -1, -1, 2);
         }
     }
-    const unsigned long long ml = __ballot(lost), mc = __ballot(cand);
-    if (lane == 0) {
-        if (ml) atomicAdd(&cnt_lost[round - 1], __popcll(ml));
-        if (mc) atomicAdd(&cnt_cand[round], __popcll(mc));
+    // Claims.  Most gaps of a batch name the same few jobs in a round, so the
+    // lanes of a wave that name one job first agree on their lowest gap index,
+    // and a claim that the job's word already beats is not sent at all.
+    unsigned long long todo = __ballot(cand);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int job = __builtin_amdgcn_readlane(cand_job, leader);
+        const bool mine = cand && cand_job == job;
+        unsigned int best = mine ? 0xffffffffu - uint32_t(g) : 0u;       // larger = lower gap index
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) best = max(best, (unsigned int)__shfl_xor(int(best), d, kWave));
+        if (lane == leader) {
+            const unsigned long long word = (static_cast<unsigned long long>(round) << 32) | best;
+            if (claim[job] < word) atomicMax(&claim[job], word);
+        }
+        todo &= ~__ballot(mine);
     }
+    // the host only asks whether anybody lost / anybody selected in a round
+    if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;
+    if (__ballot(cand) && lane == 0) cnt_cand[round] = 1;
 }
 
 }  // namespace sja

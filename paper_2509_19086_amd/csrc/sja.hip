@@ -225,6 +225,13 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
         if (rc != SJA_OK) return rc;
     }
     const int fb = eflip ? 1 : 0;
+    // records of the sorted lists; the key buffer that is not in use any more holds them (16 B per entry)
+    uint4 *rec = reinterpret_cast<uint4 *>(ws_ptr<char>(ctx, L.g_ekey0));
+    if (n_entries > 0) {
+        hipLaunchKernelGGL(k_list_pack, dim3(unsigned((n_entries + 255) / 256)), dim3(256), 0, st, counters, ej[fb],
+                           ea[fb], el[fb], rec);
+        SJA_HIP(hipGetLastError(), "k_list_pack launch");
+    }
 
     // 4. rounds, in batches between looks at the counters
     int32_t *cnt_lost = ws_ptr<int32_t>(ctx, L.g_cnt_lost), *cnt_cand = ws_ptr<int32_t>(ctx, L.g_cnt_cand);
@@ -234,9 +241,8 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(hipGetLastError(), "counter fill launch");
     auto launch_round = [&](int64_t k, int propose) {
         hipLaunchKernelGGL(k_grant_round, dim3((n_subs + 3) / 4), dim3(256), 0, st, int(k), propose, J, pol, plan,
-                           sub_begin, sub_end, list_off, ws_ptr<int32_t>(ctx, L.gap_order), ej[fb], ea[fb], el[fb],
-                           ws_ptr<unsigned long long>(ctx, L.res_claim), ws_ptr<int32_t>(ctx, L.g_ptr),
-                           ws_ptr<int32_t>(ctx, L.g_cand), ws_ptr<uint8_t>(ctx, L.g_flag), cnt_lost, cnt_cand,
+                           sub_begin, sub_end, list_off, ws_ptr<int32_t>(ctx, L.gap_order), rec,
+                           ws_ptr<unsigned long long>(ctx, L.res_claim), ws_ptr<int4>(ctx, L.g_state), cnt_lost, cnt_cand,
                            ctx->seg_off, atom_dp, atom_db, wait, sla_class, grant_job, grant_cut, grant_score, job_gap);
         return hipGetLastError();
     };

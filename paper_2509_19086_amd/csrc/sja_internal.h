@@ -62,8 +62,7 @@ struct Layout {
     size_t g_ekey0, g_ekey1;               // [entry_cap] uint64
     size_t g_ej0, g_ej1, g_ea0, g_ea1, g_el0, g_el1;   // [entry_cap] uint32
     size_t g_list_off;                     // [sub_bound+2] int32
-    size_t g_ptr, g_cand;                  // [G] int32
-    size_t g_flag;                         // [G] uint8
+    size_t g_state;                        // [G] int4: pointer, candidate job, candidate atom, flag
     size_t g_cnt_lost, g_cnt_cand;         // [min(G,J)+4] int32
     int64_t atom_cap, entry_cap;
     size_t total;
@@ -156,9 +155,7 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.g_el0 = take(ec * 4);
     L.g_el1 = take(ec * 4);
     L.g_list_off = take((ub + 2) * 4);
-    L.g_ptr = take(size_t(G) * 4);
-    L.g_cand = take(size_t(G) * 4);
-    L.g_flag = take(size_t(G));
+    L.g_state = take(size_t(G) * 16);
     const size_t rounds_cap = size_t(G < J ? G : J) + 4;
     L.g_cnt_lost = take(rounds_cap * 4);
     L.g_cnt_cand = take(rounds_cap * 4);
