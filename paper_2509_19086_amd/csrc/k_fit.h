@@ -307,7 +307,8 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     int a = 0;       // atoms whose running duration fits the current window
     int hi = 0;      // atoms [a, hi) are staged in the LDS window
     int cur = -1;    // boundary of atom a-1, or -1
-    int nd = 0, nb = 0;   // atom a (valid while a < hi)
+    int nd = 0, nb = 0;     // atom a     (meaningful while a < hi)
+    int nd2 = 0, nb2 = 0;   // atom a + 1 (meaningful while a + 1 < hi)
     int c_cur = 0;
 
     auto init = [&](int s) {
@@ -322,6 +323,10 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         cur = a > 0 ? db[a - 1].y : -1;
         hi = a;
     };
+    auto reload = [&]() {
+        const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y;
+        const int2 y = win[(a + 1) & (CAP - 1)][tid]; nd2 = y.x; nb2 = y.y;
+    };
     auto topup = [&]() {
         const int want = min(a + CAP, n_cap);
         int2 v[CAP];
@@ -332,22 +337,32 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         for (int t = 0; t < CAP; ++t)
             if (hi + t < want) win[(hi + t) & (CAP - 1)][tid] = v[t];
         hi = max(hi, want);
-        if (a < hi) { const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y; }
+        reload();
     };
+    // Moves every lane past the atoms its window w has reached.  Branch-free per
+    // lane: the next two atoms are kept in registers, so a single advance needs
+    // no LDS answer before the loop condition is known.
     auto advance = [&](int w) {
-        while (a < hi && nd <= w) {
-            cur = nb;
-            ++a;
-            if (a < hi) {
-                const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y;
-            } else if (a < n_cap) {
-                // the window ran dry inside a period: refill at once (rare)
+        for (;;) {
+            bool adv = a < hi && nd <= w;
+            while (__any(adv)) {
+                cur = adv ? nb : cur;
+                a += adv ? 1 : 0;
+                nd = adv ? nd2 : nd;
+                nb = adv ? nb2 : nb;
+                const int2 y = win[(a + 1) & (CAP - 1)][tid]; nd2 = y.x; nb2 = y.y;
+                adv = a < hi && nd <= w;
+            }
+            const bool dry = a == hi && a < n_cap;
+            if (!__any(dry)) break;
+            // a window ran dry inside a period: refill at once (rare)
+            if (dry) {
                 const int want = min(a + CAP, n_cap);
                 for (int idx = hi; idx < want; ++idx) win[idx & (CAP - 1)][tid] = db[idx];
                 hi = want;
-                const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y;
-                wait_vmem();
+                reload();
             }
+            wait_vmem();
         }
     };
     auto emit = [&](int s, int64_t row) {

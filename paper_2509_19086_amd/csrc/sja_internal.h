@@ -14,7 +14,7 @@ namespace sja {
 constexpr int kWave = 64;
 
 // ---- tiling constants shared by host launch code and kernels -------------
-constexpr int kFitBlock = 512;        // threads per fit block, one job per thread
+constexpr int kFitBlock = 256;        // threads per fit block, one job per thread
 constexpr int kFitMaxChunk = 256;     // most sorted gap positions one fit block walks
 constexpr int kFitWindow = 8;         // atoms per job staged ahead in LDS (power of two)
 constexpr int kFitPeriod = 16;        // steps between window top-ups (multiple of 4)
