@@ -78,11 +78,23 @@ def main():
     ap.add_argument("--workload", default="stress",
                     help="named config (default: stress, the largest single-GPU config)")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--cpu-sample-gaps", type=int, default=512)
+    ap.add_argument("--cpu-sample-gaps", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-rounds", type=int, default=None,
                     help="override the config's resolve round cap (0 = until stable)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy three times (reference reading for "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE) and exit")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.arange(2**28, dtype=torch.int32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: this path uses no second GPU, run with --gpus 1",
               file=sys.stderr)

@@ -310,6 +310,8 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     int nd = 0, nb = 0;     // atom a     (meaningful while a < hi)
     int nd2 = 0, nb2 = 0;   // atom a + 1 (meaningful while a + 1 < hi)
     int c_cur = 0;
+    unsigned long long dry_mask = 0;   // lanes with hi < n_cap: reaching hi may leave atoms unpassed
+    bool all_in = false;               // every live lane of the wave is interested (stays so within a class)
 
     auto init = [&](int s) {
         c_cur = gap_c[s];
@@ -322,6 +324,7 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         }
         cur = a > 0 ? db[a - 1].y : -1;
         hi = a;
+        all_in = false;
     };
     auto reload = [&]() {
         const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y;
@@ -339,41 +342,57 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         hi = max(hi, want);
         reload();
     };
-    // Moves every lane past the atoms its window w has reached.  Branch-free per
-    // lane: the next two atoms are kept in registers, so a single advance needs
-    // no LDS answer before the loop condition is known.
-    auto advance = [&](int w) {
-        for (;;) {
-            bool adv = a < hi && nd <= w;
-            while (__any(adv)) {
+    const unsigned long long live_mask = __ballot(live);
+    if (bits)   // interest words default to "all interested"; steps before that holds overwrite them
+        for (int t = tid & (kWave - 1); t < s_end - s_begin; t += kWave) bal[t][wave] = live_mask;
+    constexpr unsigned ROW = BLOCK * sizeof(int2);     // bytes per window slot row (a power of two)
+    static_assert((ROW & (ROW - 1)) == 0, "BLOCK must be a power of two");
+    const unsigned lds_lane = unsigned(tid) * unsigned(sizeof(int2));
+    // One step: move every lane past the atoms that window w has reached, then
+    // store.  The body is predicated rather than branched per lane, and the next
+    // two atoms of each lane sit in registers, so no LDS answer is needed before
+    // the loop condition is known; it repeats only while some lane passes a
+    // further atom.
+    auto step = [&](int w, int s, int64_t row) {
+        bool adv = a < hi && nd <= w;
+        if (__any(adv)) {
+            do {
                 cur = adv ? nb : cur;
                 a += adv ? 1 : 0;
                 nd = adv ? nd2 : nd;
                 nb = adv ? nb2 : nb;
-                const int2 y = win[(a + 1) & (CAP - 1)][tid]; nd2 = y.x; nb2 = y.y;
+                {   // atom a + 1 from the circular window: slot = (a + 1) mod CAP
+                    const unsigned off = (unsigned(a) * ROW + (ROW + lds_lane)) & (CAP * ROW - 1u);
+                    const int2 y = *reinterpret_cast<const int2 *>(reinterpret_cast<const char *>(&win[0][0]) + off);
+                    nd2 = y.x; nb2 = y.y;
+                }
+                if (__ballot(a == hi) & dry_mask) {
+                    // a window ran dry inside a period: refill at once (rare)
+                    if (a == hi && hi < n_cap) {
+                        const int want = min(a + CAP, n_cap);
+                        for (int idx = hi; idx < want; ++idx) win[idx & (CAP - 1)][tid] = db[idx];
+                        hi = want;
+                        reload();
+                    }
+                    dry_mask = __ballot(hi < n_cap);
+                    wait_vmem();
+                }
                 adv = a < hi && nd <= w;
-            }
-            const bool dry = a == hi && a < n_cap;
-            if (!__any(dry)) break;
-            // a window ran dry inside a period: refill at once (rare)
-            if (dry) {
-                const int want = min(a + CAP, n_cap);
-                for (int idx = hi; idx < want; ++idx) win[idx & (CAP - 1)][tid] = db[idx];
-                hi = want;
-                reload();
-            }
-            wait_vmem();
+            } while (__any(adv));
         }
-    };
-    auto emit = [&](int s, int64_t row) {
         (cut + row)[j] = cur;
-        if (bits) bal[s - s_begin][wave] = __ballot(live && cur >= 0);
+        if (bits && !all_in) {
+            const unsigned long long m = __ballot(cur >= 0) & live_mask;
+            bal[s - s_begin][wave] = m;
+            all_in = m == live_mask;
+        }
     };
 
     for (int s0 = s_begin; s0 < s_end; s0 += PERIOD) {
         const int s1 = min(s_end, s0 + PERIOD);
         if (s0 == s_begin || gap_c[s0] != c_cur) init(s0);
         topup();
+        dry_mask = __ballot(hi < n_cap);
         wait_vmem();   // below, until the next period, no global load is pending
         if (s1 - s0 == PERIOD && gap_run_end[s0] >= s1) {
 #pragma unroll
@@ -382,16 +401,12 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
                 const int64_t rv[4] = {gap_row[s0 + u4], gap_row[s0 + u4 + 1], gap_row[s0 + u4 + 2],
                                        gap_row[s0 + u4 + 3]};
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (__any(a < hi && nd <= wv[u])) advance(wv[u]);
-                    emit(s0 + u4 + u, rv[u]);
-                }
+                for (int u = 0; u < 4; ++u) step(wv[u], s0 + u4 + u, rv[u]);
             }
         } else {
             for (int s = s0; s < s1; ++s) {
-                if (gap_c[s] != c_cur) { init(s); topup(); wait_vmem(); }
-                advance(gap_w[s]);
-                emit(s, gap_row[s]);
+                if (gap_c[s] != c_cur) { init(s); topup(); dry_mask = __ballot(hi < n_cap); wait_vmem(); }
+                step(gap_w[s], s, gap_row[s]);
             }
         }
     }
