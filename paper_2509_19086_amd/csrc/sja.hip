@@ -89,7 +89,8 @@ int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const 
         const int n_chunks = (G + kSelGapChunk - 1) / kSelGapChunk;
         const int tiles8 = (job_tiles + 7) / 8 * 8;
         const unsigned grid = unsigned(tiles8) * unsigned(n_chunks);
-        hipLaunchKernelGGL(k_select_pass, dim3(grid), dim3(kSelBlock), 0, st, J, G, n_chunks,
+        auto kern = params->policy == SJA_POLICY_MIXED ? k_select_pass<true> : k_select_pass<false>;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kSelBlock), 0, st, J, G, n_chunks,
                            to_dev(params), ctx->seg_off, ctx->pre_dur, ctx->pre_peak, ctx->cut,
                            ws_ptr<int32_t>(ctx, L.gap_order), wait, sla_class, job_held, gap_active,
                            ws_ptr<SelPartial>(ctx, L.sel_part));

@@ -115,6 +115,10 @@ __device__ __forceinline__ bool key_better(unsigned long long hi_a, unsigned lon
     return j_a < j_b;
 }
 
+// Steps reduced together by one wave (see k_select_pass).
+constexpr int kSelBatch = 16;
+
+template <bool MIXED>
 __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     int n_jobs, int n_gaps, int n_chunks, PolicyDev pol, const int64_t *__restrict__ seg_off,
     const int32_t *__restrict__ pre_dur, const int32_t *__restrict__ pre_peak,
@@ -123,10 +127,14 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     const int32_t *__restrict__ job_held, const uint8_t *__restrict__ gap_active,
     SelPartial *__restrict__ part)
 {
-    __shared__ unsigned long long s_hi[kSelBlock / kWave][kSelGapChunk];
-    __shared__ unsigned long long s_lo[kSelBlock / kWave][kSelGapChunk];
-    __shared__ int s_job[kSelBlock / kWave][kSelGapChunk];
-    __shared__ int s_cut[kSelBlock / kWave][kSelGapChunk];
+    constexpr int WAVES = kSelBlock / kWave;
+    constexpr int ROW = kWave + 1;                       // padded: a column read hits distinct banks
+    __shared__ unsigned long long s_key[WAVES][kSelBatch][ROW];   // one batch of per-lane keys per wave
+    __shared__ unsigned long long s_mult[WAVES][kWave];           // per-lane score multiplier (MIXED ties)
+    __shared__ unsigned long long s_hi[WAVES][kSelGapChunk];
+    __shared__ unsigned long long s_lo[WAVES][kSelGapChunk];
+    __shared__ int s_job[WAVES][kSelGapChunk];
+    __shared__ int s_cut[WAVES][kSelGapChunk];
 
     const int xcd = blockIdx.x & 7;
     const int k = blockIdx.x >> 3;
@@ -136,6 +144,7 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     const int j = job_tile * kSelBlock + threadIdx.x;
     const int wave = threadIdx.x / kWave;
     const int lane = lane_id();
+    const int wave_job0 = job_tile * kSelBlock + wave * kWave;
 
     bool usable = j < n_jobs;
     int64_t base = 0;
@@ -145,40 +154,87 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
         base = seg_off[j];
         job_policy(pol, wait, sla_class, j, mult, tier);
     }
-    const bool mixed = pol.policy == SJA_POLICY_MIXED;
+    s_mult[wave][lane] = mult;
 
     const int s_begin = chunk * kSelGapChunk;
     const int s_end = min(n_gaps, s_begin + kSelGapChunk);
     int last_cut = -1;
-    unsigned long long hi = 0, lo = 0;
-    for (int s = s_begin; s < s_end; ++s) {
-        const int g = gap_order[s];
-        const int slot = s - s_begin;
-        if (gap_active && !gap_active[g]) {
-            if (lane == 0) { s_hi[wave][slot] = 0; s_lo[wave][slot] = 0; s_job[wave][slot] = -1; s_cut[wave][slot] = -1; }
-            continue;
-        }
-        int c = usable ? cut[int64_t(g) * n_jobs + j] : -1;
-        if (c >= 0 && c != last_cut) {
-            const unsigned long long F =
-                (unsigned long long)pre_dur[base + c - 1] * (unsigned long long)pre_peak[base + c - 1];
-            hi = ((tier << 62) | (F * mult)) + 1ull;
-            lo = mixed ? F : 0ull;
-            last_cut = c;
-        }
-        unsigned long long bh = c >= 0 ? hi : 0ull;
-        unsigned long long bl = c >= 0 ? lo : 0ull;
-        int bj = c >= 0 ? j : INT32_MAX;
-        int bc = c;
+    unsigned long long hi = 0;
+    // secondary score of a key (MIXED: F = score / multiplier), only needed to break ties
+    auto second = [&](unsigned long long key, int src) -> unsigned long long {
+        return MIXED ? ((key - 1ull) & ((1ull << 62) - 1ull)) / s_mult[wave][src] : 0ull;
+    };
+    for (int s0 = s_begin; s0 < s_end; s0 += kSelBatch) {
+        const int n_step = min(kSelBatch, s_end - s0);
+        // phase 1: every lane's key for each step of the batch (cut rows are read coalesced)
+        int cv[kSelBatch];
 #pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const unsigned long long oh = __shfl_xor(bh, d, kWave);
-            const unsigned long long ol = __shfl_xor(bl, d, kWave);
-            const int oj = __shfl_xor(bj, d, kWave);
-            const int oc = __shfl_xor(bc, d, kWave);
-            if (key_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; bc = oc; }
+        for (int t = 0; t < kSelBatch; ++t) {
+            cv[t] = -1;
+            if (t < n_step && usable) {
+                const int g = gap_order[s0 + t];
+                if (!gap_active || gap_active[g]) cv[t] = cut[int64_t(g) * n_jobs + j];
+            }
         }
-        if (lane == 0) { s_hi[wave][slot] = bh; s_lo[wave][slot] = bl; s_job[wave][slot] = bj; s_cut[wave][slot] = bc; }
+        // a job's cut rarely changes from one sorted position to the next: only the changes
+        // gather (duration, peak), all of a batch's gathers in flight together
+        int dv[kSelBatch], pv[kSelBatch];
+        bool fresh[kSelBatch];
+        int prev = last_cut;
+#pragma unroll
+        for (int t = 0; t < kSelBatch; ++t) {
+            const int c = cv[t];
+            fresh[t] = c >= 0 && c != prev;
+            if (fresh[t]) {
+                dv[t] = pre_dur[base + c - 1];
+                pv[t] = pre_peak[base + c - 1];
+            }
+            prev = c >= 0 ? c : prev;
+        }
+        last_cut = prev;
+#pragma unroll
+        for (int t = 0; t < kSelBatch; ++t) {
+            if (fresh[t]) {
+                const unsigned long long F = (unsigned long long)dv[t] * (unsigned long long)pv[t];
+                hi = ((tier << 62) | (F * mult)) + 1ull;
+            }
+            s_key[wave][t][lane] = cv[t] >= 0 ? hi : 0ull;
+        }
+        // phase 2: lane l reduces step (l % 16) over lanes [16 * (l / 16), +16), then the four
+        // quarter results of a step are combined across lanes l, l+16, l+32, l+48
+        const int t = lane & (kSelBatch - 1), q = lane / kSelBatch;
+        unsigned long long bh = 0;
+        int bsrc = kWave;
+#pragma unroll
+        for (int i = 0; i < kSelBatch; ++i) {
+            const int src = q * kSelBatch + i;
+            const unsigned long long oh = s_key[wave][t][src];
+            bool better = oh > bh;
+            if (MIXED && oh == bh && oh != 0) better = second(oh, src) > second(bh, bsrc);
+            if (better) { bh = oh; bsrc = src; }     // equal keys keep the lower lane = lower job id
+        }
+#pragma unroll
+        for (int d = kSelBatch; d < kWave; d <<= 1) {
+            const unsigned long long oh = __shfl_xor(bh, d, kWave);
+            const int osrc = __shfl_xor(bsrc, d, kWave);
+            bool better = oh > bh || (oh == bh && osrc < bsrc);
+            if (MIXED && oh == bh && oh != 0) {
+                const unsigned long long fo = second(oh, osrc), fb = second(bh, bsrc);
+                better = fo > fb || (fo == fb && osrc < bsrc);
+            }
+            if (better) { bh = oh; bsrc = osrc; }
+        }
+        if (lane < n_step) {
+            const int slot = s0 - s_begin + lane;
+            int wj = -1, wc = -1;
+            unsigned long long wl = 0;
+            if (bh) {
+                wj = wave_job0 + bsrc;
+                wc = cut[int64_t(gap_order[s0 + lane]) * n_jobs + wj];
+                wl = second(bh, bsrc);
+            }
+            s_hi[wave][slot] = bh; s_lo[wave][slot] = wl; s_job[wave][slot] = bh ? wj : INT32_MAX; s_cut[wave][slot] = wc;
+        }
     }
     __syncthreads();
     for (int slot = threadIdx.x; slot < s_end - s_begin; slot += kSelBlock) {
@@ -186,7 +242,7 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
         int bj = s_job[0][slot], bc = s_cut[0][slot];
         if (bh == 0) bj = INT32_MAX;
 #pragma unroll
-        for (int w = 1; w < kSelBlock / kWave; ++w) {
+        for (int w = 1; w < WAVES; ++w) {
             const unsigned long long oh = s_hi[w][slot], ol = s_lo[w][slot];
             const int oj = oh ? s_job[w][slot] : INT32_MAX;
             if (key_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; bc = s_cut[w][slot]; }
