@@ -282,7 +282,9 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     static_assert((CAP & (CAP - 1)) == 0 && PERIOD % 4 == 0 && BLOCK % kWave == 0, "tile shape");
     constexpr int WAVES = BLOCK / kWave;
     __shared__ int2 win[CAP][BLOCK];
-    __shared__ unsigned long long bal[kFitMaxChunk][WAVES];
+    static_assert(sizeof(int2) * CAP * BLOCK >= sizeof(unsigned long long) * kFitMaxChunk * WAVES,
+                  "the interest words reuse the window memory at the end");
+    static_assert(kFitMaxChunk <= 4 * kWave, "four interest words per lane cover a chunk");
 
     // Blocks of one job tile sit on one XCD (block ids are dealt round-robin
     // over the 8 XCDs): its atoms and tables stay in that XCD's L2.
@@ -343,8 +345,11 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         reload();
     };
     const unsigned long long live_mask = __ballot(live);
-    if (bits)   // interest words default to "all interested"; steps before that holds overwrite them
-        for (int t = tid & (kWave - 1); t < s_end - s_begin; t += kWave) bal[t][wave] = live_mask;
+    // Interest words of this wave, one per step, kept in registers until the block
+    // is done: lane l holds steps 4l .. 4l+3.  They default to "all interested";
+    // the steps before that holds overwrite them.
+    const int lane = tid & (kWave - 1);
+    unsigned long long bw[4] = {live_mask, live_mask, live_mask, live_mask};
     constexpr unsigned ROW = BLOCK * sizeof(int2);     // bytes per window slot row (a power of two)
     static_assert((ROW & (ROW - 1)) == 0, "BLOCK must be a power of two");
     const unsigned lds_lane = unsigned(tid) * unsigned(sizeof(int2));
@@ -353,7 +358,8 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     // two atoms of each lane sit in registers, so no LDS answer is needed before
     // the loop condition is known; it repeats only while some lane passes a
     // further atom.
-    auto step = [&](int w, int s, int64_t row) {
+    // q = (s - s_begin) % 4 (a compile-time constant on the unrolled path)
+    auto step = [&](int w, int s, int64_t row, int q) {
         bool adv = a < hi && nd <= w;
         if (__any(adv)) {
             do {
@@ -383,7 +389,10 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         (cut + row)[j] = cur;
         if (bits && !all_in) {
             const unsigned long long m = __ballot(cur >= 0) & live_mask;
-            bal[s - s_begin][wave] = m;
+            const bool mine = lane == ((s - s_begin) >> 2);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (i == q) bw[i] = mine ? m : bw[i];
             all_in = m == live_mask;
         }
     };
@@ -401,21 +410,26 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
                 const int64_t rv[4] = {gap_row[s0 + u4], gap_row[s0 + u4 + 1], gap_row[s0 + u4 + 2],
                                        gap_row[s0 + u4 + 3]};
 #pragma unroll
-                for (int u = 0; u < 4; ++u) step(wv[u], s0 + u4 + u, rv[u]);
+                for (int u = 0; u < 4; ++u) step(wv[u], s0 + u4 + u, rv[u], u);   // s0 - s_begin is a multiple of 4
             }
         } else {
             for (int s = s0; s < s1; ++s) {
                 if (gap_c[s] != c_cur) { init(s); topup(); dry_mask = __ballot(hi < n_cap); wait_vmem(); }
-                step(gap_w[s], s, gap_row[s]);
+                step(gap_w[s], s, gap_row[s], (s - s_begin) & 3);
             }
         }
     }
 
     if (bits) {
         // one interest row piece per gap position: WAVES * 8 contiguous bytes
+        __syncthreads();      // every wave is done with the window: its memory now collects the words
+        unsigned long long *bal = reinterpret_cast<unsigned long long *>(&win[0][0]);   // [step][wave]
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (lane * 4 + q < s_end - s_begin) bal[(lane * 4 + q) * WAVES + wave] = bw[q];
         __syncthreads();
         constexpr int WPR = 2 * WAVES;
-        const uint32_t *bal32 = reinterpret_cast<const uint32_t *>(&bal[0][0]);
+        const uint32_t *bal32 = reinterpret_cast<const uint32_t *>(bal);
         const int word0 = (job_tile * BLOCK) >> 5;
         const int total = (s_end - s_begin) * WPR;
         for (int i = tid; i < total; i += BLOCK) {
