@@ -249,19 +249,19 @@ __global__ __launch_bounds__(256) void k_grant_round(
         g = gap_order[s];
         if (round > 1) st = state[s];
     }
+    // In flight together: the claim word of last round's candidate and, speculatively,
+    // the first records of the walk that follows if the gap lost.
+    const bool may_walk = st.w == 0 && propose != 0;
+    uint4 r[kWalk];
+    if (may_walk) {
+#pragma unroll
+        for (int t = 0; t < kWalk; ++t) r[t] = rec[max(min(st.x + t, list_end - 1), 0)];
+    }
+    const unsigned long long last_word = (st.w == 0 && st.y >= 0) ? claim[st.y] : 0ull;
     bool lost = false;
     if (st.w == 0 && st.y >= 0) {
-        const int j = st.y;
-        if (claim[j] == claim_of(round - 1, g)) {
-            const int64_t base = seg_off[j];
-            const int2 v = atom_dp[base + st.z];
-            unsigned long long mult, tier;
-            job_policy(pol, wait, sla_class, j, mult, tier);
-            grant_job[g] = j;
-            grant_cut[g] = atom_db[base + st.z].y;
-            grant_score[g] = int64_t((unsigned long long)v.x * (unsigned long long)v.y * mult);
-            job_gap[j] = g;
-            st.w = 1;
+        if (last_word == claim_of(round - 1, g)) {
+            st.w = 1;                  // won: final; k_grant_finish writes the grant itself
             state[s].w = 1;
         } else {
             lost = true;
@@ -269,13 +269,11 @@ __global__ __launch_bounds__(256) void k_grant_round(
     }
     bool cand = false;
     int cand_job = -1;
+    unsigned long long cand_word = 0;      // the candidate job's claim word as the walk saw it
     if (st.w == 0 && propose) {
         int e = st.x, found = -1, found_j = -1, found_a = -1;
-        while (e < list_end && found < 0) {
-            uint4 r[kWalk];
+        while (e < list_end) {
             unsigned long long c[kWalk];
-#pragma unroll
-            for (int t = 0; t < kWalk; ++t) r[t] = rec[min(e + t, list_end - 1)];
 #pragma unroll
             for (int t = 0; t < kWalk; ++t) {
                 const bool covers = e + t < list_end && lane >= int(r[t].z & 255u) && lane < int(r[t].z >> 8);
@@ -286,9 +284,12 @@ __global__ __launch_bounds__(256) void k_grant_round(
             for (int t = 0; t < kWalk; ++t) {
                 const uint32_t stamp = uint32_t(c[t] >> 32);
                 const bool free_job = r[t].z != 0 && (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu));
-                if (found < 0 && free_job) { found = e + t; found_j = int(r[t].x); found_a = int(r[t].y); }
+                if (found < 0 && free_job) { found = e + t; found_j = int(r[t].x); found_a = int(r[t].y); cand_word = c[t]; }
             }
             e += kWalk;
+            if (found >= 0 || e >= list_end) break;
+#pragma unroll
+            for (int t = 0; t < kWalk; ++t) r[t] = rec[min(e + t, list_end - 1)];
         }
         if (found >= 0) {
             state[s] = make_int4(found + 1, found_j, found_a, 0);
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(256) void k_grant_round(
     }
     // Claims.  Most gaps of a batch name the same few jobs in a round, so the
     // lanes of a wave that name one job first agree on their lowest gap index,
-    // and a claim that the job's word already beats is not sent at all.
+    // and a claim that the job's word (as the walk read it) already beats is not sent.
     unsigned long long todo = __ballot(cand);
     while (todo) {
         const int leader = __ffsll((long long)todo) - 1;
@@ -311,13 +312,37 @@ __global__ __launch_bounds__(256) void k_grant_round(
         for (int d = 1; d < kWave; d <<= 1) best = max(best, (unsigned int)__shfl_xor(int(best), d, kWave));
         if (lane == leader) {
             const unsigned long long word = (static_cast<unsigned long long>(round) << 32) | best;
-            if (claim[job] < word) atomicMax(&claim[job], word);
+            if (cand_word < word) atomicMax(&claim[job], word);
         }
         todo &= ~__ballot(mine);
     }
     // the host only asks whether anybody lost / anybody selected in a round
     if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;
     if (__ballot(cand) && lane == 0) cnt_cand[round] = 1;
+}
+
+// After the last round: the grants themselves.  A granted position still holds
+// its winning (job, atom) in its state.
+__global__ void k_grant_finish(int n_gaps, PolicyDev pol, const int32_t *__restrict__ gap_order,
+                               const int4 *__restrict__ state, const int64_t *__restrict__ seg_off,
+                               const int2 *__restrict__ atom_dp, const int2 *__restrict__ atom_db,
+                               const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
+                               int32_t *grant_job, int32_t *grant_cut, int64_t *grant_score,
+                               int32_t *job_gap)
+{
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n_gaps) return;
+    const int4 st = state[s];
+    if (st.w != 1) return;
+    const int g = gap_order[s], j = st.y;
+    const int64_t base = seg_off[j];
+    const int2 v = atom_dp[base + st.z];
+    unsigned long long mult, tier;
+    job_policy(pol, wait, sla_class, j, mult, tier);
+    grant_job[g] = j;
+    grant_cut[g] = atom_db[base + st.z].y;
+    grant_score[g] = int64_t((unsigned long long)v.x * (unsigned long long)v.y * mult);
+    job_gap[j] = g;
 }
 
 }  // namespace sja

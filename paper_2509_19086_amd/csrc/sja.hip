@@ -271,6 +271,10 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
             next_check = r + 1;
         }
     }
+    hipLaunchKernelGGL(k_grant_finish, dim3((G + 255) / 256), dim3(256), 0, st, G, pol,
+                       ws_ptr<int32_t>(ctx, L.gap_order), ws_ptr<int4>(ctx, L.g_state), ctx->seg_off, atom_dp, atom_db,
+                       wait, sla_class, grant_job, grant_cut, grant_score, job_gap);
+    SJA_HIP(hipGetLastError(), "k_grant_finish launch");
     *done = true;
     return SJA_OK;
 }
