@@ -117,15 +117,61 @@ __device__ __forceinline__ int count_less(const int *w, int len, int d)
     return lo;
 }
 
-// Entries of the sub-block lists.  Thread (sub-block u, job j) visits the atoms
-// of j that some position of u gets: atom a applies to lanes [lo, hi) where lo
-// is the first position whose window reaches D_a and hi the first one that
-// already reaches atom a+1.  WRITE = false only counts (per sub-block and in
-// total); WRITE = true stores (key = u : rank, job, atom, lo | hi << 8).
+// Grant-list blocks.  A list serves its gaps well when most of its records
+// cover most of its lanes; a sub-block that starts at a very small window and
+// ends at a much larger one is therefore cut into pieces, each ending before
+// the first window beyond 1.5 * (its first window) + 64.
+__device__ __forceinline__ int list_piece_end(const int32_t *__restrict__ gap_w, int b, int e)
+{
+    const int64_t w0 = max(gap_w[b], 0);
+    const int64_t limit = w0 + (w0 >> 1) + 64;
+    int p = b + 1;
+    while (p < e && int64_t(gap_w[p]) <= limit) ++p;
+    return p;
+}
+
+// Pieces per sub-block (an exclusive scan turns them into lb_off).
+__global__ void k_list_blocks_count(int n_slots, const int32_t *__restrict__ plan,
+                                    const int32_t *__restrict__ sub_begin, const int32_t *__restrict__ sub_end,
+                                    const int32_t *__restrict__ gap_w, int32_t *lb_off)
+{
+    const int u = blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= n_slots) return;
+    int cnt = 0;
+    if (plan[kPlanTabled] && u < plan[kPlanSubBlocks]) {
+        const int e = sub_end[u];
+        for (int b = sub_begin[u]; b < e; b = list_piece_end(gap_w, b, e)) ++cnt;
+    }
+    lb_off[u] = cnt;
+}
+
+__global__ void k_list_blocks_write(int lb_cap, const int32_t *__restrict__ plan,
+                                    const int32_t *__restrict__ sub_begin, const int32_t *__restrict__ sub_end,
+                                    const int32_t *__restrict__ gap_w, const int32_t *__restrict__ lb_off,
+                                    int32_t *lb_begin, int32_t *lb_end, int32_t *lb_sub)
+{
+    const int u = blockIdx.x * blockDim.x + threadIdx.x;
+    if (!plan[kPlanTabled] || u >= plan[kPlanSubBlocks]) return;
+    int v = lb_off[u];
+    const int e = sub_end[u];
+    for (int b = sub_begin[u]; b < e && v < lb_cap; ++v) {
+        const int p = list_piece_end(gap_w, b, e);
+        lb_begin[v] = b;
+        lb_end[v] = p;
+        lb_sub[v] = u;
+        b = p;
+    }
+}
+
+// Entries of the lists.  Thread (list block v, job j) visits the atoms of j
+// that some position of v gets: atom a applies to lanes [lo, hi) where lo is
+// the first position whose window reaches D_a and hi the first one that
+// already reaches atom a+1.  WRITE = false only counts (per block and in
+// total); WRITE = true stores (key = v : rank, job, atom, lo | hi << 8).
 template <bool WRITE>
 __global__ __launch_bounds__(256) void k_list_emit(
-    int n_jobs, int rank_bits, const int32_t *__restrict__ plan, const int32_t *__restrict__ sub_begin,
-    const int32_t *__restrict__ sub_end, const int32_t *__restrict__ sub_class,
+    int n_jobs, int rank_bits, int lb_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
+    const int32_t *__restrict__ lb_end, const int32_t *__restrict__ lb_sub, const int32_t *__restrict__ sub_class,
     const int32_t *__restrict__ gap_w, const int64_t *__restrict__ seg_off,
     const int2 *__restrict__ atom_dp, const int32_t *__restrict__ start_tab,
     const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ abase,
@@ -134,9 +180,9 @@ __global__ __launch_bounds__(256) void k_list_emit(
     uint32_t *__restrict__ el)
 {
     __shared__ int s_w[64];
-    const int u = blockIdx.y;
-    if (!plan[kPlanTabled] || u >= plan[kPlanSubBlocks]) return;
-    const int b0 = sub_begin[u], len = sub_end[u] - b0;
+    const int u = blockIdx.y;                  // list block
+    if (!plan[kPlanTabled] || u >= min(plan[kPlanListBlocks], lb_cap)) return;
+    const int b0 = lb_begin[u], len = lb_end[u] - b0;
     if (threadIdx.x < 64) s_w[threadIdx.x] = threadIdx.x < len ? gap_w[b0 + threadIdx.x] : INT32_MAX;
     __syncthreads();
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -145,9 +191,12 @@ __global__ __launch_bounds__(256) void k_list_emit(
     int a_first = 0, n_cap = 0;
     const int2 *dp = atom_dp;
     if (live) {
-        a_first = start_tab[int64_t(u) * n_jobs + j];
-        n_cap = ncap_tab[int64_t(sub_class[u]) * n_jobs + j];
+        const int sub = lb_sub[u];
+        a_first = start_tab[int64_t(sub) * n_jobs + j];
+        n_cap = ncap_tab[int64_t(sub_class[sub]) * n_jobs + j];
         dp = atom_dp + seg_off[j];
+        // the table holds the count at the sub-block's first position; a later piece starts further on
+        while (a_first < n_cap && dp[a_first].x <= s_w[0]) ++a_first;
     }
     const int a_begin = max(a_first - 1, 0);
 
@@ -217,7 +266,7 @@ __global__ void k_list_pack(const int32_t *n_ptr, const uint32_t *__restrict__ e
     if (i < *n_ptr) rec[i] = make_uint4(ej[i], ea[i], el[i], 0u);
 }
 
-// One round, one wave per sub-block, one lane per gap position.  First the
+// One round, one wave per list block, one lane per gap position.  First the
 // outcome of round k-1: a gap whose candidate job carries the gap's own claim
 // word has won (the grant is final), otherwise it lost.  Then, if `propose`,
 // every lane that still needs a job walks on from its own pointer, eight
@@ -225,10 +274,12 @@ __global__ void k_list_pack(const int32_t *n_ptr, const uint32_t *__restrict__ e
 // job is not held.  state[s] = (pointer, candidate job, candidate atom, flag)
 // with flag 0 = active, 1 = granted, 2 = no candidate left.
 constexpr int kWalk = 8;
+constexpr int kSweep = 4;        // chunks of 64 records the wave reads per trip when it walks together
+constexpr int kOwnTrips = 1;      // batches a lane walks alone before the wave walks together
 
 __global__ __launch_bounds__(256) void k_grant_round(
     int round, int propose, int n_jobs, PolicyDev pol, const int32_t *__restrict__ plan,
-    const int32_t *__restrict__ sub_begin, const int32_t *__restrict__ sub_end,
+    const int32_t *__restrict__ lb_begin, const int32_t *__restrict__ lb_end,
     const int32_t *__restrict__ list_off, const int32_t *__restrict__ gap_order,
     const uint4 *__restrict__ rec, unsigned long long *claim, int4 *state, int32_t *cnt_lost,
     int32_t *cnt_cand, const int64_t *__restrict__ seg_off, const int2 *__restrict__ atom_dp,
@@ -237,10 +288,10 @@ __global__ __launch_bounds__(256) void k_grant_round(
     int32_t *job_gap)
 {
     const int u = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (u >= plan[kPlanSubBlocks]) return;
+    if (u >= plan[kPlanListBlocks]) return;
     const int lane = threadIdx.x & (kWave - 1);
-    const int b0 = sub_begin[u];
-    const bool valid = lane < sub_end[u] - b0;
+    const int b0 = lb_begin[u];
+    const bool valid = lane < lb_end[u] - b0;
     const int s = b0 + lane;
     const int list_end = list_off[u + 1];
     int g = 0;
@@ -270,9 +321,11 @@ __global__ __launch_bounds__(256) void k_grant_round(
     bool cand = false;
     int cand_job = -1;
     unsigned long long cand_word = 0;      // the candidate job's claim word as the walk saw it
-    if (st.w == 0 && propose) {
-        int e = st.x, found = -1, found_j = -1, found_a = -1;
-        while (e < list_end) {
+    const bool walking = st.w == 0 && propose != 0;
+    int e = st.x, found = -1, found_j = -1, found_a = -1;
+    if (walking) {
+        // own walk: a few batches, every lane from its own pointer
+        for (int trip = 0; e < list_end; ++trip) {
             unsigned long long c[kWalk];
 #pragma unroll
             for (int t = 0; t < kWalk; ++t) {
@@ -287,10 +340,71 @@ __global__ __launch_bounds__(256) void k_grant_round(
                 if (found < 0 && free_job) { found = e + t; found_j = int(r[t].x); found_a = int(r[t].y); cand_word = c[t]; }
             }
             e += kWalk;
-            if (found >= 0 || e >= list_end) break;
+            if (found >= 0 || e >= list_end || trip + 1 == kOwnTrips) break;
 #pragma unroll
             for (int t = 0; t < kWalk; ++t) r[t] = rec[min(e + t, list_end - 1)];
         }
+    }
+    // Lanes that are still looking walk on together: per round trip the wave
+    // reads kSweep chunks of 64 records (and their jobs' claim words), starting
+    // at the chunk of its lowest pointer still looking, so a record is read once
+    // per round; every lane whose pointer lies in that span takes the first free
+    // record at or after its pointer that covers the lane, or moves on past the span.
+    {
+        const int list_begin = list_off[u];
+        bool looking = walking && found < 0 && e < list_end;
+        for (;;) {
+            if (!__ballot(looking)) break;
+            int e0 = looking ? e : 0x7fffffff;              // the wave's lowest pointer still looking
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) e0 = min(e0, __shfl_xor(e0, d, kWave));
+            e0 = __builtin_amdgcn_readfirstlane(e0);
+            const int c0 = list_begin + ((e0 - list_begin) & ~(kWave - 1));
+            uint4 rr[kSweep];
+            unsigned long long cw[kSweep];
+#pragma unroll
+            for (int k = 0; k < kSweep; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
+#pragma unroll
+            for (int k = 0; k < kSweep; ++k) cw[k] = claim[rr[k].x];
+            const bool here = looking && e < c0 + kSweep * kWave;
+            int hit = -1, hj = 0, ha = 0;
+            unsigned int hw_lo = 0, hw_hi = 0;
+#pragma unroll
+            for (int k = 0; k < kSweep; ++k) {
+                const uint32_t stamp = uint32_t(cw[k] >> 32);
+                const bool free_rec = c0 + k * kWave + lane < list_end &&
+                                      (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu));
+                unsigned long long fm = __ballot(free_rec);
+                if (!__any(here && hit < 0)) fm = 0;
+                int hk = -1;
+                while (fm) {
+                    const int t = __ffsll((long long)fm) - 1;
+                    fm &= fm - 1;
+                    const unsigned int z = __builtin_amdgcn_readlane(rr[k].z, t);
+                    const bool h = here && hit < 0 && hk < 0 && c0 + k * kWave + t >= e && lane >= int(z & 255u) &&
+                                   lane < int(z >> 8);
+                    hk = h ? t : hk;
+                    if (!__any(here && hit < 0 && hk < 0)) break;
+                }
+                const int src = hk >= 0 ? hk : lane;
+                const int sj = __shfl(int(rr[k].x), src, kWave), sa = __shfl(int(rr[k].y), src, kWave);
+                const unsigned int s_lo = __shfl(int(uint32_t(cw[k])), src, kWave);
+                const unsigned int s_hi = __shfl(int(uint32_t(cw[k] >> 32)), src, kWave);
+                if (hk >= 0) { hit = k * kWave + hk; hj = sj; ha = sa; hw_lo = s_lo; hw_hi = s_hi; }
+            }
+            if (here) {
+                if (hit >= 0) {
+                    found = c0 + hit; found_j = hj; found_a = ha;
+                    cand_word = (static_cast<unsigned long long>(hw_hi) << 32) | hw_lo;
+                    looking = false;
+                } else {
+                    e = c0 + kSweep * kWave;
+                    looking = e < list_end;
+                }
+            }
+        }
+    }
+    if (walking) {
         if (found >= 0) {
             state[s] = make_int4(found + 1, found_j, found_a, 0);
             cand = true;

@@ -146,6 +146,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     *done = false;
     const int G = ctx->n_gaps, J = ctx->n_jobs;
     const int sub_bound = int(fit_sub_bound(G, J));
+    const int lb_bound = int(list_block_bound(G, J));
     const PolicyDev pol = to_dev(params);
     int32_t *plan = ws_ptr<int32_t>(ctx, L.plan);
     int32_t *abase = ws_ptr<int32_t>(ctx, L.g_abase);
@@ -156,6 +157,8 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     const int2 *atom_db = ws_ptr<int2>(ctx, L.atom_db);
     const int32_t *sub_begin = ws_ptr<int32_t>(ctx, L.sub_begin), *sub_end = ws_ptr<int32_t>(ctx, L.sub_end);
     const int32_t *sub_class = ws_ptr<int32_t>(ctx, L.sub_class);
+    int32_t *lb_begin = ws_ptr<int32_t>(ctx, L.lb_begin), *lb_end = ws_ptr<int32_t>(ctx, L.lb_end);
+    int32_t *lb_sub = ws_ptr<int32_t>(ctx, L.lb_sub), *lb_off = ws_ptr<int32_t>(ctx, L.lb_off);
     const int32_t *start_tab = ws_ptr<int32_t>(ctx, L.start_tab), *ncap_tab = ws_ptr<int32_t>(ctx, L.ncap_tab);
     const int32_t *gap_w = ws_ptr<int32_t>(ctx, L.gap_w);
     unsigned long long *key_hi = ws_ptr<unsigned long long>(ctx, L.g_key_hi);
@@ -169,12 +172,18 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
 
     // 1. reachable atoms per job -> compact atom ids; entry counts per sub-block
     hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, st, counters, int64_t(16), 0);
-    hipLaunchKernelGGL(k_fill_i32, dim3((sub_bound + 2 + 255) / 256), dim3(256), 0, st, list_off, int64_t(sub_bound + 2), 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3((lb_bound + 2 + 255) / 256), dim3(256), 0, st, list_off, int64_t(lb_bound + 2), 0);
+    hipLaunchKernelGGL(k_list_blocks_count, dim3((sub_bound + 1 + 255) / 256), dim3(256), 0, st, sub_bound + 1, plan, sub_begin,
+                       sub_end, gap_w, lb_off);
+    SJA_HIP(enqueue_scan(st, lb_off, int64_t(sub_bound) + 1, tmp, plan + kPlanListBlocks), "list block scan launch");
+    hipLaunchKernelGGL(k_list_blocks_write, dim3((sub_bound + 255) / 256), dim3(256), 0, st, lb_bound, plan, sub_begin,
+                       sub_end, gap_w, lb_off, lb_begin, lb_end, lb_sub);
+    SJA_HIP(hipGetLastError(), "list block launch");
     hipLaunchKernelGGL(k_reach, dim3((J + 1 + 255) / 256), dim3(256), 0, st, J, plan, ncap_tab, abase);
     SJA_HIP(hipGetLastError(), "k_reach launch");
     SJA_HIP(enqueue_scan(st, abase, int64_t(J) + 1, tmp, counters + 2), "atom scan launch");
-    const dim3 emit_grid((J + 255) / 256, sub_bound);
-    hipLaunchKernelGGL((k_list_emit<false>), emit_grid, dim3(256), 0, st, J, 0, plan, sub_begin, sub_end, sub_class,
+    const dim3 emit_grid((J + 255) / 256, lb_bound);
+    hipLaunchKernelGGL((k_list_emit<false>), emit_grid, dim3(256), 0, st, J, 0, lb_bound, plan, lb_begin, lb_end, lb_sub, sub_class,
                        gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters, ekey[0],
                        ej[0], ea[0], el[0]);
     SJA_HIP(hipGetLastError(), "k_list_emit count launch");
@@ -183,8 +192,8 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(hipMemcpyAsync(host_counters, counters, sizeof(host_counters), hipMemcpyDeviceToHost, st), "count readback");
     SJA_HIP(hipStreamSynchronize(st), "count synchronise");
     const int64_t n_entries = host_counters[0], n_atoms = host_counters[2];
-    const int n_subs = host_plan[kPlanSubBlocks];
-    if (!host_plan[kPlanTabled] || n_entries < 0 || n_entries > L.entry_cap || n_atoms > L.atom_cap) return SJA_OK;
+    const int n_subs = host_plan[kPlanListBlocks];          // list blocks from here on
+    if (!host_plan[kPlanTabled] || n_subs > lb_bound || n_entries < 0 || n_entries > L.entry_cap || n_atoms > L.atom_cap) return SJA_OK;
 
     // 2. rank the atoms by policy key (descending key, ascending job id)
     if (n_atoms > 0) {
@@ -210,11 +219,11 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     // 3. sub-block lists in rank order
     const int rank_bits = bits_for(n_atoms > 1 ? n_atoms : 2);
     const int sub_bits = bits_for(n_subs > 1 ? n_subs : 2);
-    SJA_HIP(enqueue_scan(st, list_off, int64_t(sub_bound) + 2, tmp, nullptr), "list offset scan launch");
+    SJA_HIP(enqueue_scan(st, list_off, int64_t(lb_bound) + 2, tmp, nullptr), "list offset scan launch");
     bool eflip = false;
     if (n_entries > 0) {
-        hipLaunchKernelGGL((k_list_emit<true>), emit_grid, dim3(256), 0, st, J, rank_bits, plan, sub_begin, sub_end,
-                           sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters,
+        hipLaunchKernelGGL((k_list_emit<true>), emit_grid, dim3(256), 0, st, J, rank_bits, lb_bound, plan, lb_begin, lb_end,
+                           lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters,
                            ekey[0], ej[0], ea[0], el[0]);
         SJA_HIP(hipGetLastError(), "k_list_emit launch");
         int rc = radix_sort_bits(ctx, st, L, counters, n_entries, 0, rank_bits + sub_bits, eflip,
@@ -242,7 +251,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(hipGetLastError(), "counter fill launch");
     auto launch_round = [&](int64_t k, int propose) {
         hipLaunchKernelGGL(k_grant_round, dim3((n_subs + 3) / 4), dim3(256), 0, st, int(k), propose, J, pol, plan,
-                           sub_begin, sub_end, list_off, ws_ptr<int32_t>(ctx, L.gap_order), rec,
+                           lb_begin, lb_end, list_off, ws_ptr<int32_t>(ctx, L.gap_order), rec,
                            ws_ptr<unsigned long long>(ctx, L.res_claim), ws_ptr<int4>(ctx, L.g_state), cnt_lost, cnt_cand,
                            ctx->seg_off, atom_dp, atom_db, wait, sla_class, grant_job, grant_cut, grant_score, job_gap);
         return hipGetLastError();

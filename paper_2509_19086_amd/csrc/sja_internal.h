@@ -21,6 +21,7 @@ constexpr int kFitPeriod = 32;        // steps between window top-ups (multiple 
 constexpr int kMaxClasses = 64;       // distinct capacities served by the table-driven path
 constexpr int kSelBlock = 256;        // threads per select block, one job per thread
 constexpr int kSelGapChunk = 128;     // sorted gap positions walked by one select block
+constexpr int kListSplits = 40;       // most pieces one capacity class's small windows are split into
 
 // One partial arg-max per (job tile, gap): 32 bytes.
 struct SelPartial {
@@ -32,7 +33,7 @@ struct SelPartial {
 };
 
 // Gap plan header written by k_gap_plan (device memory, int32 each).
-enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanSubBlocks = 3, kPlanWords = 8 };
+enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanSubBlocks = 3, kPlanListBlocks = 4, kPlanWords = 8 };
 
 // Byte offsets of the private tables inside the caller's workspace.
 struct Layout {
@@ -61,7 +62,9 @@ struct Layout {
     size_t g_hist;                         // [256 * ceil(entry_cap/2048)] int32
     size_t g_ekey0, g_ekey1;               // [entry_cap] uint64
     size_t g_ej0, g_ej1, g_ea0, g_ea1, g_el0, g_el1;   // [entry_cap] uint32
-    size_t g_list_off;                     // [sub_bound+2] int32
+    size_t lb_begin, lb_end, lb_sub;       // [list_bound] int32: grant-list blocks (pieces of sub-blocks)
+    size_t lb_off;                         // [sub_bound+2] int32: first list block of a sub-block
+    size_t g_list_off;                     // [list_bound+2] int32
     size_t g_state;                        // [G] int4: pointer, candidate job, candidate atom, flag
     size_t g_cnt_lost, g_cnt_cand;         // [min(G,J)+4] int32
     int64_t atom_cap, entry_cap;
@@ -95,6 +98,10 @@ inline int64_t fit_sub_bound(int64_t G, int64_t J)
     const int sb = fit_sub_len(G, J);
     return (G + sb - 1) / sb + kMaxClasses;
 }
+
+// Grant-list blocks: the sub-blocks, those that span a wide range of small
+// windows cut into pieces (at most kListSplits per capacity class).
+inline int64_t list_block_bound(int64_t G, int64_t J) { return fit_sub_bound(G, J) + int64_t(kMaxClasses) * kListSplits; }
 
 inline Layout make_layout(int64_t G, int64_t J, int64_t S)
 {
@@ -135,11 +142,12 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.res_claim = take(size_t(J) * 8);
     L.res_counters = take(64);
     L.atom_cap = S + 8;
-    L.entry_cap = int64_t(ub) * J + 2 * S + 8;
+    const size_t lb = size_t(list_block_bound(G, J));
+    L.entry_cap = int64_t(ub + 128) * J + 2 * S + 8;
     const size_t ac = size_t(L.atom_cap), ec = size_t(L.entry_cap);
     const size_t hist_ints = 256 * ((ec + 2047) / 2048);
     L.g_abase = take(size_t(J + 2) * 4);
-    L.g_scan_tmp = take(((hist_ints + 2047) / 2048 + size_t(J) / 2048 + ub / 2048 + 16) * 4);
+    L.g_scan_tmp = take(((hist_ints + 2047) / 2048 + size_t(J) / 2048 + lb / 2048 + 16) * 4);
     L.g_key_hi = take(ac * 8);
     L.g_key_lo = take(ac * 8);
     L.g_perm0 = take(ac * 4);
@@ -154,7 +162,11 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.g_ea1 = take(ec * 4);
     L.g_el0 = take(ec * 4);
     L.g_el1 = take(ec * 4);
-    L.g_list_off = take((ub + 2) * 4);
+    L.lb_begin = take(lb * 4);
+    L.lb_end = take(lb * 4);
+    L.lb_sub = take(lb * 4);
+    L.lb_off = take((ub + 2) * 4);
+    L.g_list_off = take((lb + 2) * 4);
     L.g_state = take(size_t(G) * 16);
     const size_t rounds_cap = size_t(G < J ? G : J) + 4;
     L.g_cnt_lost = take(rounds_cap * 4);
