@@ -371,11 +371,15 @@ __global__ __launch_bounds__(256) void k_grant_round(
             unsigned int hw_lo = 0, hw_hi = 0;
 #pragma unroll
             for (int k = 0; k < kSweep; ++k) {
+                // records worth a look: free, and covering some lane that still needs one
+                const unsigned long long need = __ballot(here && hit < 0);
+                const int need_lo = need ? __ffsll((long long)need) - 1 : 0;
+                const int need_hi = need ? 63 - __clzll((long long)need) : -1;
                 const uint32_t stamp = uint32_t(cw[k] >> 32);
                 const bool free_rec = c0 + k * kWave + lane < list_end &&
-                                      (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu));
+                                      (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu)) &&
+                                      int(rr[k].z & 255u) <= need_hi && int(rr[k].z >> 8) > need_lo;
                 unsigned long long fm = __ballot(free_rec);
-                if (!__any(here && hit < 0)) fm = 0;
                 int hk = -1;
                 while (fm) {
                     const int t = __ffsll((long long)fm) - 1;
