@@ -24,6 +24,8 @@
 
 namespace sja {
 
+constexpr int kEntryLaneBits = 13;      // low bits of a list entry: lane range lo (6), hi (7)
+
 struct PolicyDev {
     int policy;
     int wait_scale;
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(256) void k_atom_keys(
     int n_jobs, PolicyDev pol, const int64_t *__restrict__ seg_off, const int2 *__restrict__ atom_dp,
     const int32_t *__restrict__ abase, const int32_t *__restrict__ wait,
     const uint8_t *__restrict__ sla_class, unsigned long long *__restrict__ key_hi,
-    unsigned long long *__restrict__ key_lo, uint32_t *__restrict__ perm)
+    unsigned long long *__restrict__ key_lo, uint32_t *__restrict__ perm, int2 *__restrict__ atom_ja)
 {
     const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
     if (j >= n_jobs) return;
@@ -90,6 +92,7 @@ __global__ __launch_bounds__(256) void k_atom_keys(
         key_hi[a0 + a] = ~((tier << 62) | (F * mult));
         key_lo[a0 + a] = ~(mixed ? F : 0ull);
         perm[a0 + a] = uint32_t(a0 + a);
+        atom_ja[a0 + a] = make_int2(j, a);
     }
 }
 
@@ -99,11 +102,17 @@ struct MovePerm {
     __device__ void operator()(int64_t i, int64_t o) const { dst[o] = src[i]; }
 };
 
+// rank of every atom, and the (job, atom) that holds each rank
 __global__ void k_rank_from_perm(const int32_t *n_ptr, const uint32_t *__restrict__ perm,
-                                 uint32_t *__restrict__ rank)
+                                 const int2 *__restrict__ atom_ja, uint32_t *__restrict__ rank,
+                                 int2 *__restrict__ ranked)
 {
     const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < *n_ptr) rank[perm[i]] = uint32_t(i);
+    if (i < *n_ptr) {
+        const uint32_t a = perm[i];
+        rank[a] = uint32_t(i);
+        ranked[i] = atom_ja[a];
+    }
 }
 
 // Number of entries of sorted w[0..len) that are < d.
@@ -167,7 +176,7 @@ __global__ void k_list_blocks_write(int lb_cap, const int32_t *__restrict__ plan
 // that some position of v gets: atom a applies to lanes [lo, hi) where lo is
 // the first position whose window reaches D_a and hi the first one that
 // already reaches atom a+1.  WRITE = false only counts (per block and in
-// total); WRITE = true stores (key = v : rank, job, atom, lo | hi << 8).
+// total); WRITE = true stores one 64-bit entry: v : rank : hi (7 bits) : lo (6 bits).
 template <bool WRITE>
 __global__ __launch_bounds__(256) void k_list_emit(
     int n_jobs, int rank_bits, int lb_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
@@ -176,8 +185,7 @@ __global__ __launch_bounds__(256) void k_list_emit(
     const int2 *__restrict__ atom_dp, const int32_t *__restrict__ start_tab,
     const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ abase,
     const uint32_t *__restrict__ rank, int32_t *sub_count, int32_t *counters /*[0]=total, [1]=cursor*/,
-    unsigned long long *__restrict__ ekey, uint32_t *__restrict__ ej, uint32_t *__restrict__ ea,
-    uint32_t *__restrict__ el)
+    unsigned long long *__restrict__ ekey)
 {
     __shared__ int s_w[64];
     const int u = blockIdx.y;                  // list block
@@ -237,20 +245,12 @@ __global__ __launch_bounds__(256) void k_list_emit(
         int64_t slot = int64_t(wave_base) + incl - cnt;
         const int a0 = live ? abase[j] : 0;
         visit([&](int a, int lo, int hi) {
-            ekey[slot] = ((unsigned long long)u << rank_bits) | rank[a0 + a];
-            ej[slot] = uint32_t(j);
-            ea[slot] = uint32_t(a);
-            el[slot] = uint32_t(lo | (hi << 8));
+            ekey[slot] = ((((unsigned long long)u << rank_bits) | rank[a0 + a]) << kEntryLaneBits) |
+                         (unsigned long long)((hi << 6) | lo);
             ++slot;
         });
     }
 }
-
-struct MoveEntry {
-    const unsigned long long *k0; const uint32_t *j0, *a0, *l0;
-    unsigned long long *k1; uint32_t *j1, *a1, *l1;
-    __device__ void operator()(int64_t i, int64_t o) const { k1[o] = k0[i]; j1[o] = j0[i]; a1[o] = a0[i]; l1[o] = l0[i]; }
-};
 
 __device__ __forceinline__ unsigned long long claim_of(int round, int g)
 {
@@ -258,12 +258,15 @@ __device__ __forceinline__ unsigned long long claim_of(int round, int g)
 }
 
 // Sorted entries as 16-byte records (job, atom, lo | hi << 8, 0): one load per entry.
-__global__ void k_list_pack(const int32_t *n_ptr, const uint32_t *__restrict__ ej,
-                            const uint32_t *__restrict__ ea, const uint32_t *__restrict__ el,
-                            uint4 *__restrict__ rec)
+__global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__restrict__ ekey, int rank_bits,
+                            const int2 *__restrict__ ranked, uint4 *__restrict__ rec)
 {
     const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < *n_ptr) rec[i] = make_uint4(ej[i], ea[i], el[i], 0u);
+    if (i >= *n_ptr) return;
+    const unsigned long long k = ekey[i];
+    const int2 ja = ranked[(k >> kEntryLaneBits) & ((1ull << rank_bits) - 1ull)];
+    const unsigned int lo = unsigned(k) & 63u, hi = unsigned(k >> 6) & 127u;
+    rec[i] = make_uint4(uint32_t(ja.x), uint32_t(ja.y), lo | (hi << 8), 0u);
 }
 
 // One round, one wave per list block, one lane per gap position.  First the

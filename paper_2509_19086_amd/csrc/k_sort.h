@@ -168,4 +168,120 @@ __global__ __launch_bounds__(256) void k_radix_scatter(Digit dig, Mover mv, cons
     }
 }
 
+
+// --------------------------------------------------------------------------
+// Stable radix pass over bare 64-bit keys (the grant-list entries), tiles of
+// kKeyTile items.  A tile is ranked per wave (each wave owns a contiguous
+// quarter, walked in order so the pass stays stable), put in digit order in
+// LDS and written out from there, so that items of one digit leave as one
+// contiguous run.
+// --------------------------------------------------------------------------
+constexpr int kKeyTile = 4096;
+constexpr int kKeyPerWave = kKeyTile / 4;
+constexpr int kKeyChunks = kKeyPerWave / kWave;
+
+// Lanes of the wave (among `valid`) holding the same 8-bit digit as this lane.
+__device__ __forceinline__ unsigned long long digit_peers(unsigned d, bool valid)
+{
+    unsigned long long peers = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const unsigned long long m = __ballot((d >> b) & 1u);
+        peers &= ((d >> b) & 1u) ? m : ~m;
+    }
+    return peers;
+}
+
+__global__ __launch_bounds__(256) void k_keys_hist(const unsigned long long *__restrict__ keys,
+                                                   const int32_t *n_ptr, int shift, int32_t *hist, int n_tiles)
+{
+    __shared__ int s_h[256];
+    const int64_t n = *n_ptr;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    s_h[tid] = 0;
+    __syncthreads();
+    const int64_t base = int64_t(blockIdx.x) * kKeyTile;
+#pragma unroll 4
+    for (int r = 0; r < kKeyTile / 256; ++r) {
+        const int64_t i = base + r * 256 + tid;
+        const bool valid = i < n;
+        const unsigned d = valid ? unsigned(keys[i] >> shift) & 255u : 0u;
+        const unsigned long long peers = digit_peers(d, valid);
+        if (valid && (peers & ((1ull << lane) - 1ull)) == 0) atomicAdd(&s_h[d], __popcll(peers));
+    }
+    __syncthreads();
+    hist[int64_t(tid) * n_tiles + blockIdx.x] = s_h[tid];
+}
+
+__global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *__restrict__ src,
+                                                      unsigned long long *__restrict__ dst, const int32_t *n_ptr,
+                                                      int shift, const int32_t *__restrict__ hist, int n_tiles)
+{
+    __shared__ unsigned long long s_key[kKeyTile];
+    __shared__ int s_cnt[4][256];       // per wave and digit: running count, later the offset inside the digit
+    __shared__ int s_start[256];        // first tile-local slot of a digit
+    __shared__ int s_goff[256];         // where the tile's items of a digit go
+    __shared__ int s_wsum[4];
+    const int64_t n = *n_ptr;
+    const int64_t base = int64_t(blockIdx.x) * kKeyTile;
+    if (base >= n) return;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) s_cnt[w][tid] = 0;
+    s_goff[tid] = hist[int64_t(tid) * n_tiles + blockIdx.x];
+    __syncthreads();
+
+    unsigned long long key[kKeyChunks];
+    int pos[kKeyChunks];
+    const int64_t wbase = base + wave * kKeyPerWave + lane;
+#pragma unroll
+    for (int c = 0; c < kKeyChunks; ++c) key[c] = wbase + c * kWave < n ? src[wbase + c * kWave] : ~0ull;
+    volatile int *cnt = &s_cnt[wave][0];
+#pragma unroll
+    for (int c = 0; c < kKeyChunks; ++c) {
+        const bool valid = wbase + c * kWave < n;
+        const unsigned d = unsigned(key[c] >> shift) & 255u;
+        const unsigned long long peers = digit_peers(d, valid);
+        const int before = __popcll(peers & ((1ull << lane) - 1ull));
+        const int prev = cnt[d];
+        pos[c] = prev + before;
+        __builtin_amdgcn_wave_barrier();
+        if (valid && before == 0) cnt[d] = prev + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+
+    {   // digit tid: offsets of the four waves inside the digit, then the digits' starts
+        const int c0 = s_cnt[0][tid], c1 = s_cnt[1][tid], c2 = s_cnt[2][tid], c3 = s_cnt[3][tid];
+        s_cnt[0][tid] = 0; s_cnt[1][tid] = c0; s_cnt[2][tid] = c0 + c1; s_cnt[3][tid] = c0 + c1 + c2;
+        const int total = c0 + c1 + c2 + c3;
+        int incl = total;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int t = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += t;
+        }
+        if (lane == kWave - 1) s_wsum[wave] = incl;
+        __syncthreads();
+        int off = 0;
+        for (int w = 0; w < wave; ++w) off += s_wsum[w];
+        s_start[tid] = off + incl - total;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kKeyChunks; ++c) {
+        if (wbase + c * kWave < n) {
+            const unsigned d = unsigned(key[c] >> shift) & 255u;
+            s_key[s_start[d] + s_cnt[wave][d] + pos[c]] = key[c];
+        }
+    }
+    __syncthreads();
+    const int count = int(n - base < kKeyTile ? n - base : kKeyTile);
+    for (int k = tid; k < count; k += 256) {
+        const unsigned long long v = s_key[k];
+        const unsigned d = unsigned(v >> shift) & 255u;
+        dst[int64_t(s_goff[d]) + (k - s_start[d])] = v;
+    }
+}
+
 }  // namespace sja

@@ -128,6 +128,27 @@ int radix_sort_bits(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t
     return SJA_OK;
 }
 
+// The same over bare 64-bit keys (key-only tiles), between two buffers.
+int radix_sort_keys(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t *n_dev, int64_t n_host,
+                    int first_bit, int last_bit, bool &flip, unsigned long long *const buf[2])
+{
+    if (n_host <= 0) return SJA_OK;
+    const int n_tiles = int((n_host + kKeyTile - 1) / kKeyTile);
+    int32_t *hist = ws_ptr<int32_t>(ctx, L.g_hist);
+    int32_t *tmp = ws_ptr<int32_t>(ctx, L.g_scan_tmp);
+    for (int shift = first_bit; shift < last_bit; shift += 8) {
+        const unsigned long long *src = buf[flip ? 1 : 0];
+        unsigned long long *dst = buf[flip ? 0 : 1];
+        hipLaunchKernelGGL(k_keys_hist, dim3(n_tiles), dim3(256), 0, st, src, n_dev, shift, hist, n_tiles);
+        SJA_HIP(hipGetLastError(), "k_keys_hist launch");
+        SJA_HIP(enqueue_scan(st, hist, int64_t(256) * n_tiles, tmp, nullptr), "radix scan launch");
+        hipLaunchKernelGGL(k_keys_scatter, dim3(n_tiles), dim3(256), 0, st, src, dst, n_dev, shift, hist, n_tiles);
+        SJA_HIP(hipGetLastError(), "k_keys_scatter launch");
+        flip = !flip;
+    }
+    return SJA_OK;
+}
+
 int bits_for(int64_t n)
 {
     int b = 1;
@@ -166,9 +187,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     uint32_t *perm[2] = {ws_ptr<uint32_t>(ctx, L.g_perm0), ws_ptr<uint32_t>(ctx, L.g_perm1)};
     uint32_t *rank = ws_ptr<uint32_t>(ctx, L.g_rank);
     unsigned long long *ekey[2] = {ws_ptr<unsigned long long>(ctx, L.g_ekey0), ws_ptr<unsigned long long>(ctx, L.g_ekey1)};
-    uint32_t *ej[2] = {ws_ptr<uint32_t>(ctx, L.g_ej0), ws_ptr<uint32_t>(ctx, L.g_ej1)};
-    uint32_t *ea[2] = {ws_ptr<uint32_t>(ctx, L.g_ea0), ws_ptr<uint32_t>(ctx, L.g_ea1)};
-    uint32_t *el[2] = {ws_ptr<uint32_t>(ctx, L.g_el0), ws_ptr<uint32_t>(ctx, L.g_el1)};
+    int2 *atom_ja = ws_ptr<int2>(ctx, L.g_atom_ja), *ranked = ws_ptr<int2>(ctx, L.g_ranked);
 
     // 1. reachable atoms per job -> compact atom ids; entry counts per sub-block
     hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, st, counters, int64_t(16), 0);
@@ -184,8 +203,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(enqueue_scan(st, abase, int64_t(J) + 1, tmp, counters + 2), "atom scan launch");
     const dim3 emit_grid((J + 255) / 256, lb_bound);
     hipLaunchKernelGGL((k_list_emit<false>), emit_grid, dim3(256), 0, st, J, 0, lb_bound, plan, lb_begin, lb_end, lb_sub, sub_class,
-                       gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters, ekey[0],
-                       ej[0], ea[0], el[0]);
+                       gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters, ekey[0]);
     SJA_HIP(hipGetLastError(), "k_list_emit count launch");
     int32_t host_plan[kPlanWords] = {0}, host_counters[4] = {0};
     SJA_HIP(hipMemcpyAsync(host_plan, plan, sizeof(host_plan), hipMemcpyDeviceToHost, st), "plan readback");
@@ -198,7 +216,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     // 2. rank the atoms by policy key (descending key, ascending job id)
     if (n_atoms > 0) {
         hipLaunchKernelGGL(k_atom_keys, dim3((J + 3) / 4), dim3(256), 0, st, J, pol, ctx->seg_off, atom_dp, abase, wait,
-                           sla_class, key_hi, key_lo, perm[0]);
+                           sla_class, key_hi, key_lo, perm[0], atom_ja);
         SJA_HIP(hipGetLastError(), "k_atom_keys launch");
         bool flip = false;
         auto mover = [&](bool f) { return MovePerm{perm[f ? 1 : 0], perm[f ? 0 : 1]}; };
@@ -212,7 +230,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
                              [&](bool f) { return DigitViaPerm{key_hi, perm[f ? 1 : 0]}; }, mover);
         if (rc != SJA_OK) return rc;
         hipLaunchKernelGGL(k_rank_from_perm, dim3(unsigned((n_atoms + 255) / 256)), dim3(256), 0, st, counters + 2,
-                           perm[flip ? 1 : 0], rank);
+                           perm[flip ? 1 : 0], atom_ja, rank, ranked);
         SJA_HIP(hipGetLastError(), "k_rank_from_perm launch");
     }
 
@@ -224,22 +242,17 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     if (n_entries > 0) {
         hipLaunchKernelGGL((k_list_emit<true>), emit_grid, dim3(256), 0, st, J, rank_bits, lb_bound, plan, lb_begin, lb_end,
                            lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters,
-                           ekey[0], ej[0], ea[0], el[0]);
+                           ekey[0]);
         SJA_HIP(hipGetLastError(), "k_list_emit launch");
-        int rc = radix_sort_bits(ctx, st, L, counters, n_entries, 0, rank_bits + sub_bits, eflip,
-                                 [&](bool f) { return DigitDirect{ekey[f ? 1 : 0]}; },
-                                 [&](bool f) {
-                                     const int a = f ? 1 : 0, b = f ? 0 : 1;
-                                     return MoveEntry{ekey[a], ej[a], ea[a], el[a], ekey[b], ej[b], ea[b], el[b]};
-                                 });
+        int rc = radix_sort_keys(ctx, st, L, counters, n_entries, kEntryLaneBits,
+                                 kEntryLaneBits + rank_bits + sub_bits, eflip, ekey);
         if (rc != SJA_OK) return rc;
     }
     const int fb = eflip ? 1 : 0;
-    // records of the sorted lists; the key buffer that is not in use any more holds them (16 B per entry)
-    uint4 *rec = reinterpret_cast<uint4 *>(ws_ptr<char>(ctx, L.g_ekey0));
+    uint4 *rec = ws_ptr<uint4>(ctx, L.g_rec);
     if (n_entries > 0) {
-        hipLaunchKernelGGL(k_list_pack, dim3(unsigned((n_entries + 255) / 256)), dim3(256), 0, st, counters, ej[fb],
-                           ea[fb], el[fb], rec);
+        hipLaunchKernelGGL(k_list_pack, dim3(unsigned((n_entries + 255) / 256)), dim3(256), 0, st, counters, ekey[fb],
+                           rank_bits, ranked, rec);
         SJA_HIP(hipGetLastError(), "k_list_pack launch");
     }
 

@@ -59,9 +59,10 @@ struct Layout {
     size_t g_scan_tmp;                     // tile sums of the scans
     size_t g_key_hi, g_key_lo;             // [atom_cap] uint64
     size_t g_perm0, g_perm1, g_rank;       // [atom_cap] uint32
-    size_t g_hist;                         // [256 * ceil(entry_cap/2048)] int32
-    size_t g_ekey0, g_ekey1;               // [entry_cap] uint64
-    size_t g_ej0, g_ej1, g_ea0, g_ea1, g_el0, g_el1;   // [entry_cap] uint32
+    size_t g_hist;                         // [256 * tiles] int32, tiles of the larger of the two sorts
+    size_t g_ekey0, g_ekey1;               // [entry_cap] uint64: list entries (block : rank : lane range)
+    size_t g_rec;                          // [entry_cap] uint4: the sorted lists as records
+    size_t g_atom_ja, g_ranked;            // [atom_cap] int2: (job, atom) by atom id and by rank
     size_t lb_begin, lb_end, lb_sub;       // [list_bound] int32: grant-list blocks (pieces of sub-blocks)
     size_t lb_off;                         // [sub_bound+2] int32: first list block of a sub-block
     size_t g_list_off;                     // [list_bound+2] int32
@@ -145,7 +146,8 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     const size_t lb = size_t(list_block_bound(G, J));
     L.entry_cap = int64_t(ub + 128) * J + 2 * S + 8;
     const size_t ac = size_t(L.atom_cap), ec = size_t(L.entry_cap);
-    const size_t hist_ints = 256 * ((ec + 2047) / 2048);
+    const size_t tiles_a = (ac + 2047) / 2048, tiles_e = (ec + 4095) / 4096;
+    const size_t hist_ints = 256 * (tiles_a > tiles_e ? tiles_a : tiles_e);
     L.g_abase = take(size_t(J + 2) * 4);
     L.g_scan_tmp = take(((hist_ints + 2047) / 2048 + size_t(J) / 2048 + lb / 2048 + 16) * 4);
     L.g_key_hi = take(ac * 8);
@@ -156,12 +158,9 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.g_hist = take(hist_ints * 4);
     L.g_ekey0 = take(ec * 8);
     L.g_ekey1 = take(ec * 8);
-    L.g_ej0 = take(ec * 4);
-    L.g_ej1 = take(ec * 4);
-    L.g_ea0 = take(ec * 4);
-    L.g_ea1 = take(ec * 4);
-    L.g_el0 = take(ec * 4);
-    L.g_el1 = take(ec * 4);
+    L.g_rec = take(ec * 16);
+    L.g_atom_ja = take(ac * 8);
+    L.g_ranked = take(ac * 8);
     L.lb_begin = take(lb * 4);
     L.lb_end = take(lb * 4);
     L.lb_sub = take(lb * 4);
