@@ -175,16 +175,16 @@ __global__ void k_list_blocks_write(int lb_cap, const int32_t *__restrict__ plan
 // Entries of the lists.  Thread (list block v, job j) visits the atoms of j
 // that some position of v gets: atom a applies to lanes [lo, hi) where lo is
 // the first position whose window reaches D_a and hi the first one that
-// already reaches atom a+1.  WRITE = false only counts (per block and in
-// total); WRITE = true stores one 64-bit entry: v : rank : hi (7 bits) : lo (6 bits).
-template <bool WRITE>
+// already reaches atom a+1.  Every entry is one 64-bit word, v : rank : hi (7
+// bits) : lo (6 bits), stored wherever the running total puts it (the sort
+// orders them); entries beyond entry_cap are counted but not stored.
 __global__ __launch_bounds__(256) void k_list_emit(
-    int n_jobs, int rank_bits, int lb_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
+    int n_jobs, int rank_bits, int lb_cap, long long entry_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
     const int32_t *__restrict__ lb_end, const int32_t *__restrict__ lb_sub, const int32_t *__restrict__ sub_class,
     const int32_t *__restrict__ gap_w, const int64_t *__restrict__ seg_off,
     const int2 *__restrict__ atom_dp, const int32_t *__restrict__ start_tab,
     const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ abase,
-    const uint32_t *__restrict__ rank, int32_t *sub_count, int32_t *counters /*[0]=total, [1]=cursor*/,
+    const uint32_t *__restrict__ rank, int32_t *sub_count, unsigned long long *total,
     unsigned long long *__restrict__ ekey)
 {
     __shared__ int s_w[64];
@@ -233,15 +233,14 @@ __global__ __launch_bounds__(256) void k_list_emit(
         if (lane >= d) incl += t;
     }
     const int wave_total = __shfl(incl, kWave - 1, kWave);
-    if (!WRITE) {
+    {
+        unsigned long long wave_base = 0;
         if (lane == 0 && wave_total) {
             atomicAdd(&sub_count[u], wave_total);
-            atomicAdd(&counters[0], wave_total);
+            wave_base = atomicAdd(total, (unsigned long long)wave_total);
         }
-    } else {
-        int wave_base = 0;
-        if (lane == 0 && wave_total) wave_base = atomicAdd(&counters[1], wave_total);
-        wave_base = __shfl(wave_base, 0, kWave);
+        wave_base = (unsigned long long)__shfl((long long)wave_base, 0, kWave);
+        if ((long long)(wave_base + wave_total) > entry_cap) return;
         int64_t slot = int64_t(wave_base) + incl - cnt;
         const int a0 = live ? abase[j] : 0;
         visit([&](int a, int lo, int hi) {

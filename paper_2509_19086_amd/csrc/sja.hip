@@ -201,17 +201,13 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     hipLaunchKernelGGL(k_reach, dim3((J + 1 + 255) / 256), dim3(256), 0, st, J, plan, ncap_tab, abase);
     SJA_HIP(hipGetLastError(), "k_reach launch");
     SJA_HIP(enqueue_scan(st, abase, int64_t(J) + 1, tmp, counters + 2), "atom scan launch");
-    const dim3 emit_grid((J + 255) / 256, lb_bound);
-    hipLaunchKernelGGL((k_list_emit<false>), emit_grid, dim3(256), 0, st, J, 0, lb_bound, plan, lb_begin, lb_end, lb_sub, sub_class,
-                       gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters, ekey[0]);
-    SJA_HIP(hipGetLastError(), "k_list_emit count launch");
     int32_t host_plan[kPlanWords] = {0}, host_counters[4] = {0};
     SJA_HIP(hipMemcpyAsync(host_plan, plan, sizeof(host_plan), hipMemcpyDeviceToHost, st), "plan readback");
     SJA_HIP(hipMemcpyAsync(host_counters, counters, sizeof(host_counters), hipMemcpyDeviceToHost, st), "count readback");
     SJA_HIP(hipStreamSynchronize(st), "count synchronise");
-    const int64_t n_entries = host_counters[0], n_atoms = host_counters[2];
+    const int64_t n_atoms = host_counters[2];
     const int n_subs = host_plan[kPlanListBlocks];          // list blocks from here on
-    if (!host_plan[kPlanTabled] || n_subs > lb_bound || n_entries < 0 || n_entries > L.entry_cap || n_atoms > L.atom_cap) return SJA_OK;
+    if (!host_plan[kPlanTabled] || n_subs > lb_bound || n_atoms > L.atom_cap) return SJA_OK;
 
     // 2. rank the atoms by policy key (descending key, ascending job id)
     if (n_atoms > 0) {
@@ -234,16 +230,21 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
         SJA_HIP(hipGetLastError(), "k_rank_from_perm launch");
     }
 
-    // 3. sub-block lists in rank order
+    // 3. list entries (one pass, counted as they are written), then sorted by (block, rank)
     const int rank_bits = bits_for(n_atoms > 1 ? n_atoms : 2);
     const int sub_bits = bits_for(n_subs > 1 ? n_subs : 2);
+    const dim3 emit_grid((J + 255) / 256, lb_bound);
+    hipLaunchKernelGGL(k_list_emit, emit_grid, dim3(256), 0, st, J, rank_bits, lb_bound, (long long)L.entry_cap, plan,
+                       lb_begin, lb_end, lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank,
+                       list_off, reinterpret_cast<unsigned long long *>(counters), ekey[0]);
+    SJA_HIP(hipGetLastError(), "k_list_emit launch");
+    long long n_entries = 0;
+    SJA_HIP(hipMemcpyAsync(&n_entries, counters, sizeof(n_entries), hipMemcpyDeviceToHost, st), "entry count readback");
+    SJA_HIP(hipStreamSynchronize(st), "entry count synchronise");
+    if (n_entries > L.entry_cap || n_entries >= (1ll << 31)) return SJA_OK;
     SJA_HIP(enqueue_scan(st, list_off, int64_t(lb_bound) + 2, tmp, nullptr), "list offset scan launch");
     bool eflip = false;
     if (n_entries > 0) {
-        hipLaunchKernelGGL((k_list_emit<true>), emit_grid, dim3(256), 0, st, J, rank_bits, lb_bound, plan, lb_begin, lb_end,
-                           lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank, list_off, counters,
-                           ekey[0]);
-        SJA_HIP(hipGetLastError(), "k_list_emit launch");
         int rc = radix_sort_keys(ctx, st, L, counters, n_entries, kEntryLaneBits,
                                  kEntryLaneBits + rank_bits + sub_bits, eflip, ekey);
         if (rc != SJA_OK) return rc;
@@ -273,9 +274,10 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     int64_t launched = 0;        // kernels 1..launched have been enqueued
     int64_t next_check = 1;      // first round whose end is not yet decided
     bool finished = false;
-    const int64_t batch = 64;
+    int64_t batch = 64;          // rounds enqueued between looks at the flags; grows, a finished batch costs little
     while (!finished) {
         const int64_t upto = (launched + batch < cap) ? launched + batch : cap;
+        if (batch < 1024) batch *= 2;
         for (int64_t k = launched + 1; k <= upto; ++k) SJA_HIP(launch_round(k, 1), "k_grant_round launch");
         if (upto == cap) SJA_HIP(launch_round(cap + 1, 0), "k_grant_round launch");
         launched = upto;
