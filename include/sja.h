@@ -194,6 +194,23 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
 int sja_enable_timing(sja_ctx *ctx, int on);
 int sja_last_fit_kernel_ms(sja_ctx *ctx, float *ms_host);
 
+/*
+ * How sja_resolve runs the rounds of Sec. 3.5's grant phase.  Both modes give
+ * the same grants, rounds_used and stable flag; they differ in speed only.
+ *   SJA_RESOLVE_LISTS   per-gap candidate lists in preference order, one cheap
+ *                       launch per round (the default).  Falls back to the
+ *                       other mode by itself with more than 64 distinct
+ *                       capacities or when the lists would not fit the workspace.
+ *   SJA_RESOLVE_MATRIX  every round re-scans the cut matrix rows of the gaps
+ *                       that are still ungranted.
+ * SJA_ERR_SIZE for any other value.
+ */
+typedef enum {
+    SJA_RESOLVE_LISTS = 0,
+    SJA_RESOLVE_MATRIX = 1
+} sja_resolve_mode;
+int sja_set_resolve_mode(sja_ctx *ctx, int mode);
+
 #ifdef __cplusplus
 }
 #endif

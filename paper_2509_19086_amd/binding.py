@@ -74,6 +74,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_enable_timing.restype = ctypes.c_int
     lib.sja_last_fit_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.sja_last_fit_kernel_ms.restype = ctypes.c_int
+    lib.sja_set_resolve_mode.argtypes = [vp, ctypes.c_int]
+    lib.sja_set_resolve_mode.restype = ctypes.c_int
     if path is None:
         _lib = lib
     return lib
@@ -139,6 +141,10 @@ class Engine:
 
     def sja_enable_timing(self, on: bool) -> None:
         self._check(self.lib.sja_enable_timing(self.h, int(on)), self.h)
+
+    def sja_set_resolve_mode(self, mode: int) -> None:
+        """0 = candidate lists (default), 1 = matrix-scanning rounds."""
+        self._check(self.lib.sja_set_resolve_mode(self.h, int(mode)), self.h)
 
     def sja_last_fit_kernel_ms(self) -> float:
         ms = ctypes.c_float()

@@ -268,71 +268,39 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
     rec[i] = make_uint4(uint32_t(ja.x), uint32_t(ja.y), lo | (hi << 8), 0u);
 }
 
-// One round, one wave per list block, one lane per gap position.  First the
-// outcome of round k-1: a gap whose candidate job carries the gap's own claim
-// word has won (the grant is final), otherwise it lost.  Then, if `propose`,
-// every lane that still needs a job walks on from its own pointer, eight
-// records per memory round trip, to the first entry that covers it and whose
-// job is not held.  state[s] = (pointer, candidate job, candidate atom, flag)
-// with flag 0 = active, 1 = granted, 2 = no candidate left.
-constexpr int kWalk = 8;
+// One round for one list block (one wave, one lane per gap position).  First
+// the outcome of round k-1: a gap whose candidate job carries the gap's own
+// claim word has won (the grant is final), otherwise it lost.  Then, if
+// `propose`, every lane that still needs a job walks on from its own pointer to
+// the first entry that covers it and whose job is not held, and claims it.
+// st = (pointer, candidate job, candidate atom, flag) with flag 0 = active,
+// 1 = granted, 2 = no candidate left.  r[] holds the records at st.x on entry.
+constexpr int kWalk = 8;         // records a lane reads per trip on its own
 constexpr int kSweep = 4;        // chunks of 64 records the wave reads per trip when it walks together
-constexpr int kOwnTrips = 1;      // batches a lane walks alone before the wave walks together
+constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
 
-__global__ __launch_bounds__(256) void k_grant_round(
-    int round, int propose, int n_jobs, PolicyDev pol, const int32_t *__restrict__ plan,
-    const int32_t *__restrict__ lb_begin, const int32_t *__restrict__ lb_end,
-    const int32_t *__restrict__ list_off, const int32_t *__restrict__ gap_order,
-    const uint4 *__restrict__ rec, unsigned long long *claim, int4 *state, int32_t *cnt_lost,
-    int32_t *cnt_cand, const int64_t *__restrict__ seg_off, const int2 *__restrict__ atom_dp,
-    const int2 *__restrict__ atom_db, const int32_t *__restrict__ wait,
-    const uint8_t *__restrict__ sla_class, int32_t *grant_job, int32_t *grant_cut, int64_t *grant_score,
-    int32_t *job_gap)
+__device__ __forceinline__ void grant_step(int round, bool propose, int lane, int g, int list_begin, int list_end,
+                                           const uint4 *__restrict__ rec, unsigned long long *claim, int4 &st,
+                                           uint4 (&r)[kWalk], bool &lost, bool &cand)
 {
-    const int u = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (u >= plan[kPlanListBlocks]) return;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int b0 = lb_begin[u];
-    const bool valid = lane < lb_end[u] - b0;
-    const int s = b0 + lane;
-    const int list_end = list_off[u + 1];
-    int g = 0;
-    int4 st = make_int4(list_off[u], -1, -1, valid ? 0 : 2);
-    if (valid) {
-        g = gap_order[s];
-        if (round > 1) st = state[s];
-    }
-    // In flight together: the claim word of last round's candidate and, speculatively,
-    // the first records of the walk that follows if the gap lost.
-    const bool may_walk = st.w == 0 && propose != 0;
-    uint4 r[kWalk];
-    if (may_walk) {
-#pragma unroll
-        for (int t = 0; t < kWalk; ++t) r[t] = rec[max(min(st.x + t, list_end - 1), 0)];
-    }
-    const unsigned long long last_word = (st.w == 0 && st.y >= 0) ? claim[st.y] : 0ull;
-    bool lost = false;
+    lost = false;
+    cand = false;
     if (st.w == 0 && st.y >= 0) {
-        if (last_word == claim_of(round - 1, g)) {
-            st.w = 1;                  // won: final; k_grant_finish writes the grant itself
-            state[s].w = 1;
-        } else {
-            lost = true;
-        }
+        if (claim[st.y] == claim_of(round - 1, g)) st.w = 1;      // won: final
+        else lost = true;
     }
-    bool cand = false;
     int cand_job = -1;
     unsigned long long cand_word = 0;      // the candidate job's claim word as the walk saw it
-    const bool walking = st.w == 0 && propose != 0;
+    const bool walking = st.w == 0 && propose;
     int e = st.x, found = -1, found_j = -1, found_a = -1;
     if (walking) {
-        // own walk: a few batches, every lane from its own pointer
+        // own walk: every lane from its own pointer
         for (int trip = 0; e < list_end; ++trip) {
             unsigned long long c[kWalk];
 #pragma unroll
             for (int t = 0; t < kWalk; ++t) {
                 const bool covers = e + t < list_end && lane >= int(r[t].z & 255u) && lane < int(r[t].z >> 8);
-                c[t] = covers ? claim[r[t].x] : ~0ull;        // a huge stamp of an earlier round: "held"
+                c[t] = covers ? claim[r[t].x] : ~0ull;   // a huge stamp of an earlier round: "held"
                 if (!covers) r[t].z = 0;
             }
 #pragma unroll
@@ -353,7 +321,6 @@ __global__ __launch_bounds__(256) void k_grant_round(
     // per round; every lane whose pointer lies in that span takes the first free
     // record at or after its pointer that covers the lane, or moves on past the span.
     {
-        const int list_begin = list_off[u];
         bool looking = walking && found < 0 && e < list_end;
         for (;;) {
             if (!__ballot(looking)) break;
@@ -412,11 +379,11 @@ __global__ __launch_bounds__(256) void k_grant_round(
     }
     if (walking) {
         if (found >= 0) {
-            state[s] = make_int4(found + 1, found_j, found_a, 0);
+            st = make_int4(found + 1, found_j, found_a, 0);
             cand = true;
             cand_job = found_j;
         } else {
-            state[s] = make_int4(list_end, -1, -1, 2);
+            st = make_int4(list_end, -1, -1, 2);
         }
     }
     // Claims.  Most gaps of a batch name the same few jobs in a round, so the
@@ -436,7 +403,40 @@ __global__ __launch_bounds__(256) void k_grant_round(
         }
         todo &= ~__ballot(mine);
     }
-    // the host only asks whether anybody lost / anybody selected in a round
+}
+
+// One round per launch.  A round leaves two flags: somebody lost (round k-1),
+// somebody selected (round k); the host only asks those two questions.
+__global__ __launch_bounds__(256) void k_grant_round(
+    int round, int propose, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
+    const int32_t *__restrict__ lb_end, const int32_t *__restrict__ list_off,
+    const int32_t *__restrict__ gap_order, const uint4 *__restrict__ rec, unsigned long long *claim,
+    int4 *state, int32_t *cnt_lost, int32_t *cnt_cand)
+{
+    const int u = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (u >= plan[kPlanListBlocks]) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int b0 = lb_begin[u];
+    const bool valid = lane < lb_end[u] - b0;
+    const int s = b0 + lane;
+    const int list_begin = list_off[u], list_end = list_off[u + 1];
+    int g = 0;
+    int4 st = make_int4(list_begin, -1, -1, valid ? 0 : 2);
+    if (valid) {
+        g = gap_order[s];
+        if (round > 1) st = state[s];
+    }
+    // in flight together with the claim word of last round's candidate: the
+    // first records of the walk that follows if the gap lost
+    uint4 r[kWalk];
+    if (st.w == 0 && propose != 0) {
+#pragma unroll
+        for (int t = 0; t < kWalk; ++t) r[t] = rec[max(min(st.x + t, list_end - 1), 0)];
+    }
+    const int4 before = st;
+    bool lost, cand;
+    grant_step(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, r, lost, cand);
+    if (valid && (st.x != before.x || st.w != before.w || round == 1)) state[s] = st;
     if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;
     if (__ballot(cand) && lane == 0) cnt_cand[round] = 1;
 }

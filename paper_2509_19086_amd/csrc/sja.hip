@@ -257,17 +257,21 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
         SJA_HIP(hipGetLastError(), "k_list_pack launch");
     }
 
-    // 4. rounds, in batches between looks at the counters
+    // 4. rounds
     int32_t *cnt_lost = ws_ptr<int32_t>(ctx, L.g_cnt_lost), *cnt_cand = ws_ptr<int32_t>(ctx, L.g_cnt_cand);
     const int64_t rounds_cap = int64_t(G < J ? G : J) + 4;
     hipLaunchKernelGGL(k_fill_i32, dim3(unsigned((rounds_cap + 255) / 256)), dim3(256), 0, st, cnt_lost, rounds_cap, 0);
     hipLaunchKernelGGL(k_fill_i32, dim3(unsigned((rounds_cap + 255) / 256)), dim3(256), 0, st, cnt_cand, rounds_cap, 0);
     SJA_HIP(hipGetLastError(), "counter fill launch");
+    const int32_t *gap_order = ws_ptr<int32_t>(ctx, L.gap_order);
+    unsigned long long *claim = ws_ptr<unsigned long long>(ctx, L.res_claim);
+    int4 *state = ws_ptr<int4>(ctx, L.g_state);
+    const int round_grid = (n_subs + 3) / 4;
+
+    // one launch per round, in batches between looks at the flags
     auto launch_round = [&](int64_t k, int propose) {
-        hipLaunchKernelGGL(k_grant_round, dim3((n_subs + 3) / 4), dim3(256), 0, st, int(k), propose, J, pol, plan,
-                           lb_begin, lb_end, list_off, ws_ptr<int32_t>(ctx, L.gap_order), rec,
-                           ws_ptr<unsigned long long>(ctx, L.res_claim), ws_ptr<int4>(ctx, L.g_state), cnt_lost, cnt_cand,
-                           ctx->seg_off, atom_dp, atom_db, wait, sla_class, grant_job, grant_cut, grant_score, job_gap);
+        hipLaunchKernelGGL(k_grant_round, dim3(round_grid), dim3(256), 0, st, int(k), propose, plan, lb_begin, lb_end,
+                           list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand);
         return hipGetLastError();
     };
     std::vector<int32_t> h_lost, h_cand;
@@ -371,6 +375,15 @@ int sja_enable_timing(sja_ctx *ctx, int on)
     if (!ctx) return SJA_ERR_NULL;
     ctx->timing = on != 0;
     ctx->timed = false;
+    return SJA_OK;
+}
+
+int sja_set_resolve_mode(sja_ctx *ctx, int mode)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (mode != SJA_RESOLVE_LISTS && mode != SJA_RESOLVE_MATRIX)
+        return fail(ctx, SJA_ERR_SIZE, "sja_set_resolve_mode: unknown mode");
+    ctx->resolve_mode = mode;
     return SJA_OK;
 }
 
@@ -559,7 +572,7 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
     const int64_t cap = (params->max_rounds > 0 && params->max_rounds < natural) ? params->max_rounds : natural;
     int32_t result[2] = {0, 0};
     bool done = false;
-    if (G > 0 && J > 0) {
+    if (G > 0 && J > 0 && ctx->resolve_mode != SJA_RESOLVE_MATRIX) {
         rc = resolve_with_lists(ctx, st, L, params, wait, sla_class, grant_job, grant_cut, grant_score, job_gap, cap,
                                 result, &done);
         if (rc != SJA_OK) return rc;

@@ -195,6 +195,9 @@ struct sja_ctx {
     bool timed;
     hipEvent_t ev_start, ev_stop;
 
+    // how sja_resolve runs its rounds (sja_set_resolve_mode)
+    int resolve_mode;
+
     // state left by sja_fit
     bool fitted;
     int32_t n_gaps;

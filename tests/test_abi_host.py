@@ -85,6 +85,19 @@ def test_policy_parameter_validation(lib):
     assert ctypes.sizeof(P.Params) == 28
 
 
+def test_resolve_mode_validation(lib):
+    """The mode switch is host bookkeeping only: known values are taken, others refused."""
+    h = ctypes.c_void_p()
+    assert lib.sja_create(ctypes.byref(h), 0) == 0
+    try:
+        assert lib.sja_set_resolve_mode(h, 0) == 0
+        assert lib.sja_set_resolve_mode(h, 1) == 0
+        assert lib.sja_status_string(lib.sja_set_resolve_mode(h, 7)) == b"SJA_ERR_SIZE"
+        assert lib.sja_status_string(lib.sja_set_resolve_mode(None, 0)) == b"SJA_ERR_NULL"
+    finally:
+        lib.sja_destroy(h)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     import paper_2509_19086_amd as P

@@ -29,8 +29,10 @@ def _oracle_params(O, wl, policy=None, max_rounds=None):
                          wl.class0_override, wl.max_rounds if max_rounds is None else max_rounds)
 
 
-def full_tick_check(engine, oracle, wl, policies=None, check_resolve=True):
-    """prepare, fit, select (each policy), resolve: every output equals the oracle's."""
+def full_tick_check(engine, oracle, wl, policies=None, check_resolve=True, resolve_modes=(0, 1)):
+    """prepare, fit, select (each policy), resolve: every output equals the oracle's.
+    Resolve runs once per mode (candidate lists / matrix-scanning rounds): each
+    must reproduce the oracle's rounds exactly."""
     import torch
     import paper_2509_19086_amd as P
     t = P.DeviceTick(engine, wl)
@@ -57,14 +59,21 @@ def full_tick_check(engine, oracle, wl, policies=None, check_resolve=True):
         np.testing.assert_array_equal(t.cand_cut.cpu().numpy(), cc)
         np.testing.assert_array_equal(t.cand_score.cpu().numpy(), cs)
         if check_resolve:
-            t.resolve(par)
             gj, gc, gs, jg, rounds, stable = oracle.resolve(
                 cut, wl.seg_off, pd, pp, _oracle_params(oracle, wl, policy), wl.wait, wl.sla_class)
-            np.testing.assert_array_equal(t.grant_job.cpu().numpy(), gj)
-            np.testing.assert_array_equal(t.grant_cut.cpu().numpy(), gc)
-            np.testing.assert_array_equal(t.grant_score.cpu().numpy(), gs)
-            np.testing.assert_array_equal(t.job_gap.cpu().numpy(), jg)
-            assert t.rounds.cpu().tolist() == [rounds, stable]
+            try:
+                for mode in resolve_modes:
+                    engine.sja_set_resolve_mode(mode)
+                    for out in (t.grant_job, t.grant_cut, t.grant_score, t.job_gap, t.rounds):
+                        out.fill_(-5)
+                    t.resolve(par)
+                    np.testing.assert_array_equal(t.grant_job.cpu().numpy(), gj, err_msg=f"mode {mode}")
+                    np.testing.assert_array_equal(t.grant_cut.cpu().numpy(), gc, err_msg=f"mode {mode}")
+                    np.testing.assert_array_equal(t.grant_score.cpu().numpy(), gs, err_msg=f"mode {mode}")
+                    np.testing.assert_array_equal(t.job_gap.cpu().numpy(), jg, err_msg=f"mode {mode}")
+                    assert t.rounds.cpu().tolist() == [rounds, stable], f"mode {mode}"
+            finally:
+                engine.sja_set_resolve_mode(0)
     return t
 
 
