@@ -64,13 +64,12 @@ __global__ __launch_bounds__(256) void k_gap_rank(int n_gaps, const int32_t *__r
     if (g < n_gaps && r) atomicAdd(&rank[g], r);
 }
 
-// Sorted copies of the gaps plus, per sorted position, the element offsets of
-// the gap's cut row and interest row.
-__global__ void k_gap_scatter(int n_gaps, int n_jobs, int words, const int32_t *__restrict__ W,
+// Sorted copies of the gaps plus, per sorted position, the element offset of
+// the gap's cut row.
+__global__ void k_gap_scatter(int n_gaps, int n_jobs, const int32_t *__restrict__ W,
                               const int32_t *__restrict__ C, const int32_t *__restrict__ rank,
                               int32_t *__restrict__ order, int32_t *__restrict__ ws,
-                              int32_t *__restrict__ cs, int64_t *__restrict__ row,
-                              int64_t *__restrict__ brow)
+                              int32_t *__restrict__ cs, int64_t *__restrict__ row)
 {
     const int g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= n_gaps) return;
@@ -79,7 +78,6 @@ __global__ void k_gap_scatter(int n_gaps, int n_jobs, int words, const int32_t *
     ws[r] = W[g];
     cs[r] = C[g];
     row[r] = int64_t(g) * n_jobs;
-    brow[r] = int64_t(g) * words;
 }
 
 // run_end[s] = first sorted position after s whose capacity differs.
@@ -107,7 +105,7 @@ __global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int sb, i
                                                    int32_t *chunk_begin, int32_t *chunk_end,
                                                    int32_t *chunk_class, int32_t *chunk_sub,
                                                    int32_t *sub_begin, int32_t *sub_end,
-                                                   int32_t *sub_class)
+                                                   int32_t *sub_class, int32_t *gap_cls)
 {
     __shared__ int s_cnt[1024];
     __shared__ int s_classes, s_chunks, s_tabled, s_subs;
@@ -127,6 +125,13 @@ __global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int sb, i
     __syncthreads();
     const int n_classes = s_classes;
     const bool tabled = s_tabled != 0;
+    {   // capacity class of every sorted position
+        int k = s_cnt[t];
+        for (int s = lo; s < hi; ++s) {
+            k += (s == 0) || (cs[s] != cs[s - 1]);
+            gap_cls[s] = k - 1;
+        }
+    }
     if (tabled) {
         int k = s_cnt[t];
         for (int s = lo; s < hi; ++s)
@@ -276,15 +281,10 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     const int32_t *__restrict__ start_tab,
     const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ gap_w,
     const int32_t *__restrict__ gap_c, const int64_t *__restrict__ gap_row,
-    const int64_t *__restrict__ gap_brow, const int32_t *__restrict__ gap_run_end,
-    int32_t *__restrict__ cut, uint32_t *__restrict__ bits, int words)
+    const int32_t *__restrict__ gap_run_end, int32_t *__restrict__ cut)
 {
     static_assert((CAP & (CAP - 1)) == 0 && PERIOD % 4 == 0 && BLOCK % kWave == 0, "tile shape");
-    constexpr int WAVES = BLOCK / kWave;
     __shared__ int2 win[CAP][BLOCK];
-    static_assert(sizeof(int2) * CAP * BLOCK >= sizeof(unsigned long long) * kFitMaxChunk * WAVES,
-                  "the interest words reuse the window memory at the end");
-    static_assert(kFitMaxChunk <= 4 * kWave, "four interest words per lane cover a chunk");
 
     // Blocks of one job tile sit on one XCD (block ids are dealt round-robin
     // over the 8 XCDs): its atoms and tables stay in that XCD's L2.
@@ -295,7 +295,6 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     if (job_tile * BLOCK >= n_jobs || chunk >= plan[kPlanChunks]) return;
     const bool tabled = plan[kPlanTabled] != 0;
     const int tid = threadIdx.x;
-    const int wave = tid / kWave;
     const int j_raw = job_tile * BLOCK + tid;
     const bool live = j_raw < n_jobs;
     const int j = live ? j_raw : n_jobs - 1;   // spare lanes shadow the last job: same value, same address
@@ -313,7 +312,6 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     int nd2 = 0, nb2 = 0;   // atom a + 1 (meaningful while a + 1 < hi)
     int c_cur = 0;
     unsigned long long dry_mask = 0;   // lanes with hi < n_cap: reaching hi may leave atoms unpassed
-    bool all_in = false;               // every live lane of the wave is interested (stays so within a class)
 
     auto init = [&](int s) {
         c_cur = gap_c[s];
@@ -326,7 +324,6 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         }
         cur = a > 0 ? db[a - 1].y : -1;
         hi = a;
-        all_in = false;
     };
     auto reload = [&]() {
         const int2 x = win[a & (CAP - 1)][tid]; nd = x.x; nb = x.y;
@@ -344,12 +341,6 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
         hi = max(hi, want);
         reload();
     };
-    const unsigned long long live_mask = __ballot(live);
-    // Interest words of this wave, one per step, kept in registers until the block
-    // is done: lane l holds steps 4l .. 4l+3.  They default to "all interested";
-    // the steps before that holds overwrite them.
-    const int lane = tid & (kWave - 1);
-    unsigned long long bw[4] = {live_mask, live_mask, live_mask, live_mask};
     constexpr unsigned ROW = BLOCK * sizeof(int2);     // bytes per window slot row (a power of two)
     static_assert((ROW & (ROW - 1)) == 0, "BLOCK must be a power of two");
     const unsigned lds_lane = unsigned(tid) * unsigned(sizeof(int2));
@@ -358,8 +349,7 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     // two atoms of each lane sit in registers, so no LDS answer is needed before
     // the loop condition is known; it repeats only while some lane passes a
     // further atom.
-    // q = (s - s_begin) % 4 (a compile-time constant on the unrolled path)
-    auto step = [&](int w, int s, int64_t row, int q) {
+    auto step = [&](int w, int64_t row) {
         bool adv = a < hi && nd <= w;
         if (__any(adv)) {
             do {
@@ -387,14 +377,6 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
             } while (__any(adv));
         }
         (cut + row)[j] = cur;
-        if (bits && !all_in) {
-            const unsigned long long m = __ballot(cur >= 0) & live_mask;
-            const bool mine = lane == ((s - s_begin) >> 2);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (i == q) bw[i] = mine ? m : bw[i];
-            all_in = m == live_mask;
-        }
     };
 
     for (int s0 = s_begin; s0 < s_end; s0 += PERIOD) {
@@ -410,32 +392,102 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
                 const int64_t rv[4] = {gap_row[s0 + u4], gap_row[s0 + u4 + 1], gap_row[s0 + u4 + 2],
                                        gap_row[s0 + u4 + 3]};
 #pragma unroll
-                for (int u = 0; u < 4; ++u) step(wv[u], s0 + u4 + u, rv[u], u);   // s0 - s_begin is a multiple of 4
+                for (int u = 0; u < 4; ++u) step(wv[u], rv[u]);
             }
         } else {
             for (int s = s0; s < s1; ++s) {
                 if (gap_c[s] != c_cur) { init(s); topup(); dry_mask = __ballot(hi < n_cap); wait_vmem(); }
-                step(gap_w[s], s, gap_row[s], (s - s_begin) & 3);
+                step(gap_w[s], gap_row[s]);
             }
         }
     }
+}
 
-    if (bits) {
-        // one interest row piece per gap position: WAVES * 8 contiguous bytes
-        __syncthreads();      // every wave is done with the window: its memory now collects the words
-        unsigned long long *bal = reinterpret_cast<unsigned long long *>(&win[0][0]);   // [step][wave]
+// --------------------------------------------------------------------------
+// Interest rows.  A job answers a gap with interest exactly when its first
+// atom fits (running duration and running peak only grow along the atoms), so
+// bit j of a gap's row is D_first(j) <= W && P_first(j) <= C.  Per (capacity
+// class, 32-job word) a small table holds the word of jobs whose first atom
+// fits the capacity and the smallest and largest first duration among them:
+// a window at or above the largest gives that word, one below the smallest
+// gives 0, and only windows in between (a few hundred ticks at the bottom of a
+// class) look at the 32 jobs one by one.  One thread per (gap, word); a wave
+// stores 256 contiguous bytes of a row.
+// --------------------------------------------------------------------------
+__device__ __forceinline__ int4 bits_word_entry(int n_jobs, int j0, int c, const int2 *__restrict__ first_dp)
+{
+    int2 f[32];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (lane * 4 + q < s_end - s_begin) bal[(lane * 4 + q) * WAVES + wave] = bw[q];
-        __syncthreads();
-        constexpr int WPR = 2 * WAVES;
-        const uint32_t *bal32 = reinterpret_cast<const uint32_t *>(bal);
-        const int word0 = (job_tile * BLOCK) >> 5;
-        const int total = (s_end - s_begin) * WPR;
-        for (int i = tid; i < total; i += BLOCK) {
-            const int slot = i / WPR, wi = i % WPR;
-            if (word0 + wi < words) bits[gap_brow[s_begin + slot] + word0 + wi] = bal32[i];
+    for (int b = 0; b < 32; ++b) f[b] = first_dp[min(j0 + b, n_jobs - 1)];
+    uint32_t fits = 0;
+    int d_min = INT32_MAX, d_max = INT32_MIN;
+#pragma unroll
+    for (int b = 0; b < 32; ++b) {
+        if (j0 + b < n_jobs && f[b].y <= c && f[b].x != INT32_MAX) {
+            fits |= 1u << b;
+            d_min = min(d_min, f[b].x);
+            d_max = max(d_max, f[b].x);
         }
+    }
+    return make_int4(int(fits), d_min, d_max, 0);
+}
+
+// table[c][word] for the classes of the table-driven plan
+__global__ __launch_bounds__(256) void k_bits_table(int n_jobs, int words, const int32_t *__restrict__ plan,
+                                                    const int32_t *__restrict__ class_begin,
+                                                    const int32_t *__restrict__ gap_c,
+                                                    const int2 *__restrict__ first_dp, int4 *__restrict__ table)
+{
+    const int word = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = blockIdx.y;
+    if (!plan[kPlanTabled] || c >= plan[kPlanClasses] || word >= words) return;
+    table[int64_t(c) * words + word] = bits_word_entry(n_jobs, word * 32, gap_c[class_begin[c]], first_dp);
+}
+
+constexpr int kBitsRows = 8;       // gaps per block
+
+// Rows are taken in the caller's gap order, so the blocks write the interest
+// matrix front to back.
+__global__ __launch_bounds__(256) void k_fit_bits(int n_jobs, int n_gaps, int words,
+                                                  const int32_t *__restrict__ plan,
+                                                  const int2 *__restrict__ first_dp,
+                                                  const int4 *__restrict__ table,
+                                                  const int32_t *__restrict__ gap_rank,
+                                                  const int32_t *__restrict__ gap_cls,
+                                                  const int32_t *__restrict__ gap_w,
+                                                  const int32_t *__restrict__ gap_c,
+                                                  uint32_t *__restrict__ bits)
+{
+    const int word = blockIdx.x * blockDim.x + threadIdx.x;
+    if (word >= words) return;
+    const bool tabled = plan[kPlanTabled] != 0;
+    const int j0 = word * 32;
+    const int g_begin = blockIdx.y * kBitsRows, g_end = min(n_gaps, g_begin + kBitsRows);
+    int pos[kBitsRows];
+#pragma unroll
+    for (int r = 0; r < kBitsRows; ++r) pos[r] = gap_rank[min(g_begin + r, n_gaps - 1)];
+    int cls = -1;
+    int4 e = make_int4(0, INT32_MAX, INT32_MIN, 0);
+#pragma unroll
+    for (int r = 0; r < kBitsRows; ++r) {
+        const int g = g_begin + r;
+        if (g >= g_end) break;
+        const int s = pos[r];
+        const int w = gap_w[s];
+        if (tabled) {
+            const int c = gap_cls[s];
+            if (c != cls) { cls = c; e = table[int64_t(c) * words + word]; }
+        } else {
+            e = bits_word_entry(n_jobs, j0, gap_c[s], first_dp);
+        }
+        uint32_t v = 0;
+        if (w >= e.z) {
+            v = uint32_t(e.x);
+        } else if (w >= e.y) {
+            for (int b = 0; b < 32; ++b)
+                if ((uint32_t(e.x) >> b) & 1u) v |= (first_dp[j0 + b].x <= w ? 1u : 0u) << b;
+        }
+        bits[int64_t(g) * words + word] = v;
     }
 }
 

@@ -421,7 +421,7 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
         hipLaunchKernelGGL(k_prepare, dim3((n_jobs + jobs_per_block - 1) / jobs_per_block), dim3(256), 0, st,
                            n_jobs, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe,
                            ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),
-                           ws_ptr<int32_t>(ctx, L.n_atoms));
+                           ws_ptr<int32_t>(ctx, L.n_atoms), ws_ptr<int2>(ctx, L.first_dp));
         SJA_HIP(hipGetLastError(), "k_prepare launch");
     }
     ctx->n_jobs = n_jobs;
@@ -465,9 +465,8 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
         hipLaunchKernelGGL(k_gap_rank, dim3((n_gaps + 255) / 256, (n_gaps + kRankSpan - 1) / kRankSpan), b256, 0, st,
                            n_gaps, W, C, rank);
         SJA_HIP(hipGetLastError(), "k_gap_rank launch");
-        hipLaunchKernelGGL(k_gap_scatter, per_gap, b256, 0, st, n_gaps, J, words, W, C, rank,
-                           ws_ptr<int32_t>(ctx, L.gap_order), gw, gcap,
-                           ws_ptr<int64_t>(ctx, L.gap_row), ws_ptr<int64_t>(ctx, L.gap_brow));
+        hipLaunchKernelGGL(k_gap_scatter, per_gap, b256, 0, st, n_gaps, J, W, C, rank,
+                           ws_ptr<int32_t>(ctx, L.gap_order), gw, gcap, ws_ptr<int64_t>(ctx, L.gap_row));
         SJA_HIP(hipGetLastError(), "k_gap_scatter launch");
         if (J > 0) {
             hipLaunchKernelGGL(k_gap_run_end, per_gap, b256, 0, st, n_gaps, gcap,
@@ -478,7 +477,8 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
                                ws_ptr<int32_t>(ctx, L.class_sub0), ws_ptr<int32_t>(ctx, L.chunk_begin),
                                ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
                                ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.sub_begin),
-                               ws_ptr<int32_t>(ctx, L.sub_end), ws_ptr<int32_t>(ctx, L.sub_class));
+                               ws_ptr<int32_t>(ctx, L.sub_end), ws_ptr<int32_t>(ctx, L.sub_class),
+                               ws_ptr<int32_t>(ctx, L.gap_cls));
             SJA_HIP(hipGetLastError(), "k_gap_plan launch");
             hipLaunchKernelGGL(k_fit_starts, dim3((J + 255) / 256, kMaxClasses), b256, 0, st, J, sb, plan,
                                ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_sub0), gw, gcap,
@@ -502,12 +502,22 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
                                ws_ptr<int32_t>(ctx, L.chunk_class), ws_ptr<int32_t>(ctx, L.chunk_sub),
                                ws_ptr<int32_t>(ctx, L.start_tab),
                                ws_ptr<int32_t>(ctx, L.ncap_tab), gw, gcap, ws_ptr<int64_t>(ctx, L.gap_row),
-                               ws_ptr<int64_t>(ctx, L.gap_brow), ws_ptr<int32_t>(ctx, L.gap_run_end), cut,
-                               interest_bits, words);
+                               ws_ptr<int32_t>(ctx, L.gap_run_end), cut);
             SJA_HIP(hipGetLastError(), "k_fit_main launch");
             if (ctx->timing) {
                 SJA_HIP(hipEventRecord(ctx->ev_stop, st), "hipEventRecord");
                 ctx->timed = true;
+            }
+            if (interest_bits) {
+                int4 *table = ws_ptr<int4>(ctx, L.bits_table);
+                hipLaunchKernelGGL(k_bits_table, dim3((words + 255) / 256, kMaxClasses), b256, 0, st, J, words, plan,
+                                   ws_ptr<int32_t>(ctx, L.class_begin), gcap, ws_ptr<int2>(ctx, L.first_dp), table);
+                SJA_HIP(hipGetLastError(), "k_bits_table launch");
+                const dim3 bits_grid((words + 255) / 256, (n_gaps + kBitsRows - 1) / kBitsRows);
+                hipLaunchKernelGGL(k_fit_bits, bits_grid, b256, 0, st, J, n_gaps, words, plan,
+                                   ws_ptr<int2>(ctx, L.first_dp), table, ws_ptr<int32_t>(ctx, L.gap_rank),
+                                   ws_ptr<int32_t>(ctx, L.gap_cls), gw, gcap, interest_bits);
+                SJA_HIP(hipGetLastError(), "k_fit_bits launch");
             }
         }
     }

@@ -39,9 +39,12 @@ enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanSubBlocks = 3, k
 struct Layout {
     size_t atom_dp, atom_db;               // [S+8] int2 each: (dur, peak) and (dur, boundary)
     size_t n_atoms;                        // [J] int32
+    size_t first_dp;                       // [J] int2: a job's first atom (duration, peak), INT32_MAX twice if none
     size_t gap_rank, gap_order;            // [G] int32
     size_t gap_w, gap_c, gap_run_end;      // [G+16] int32, in sorted order
-    size_t gap_row, gap_brow;              // [G+16] int64: element offsets of a gap's rows
+    size_t gap_cls;                        // [G+16] int32: capacity class of a sorted position
+    size_t bits_table;                     // [kMaxClasses * ceil(J/32)] int4: per class and job word (fitting jobs, min, max first duration)
+    size_t gap_row;                        // [G+16] int64: element offset of a gap's cut row
     size_t plan;                           // [kPlanWords] int32 header
     size_t class_begin, class_chunk0, class_sub0;   // [kMaxClasses+1] int32
     size_t chunk_begin, chunk_end, chunk_class, chunk_sub;  // [chunk_bound] int32
@@ -112,13 +115,15 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.atom_dp = take(size_t(S + 8) * 8);
     L.atom_db = take(size_t(S + 8) * 8);
     L.n_atoms = take(size_t(J) * 4);
+    L.first_dp = take(size_t(J) * 8);
     L.gap_rank = take(size_t(G) * 4);
     L.gap_order = take(size_t(G) * 4);
     L.gap_w = take(size_t(G + 16) * 4);
     L.gap_c = take(size_t(G + 16) * 4);
     L.gap_run_end = take(size_t(G + 16) * 4);
+    L.gap_cls = take(size_t(G + 16) * 4);
+    L.bits_table = take(size_t(kMaxClasses) * size_t((J + 31) / 32) * 16);
     L.gap_row = take(size_t(G + 16) * 8);
-    L.gap_brow = take(size_t(G + 16) * 8);
     L.plan = take(kPlanWords * 4);
     L.class_begin = take((kMaxClasses + 1) * 4);
     L.class_chunk0 = take((kMaxClasses + 1) * 4);

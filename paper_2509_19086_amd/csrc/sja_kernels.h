@@ -46,7 +46,8 @@ __global__ __launch_bounds__(256) void k_prepare(
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
-    int2 *__restrict__ atom_dp, int2 *__restrict__ atom_db, int32_t *__restrict__ n_atoms)
+    int2 *__restrict__ atom_dp, int2 *__restrict__ atom_db, int32_t *__restrict__ n_atoms,
+    int2 *__restrict__ first_dp)
 {
     const int lane = lane_id();
     const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
@@ -57,6 +58,7 @@ __global__ __launch_bounds__(256) void k_prepare(
     p = p < 0 ? 0 : (p > L ? L : p);
 
     int carry_sum = 0, carry_peak = INT32_MIN, carry_last = -1, count = 0;
+    int first_d = INT32_MAX, first_p = INT32_MAX;     // the first atom, if there is one
     for (int k0 = p; k0 < L; k0 += kWave) {
         const int k = k0 + lane;
         const bool valid = k < L;
@@ -78,6 +80,11 @@ __global__ __launch_bounds__(256) void k_prepare(
             prev_safe[base + k] = l;
         }
         const unsigned long long mask = __ballot(flag);
+        if (count == 0 && mask) {
+            const int src = __ffsll((long long)mask) - 1;
+            first_d = __shfl(s, src, kWave);
+            first_p = __shfl(m, src, kWave);
+        }
         if (flag) {
             const int idx = count + __popcll(mask & lanes_below(lane));
             atom_dp[base + idx] = make_int2(s, m);
@@ -88,7 +95,10 @@ __global__ __launch_bounds__(256) void k_prepare(
         carry_peak = __shfl(m, kWave - 1, kWave);
         carry_last = __shfl(l, kWave - 1, kWave);
     }
-    if (lane == 0) n_atoms[j] = count;
+    if (lane == 0) {
+        n_atoms[j] = count;
+        first_dp[j] = make_int2(first_d, first_p);
+    }
 }
 
 }  // namespace sja
