@@ -14,10 +14,10 @@ namespace sja {
 constexpr int kWave = 64;
 
 // ---- tiling constants shared by host launch code and kernels -------------
-constexpr int kFitBlock = 256;        // threads per fit block, one job per thread
+constexpr int kFitBlock = 128;        // threads per fit block, one job per thread
 constexpr int kFitMaxChunk = 256;     // most sorted gap positions one fit block walks
-constexpr int kFitWindow = 8;         // atoms per job staged ahead in LDS (power of two)
-constexpr int kFitPeriod = 32;        // steps between window top-ups (multiple of 4)
+constexpr int kFitWindow = 16;        // atoms per job staged ahead in LDS (power of two)
+constexpr int kFitPeriod = 64;        // steps between window top-ups (multiple of 4)
 constexpr int kMaxClasses = 64;       // distinct capacities served by the table-driven path
 constexpr int kSelBlock = 256;        // threads per select block, one job per thread
 constexpr int kSelGapChunk = 128;     // sorted gap positions walked by one select block
