@@ -15,7 +15,7 @@ constexpr int kWave = 64;
 
 // ---- tiling constants shared by host launch code and kernels -------------
 constexpr int kFitBlock = 128;        // threads per fit block, one job per thread
-constexpr int kFitMaxChunk = 256;     // most sorted gap positions one fit block walks
+constexpr int kFitMaxChunk = 512;     // most sorted gap positions one fit block walks
 constexpr int kFitWindow = 16;        // atoms per job staged ahead in LDS (power of two)
 constexpr int kFitPeriod = 64;        // steps between window top-ups (multiple of 4)
 constexpr int kMaxClasses = 64;       // distinct capacities served by the table-driven path
