@@ -47,7 +47,8 @@
  * Data-dependent preconditions (not checked): seg_off non-decreasing with
  * seg_off[0] == 0 and seg_off[n_jobs] == n_segments; 0 <= progress[j] <= L_j;
  * dur >= 1; mem >= 0; per job, the sum of durations fits int32; every policy
- * score (see sja_params) fits int64.
+ * score term (see sja_params: F, or F times its weight) is below 2^62 (the
+ * arg-max packs a two-bit tier above it).
  */
 #ifndef SJA_H
 #define SJA_H
