@@ -118,6 +118,21 @@ def test_round_cap(engine, oracle):
         full_tick_check(engine, oracle, wl, policies=[0])
 
 
+@pytest.mark.parametrize("cap", [0, 64, 191, 192, 400])
+def test_long_chain_of_rounds(engine, oracle, cap):
+    """Hundreds of rounds: gaps that all want the same jobs are granted one per round, so the
+    resolve runs through several batches of round launches; caps inside a batch and at the
+    edges of one."""
+    wl = make_workload("small", 11, n_gaps=700, n_jobs=1200)
+    wl.W = np.full_like(wl.W, 1500)
+    wl.W[::7] += np.arange(len(wl.W[::7]), dtype=wl.W.dtype)          # a few gaps differ a little
+    wl.C = np.full_like(wl.C, 40960)
+    wl.max_rounds = cap
+    t = full_tick_check(engine, oracle, wl, policies=[0, 3], resolve_modes=(0,))
+    if cap == 0:
+        assert t.rounds.cpu().tolist()[0] > 448                        # past the third batch (64 + 128 + 256)
+
+
 def test_select_with_held_jobs_and_inactive_gaps(engine, oracle):
     import torch
     import paper_2509_19086_amd as P
