@@ -278,10 +278,13 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 constexpr int kWalk = 8;         // records a lane reads per trip on its own
 constexpr int kSweep = 4;        // chunks of 64 records the wave reads per trip when it walks together
 constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
+constexpr int kRoundBlock = 256; // threads per block of the round kernel
+constexpr int kBlockClaims = 256; // claims a block merges in LDS per round
 
 __device__ __forceinline__ void grant_step(int round, bool propose, int lane, int g, int list_begin, int list_end,
                                            const uint4 *__restrict__ rec, unsigned long long *claim, int4 &st,
-                                           uint4 (&r)[kWalk], bool &lost, bool &cand)
+                                           uint4 (&r)[kWalk], bool &lost, bool &cand, int *s_n, int *s_job,
+                                           unsigned long long *s_word)
 {
     lost = false;
     cand = false;
@@ -388,7 +391,10 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
     }
     // Claims.  Most gaps of a batch name the same few jobs in a round, so the
     // lanes of a wave that name one job first agree on their lowest gap index,
-    // and a claim that the job's word (as the walk read it) already beats is not sent.
+    // and a claim that the job's word (as the walk read it) already beats is not
+    // made.  The wave's claims go to the block's list (s_n, s_job, s_word); the
+    // block merges them before anything is sent (a claim that finds the list
+    // full is sent at once).
     unsigned long long todo = __ballot(cand);
     while (todo) {
         const int leader = __ffsll((long long)todo) - 1;
@@ -399,46 +405,72 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
         for (int d = 1; d < kWave; d <<= 1) best = max(best, (unsigned int)__shfl_xor(int(best), d, kWave));
         if (lane == leader) {
             const unsigned long long word = (static_cast<unsigned long long>(round) << 32) | best;
-            if (cand_word < word) atomicMax(&claim[job], word);
+            if (cand_word < word) {
+                const int slot = atomicAdd(s_n, 1);
+                if (slot < kBlockClaims) { s_job[slot] = job; s_word[slot] = word; }
+                else atomicMax(&claim[job], word);
+            }
         }
         todo &= ~__ballot(mine);
     }
 }
 
-// One round per launch.  A round leaves two flags: somebody lost (round k-1),
-// somebody selected (round k); the host only asks those two questions.
-__global__ __launch_bounds__(256) void k_grant_round(
+// One round per launch, several list blocks per thread block.  Hundreds of
+// waves name the same few jobs in a round and atomics on one word are served
+// one after the other, so the waves of a block first merge their claims in LDS
+// and the block sends one atomicMax per job.  A round leaves two flags: somebody
+// lost (round k-1), somebody selected (round k); the host only asks those two
+// questions.
+__global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     int round, int propose, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
     const int32_t *__restrict__ lb_end, const int32_t *__restrict__ list_off,
     const int32_t *__restrict__ gap_order, const uint4 *__restrict__ rec, unsigned long long *claim,
     int4 *state, int32_t *cnt_lost, int32_t *cnt_cand)
 {
-    const int u = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (u >= plan[kPlanListBlocks]) return;
+    __shared__ int s_n;
+    __shared__ int s_job[kBlockClaims];
+    __shared__ unsigned long long s_word[kBlockClaims];
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    const int u = blockIdx.x * (kRoundBlock / kWave) + (threadIdx.x / kWave);
     const int lane = threadIdx.x & (kWave - 1);
-    const int b0 = lb_begin[u];
-    const bool valid = lane < lb_end[u] - b0;
-    const int s = b0 + lane;
-    const int list_begin = list_off[u], list_end = list_off[u + 1];
-    int g = 0;
-    int4 st = make_int4(list_begin, -1, -1, valid ? 0 : 2);
-    if (valid) {
-        g = gap_order[s];
-        if (round > 1) st = state[s];
-    }
-    // in flight together with the claim word of last round's candidate: the
-    // first records of the walk that follows if the gap lost
-    uint4 r[kWalk];
-    if (st.w == 0 && propose != 0) {
+    if (u < plan[kPlanListBlocks]) {
+        const int b0 = lb_begin[u];
+        const bool valid = lane < lb_end[u] - b0;
+        const int s = b0 + lane;
+        const int list_begin = list_off[u], list_end = list_off[u + 1];
+        int g = 0;
+        int4 st = make_int4(list_begin, -1, -1, valid ? 0 : 2);
+        if (valid) {
+            g = gap_order[s];
+            if (round > 1) st = state[s];
+        }
+        uint4 r[kWalk];
+        if (st.w == 0 && propose != 0) {
 #pragma unroll
-        for (int t = 0; t < kWalk; ++t) r[t] = rec[max(min(st.x + t, list_end - 1), 0)];
+            for (int t = 0; t < kWalk; ++t) r[t] = rec[max(min(st.x + t, list_end - 1), 0)];
+        }
+        const int4 before = st;
+        bool lost, cand;
+        grant_step(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, r, lost, cand, &s_n, s_job, s_word);
+        if (valid && (st.x != before.x || st.w != before.w || round == 1)) state[s] = st;
+        if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;
+        if (__ballot(cand) && lane == 0) cnt_cand[round] = 1;
     }
-    const int4 before = st;
-    bool lost, cand;
-    grant_step(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, r, lost, cand);
-    if (valid && (st.x != before.x || st.w != before.w || round == 1)) state[s] = st;
-    if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;
-    if (__ballot(cand) && lane == 0) cnt_cand[round] = 1;
+    __syncthreads();
+    const int n = min(s_n, kBlockClaims);
+    for (int i = threadIdx.x; i < n; i += kRoundBlock) {
+        const int job = s_job[i];
+        unsigned long long word = s_word[i];
+        bool first = true;
+        for (int k = 0; k < n; ++k) {
+            if (s_job[k] == job) {
+                word = max(word, s_word[k]);
+                first = first && k >= i;
+            }
+        }
+        if (first) atomicMax(&claim[job], word);
+    }
 }
 
 // After the last round: the grants themselves.  A granted position still holds

@@ -266,11 +266,11 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     const int32_t *gap_order = ws_ptr<int32_t>(ctx, L.gap_order);
     unsigned long long *claim = ws_ptr<unsigned long long>(ctx, L.res_claim);
     int4 *state = ws_ptr<int4>(ctx, L.g_state);
-    const int round_grid = (n_subs + 3) / 4;
+    const int round_grid = (n_subs + kRoundBlock / kWave - 1) / (kRoundBlock / kWave);
 
     // one launch per round, in batches between looks at the flags
     auto launch_round = [&](int64_t k, int propose) {
-        hipLaunchKernelGGL(k_grant_round, dim3(round_grid), dim3(256), 0, st, int(k), propose, plan, lb_begin, lb_end,
+        hipLaunchKernelGGL(k_grant_round, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, plan, lb_begin, lb_end,
                            list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand);
         return hipGetLastError();
     };
