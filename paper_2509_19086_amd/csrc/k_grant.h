@@ -178,6 +178,31 @@ __global__ void k_list_blocks_write(int lb_cap, const int32_t *__restrict__ plan
 // already reaches atom a+1.  Every entry is one 64-bit word, v : rank : hi (7
 // bits) : lo (6 bits), stored wherever the running total puts it (the sort
 // orders them); entries beyond entry_cap are counted but not stored.
+// A block takes kEmitTiles tiles of 256 jobs for one list block: it counts
+// first, reserves its room with ONE addition to the running total (additions
+// to one word are served one after the other: one per wave made this kernel
+// three times slower), then writes.
+constexpr int kEmitTiles = 8;
+
+template <typename Sink>
+__device__ __forceinline__ void list_visit(const int2 *__restrict__ dp, const int *s_w, int len, int a_first, int n_cap,
+                                           Sink &&sink)
+{
+    const int a_begin = max(a_first - 1, 0);
+    int d_next = a_begin < n_cap ? dp[a_begin].x : 0;
+    for (int a = a_begin; a < n_cap; ++a) {
+        const int d_a = d_next;
+        const int lo = a < a_first ? 0 : count_less(s_w, len, d_a);
+        if (lo >= len) break;
+        int hi = len;
+        if (a + 1 < n_cap) {
+            d_next = dp[a + 1].x;
+            hi = count_less(s_w, len, d_next);
+        }
+        if (hi > lo) sink(a, lo, hi);
+    }
+}
+
 __global__ __launch_bounds__(256) void k_list_emit(
     int n_jobs, int rank_bits, int lb_cap, long long entry_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
     const int32_t *__restrict__ lb_end, const int32_t *__restrict__ lb_sub, const int32_t *__restrict__ sub_class,
@@ -188,66 +213,71 @@ __global__ __launch_bounds__(256) void k_list_emit(
     unsigned long long *__restrict__ ekey)
 {
     __shared__ int s_w[64];
+    __shared__ int s_total, s_cursor;
+    __shared__ unsigned long long s_base;
     const int u = blockIdx.y;                  // list block
     if (!plan[kPlanTabled] || u >= min(plan[kPlanListBlocks], lb_cap)) return;
     const int b0 = lb_begin[u], len = lb_end[u] - b0;
     if (threadIdx.x < 64) s_w[threadIdx.x] = threadIdx.x < len ? gap_w[b0 + threadIdx.x] : INT32_MAX;
+    if (threadIdx.x == 0) { s_total = 0; s_cursor = 0; }
     __syncthreads();
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
     const int lane = threadIdx.x & (kWave - 1);
-    const bool live = j < n_jobs;
-    int a_first = 0, n_cap = 0;
-    const int2 *dp = atom_dp;
-    if (live) {
-        const int sub = lb_sub[u];
-        a_first = start_tab[int64_t(sub) * n_jobs + j];
-        n_cap = ncap_tab[int64_t(sub_class[sub]) * n_jobs + j];
-        dp = atom_dp + seg_off[j];
-        // the table holds the count at the sub-block's first position; a later piece starts further on
-        while (a_first < n_cap && dp[a_first].x <= s_w[0]) ++a_first;
-    }
-    const int a_begin = max(a_first - 1, 0);
+    const int sub = lb_sub[u];
+    const int cls = sub_class[sub];
+    const int j0 = blockIdx.x * (kEmitTiles * 256) + threadIdx.x;
 
-    auto visit = [&](auto &&sink) {
-        int d_next = a_begin < n_cap ? dp[a_begin].x : 0;
-        for (int a = a_begin; a < n_cap; ++a) {
-            const int d_a = d_next;
-            const int lo = a < a_first ? 0 : count_less(s_w, len, d_a);
-            if (lo >= len) break;
-            int hi = len;
-            if (a + 1 < n_cap) {
-                d_next = dp[a + 1].x;
-                hi = count_less(s_w, len, d_next);
-            }
-            if (hi > lo) sink(a, lo, hi);
-        }
-    };
-
-    int cnt = 0;
-    visit([&](int, int, int) { ++cnt; });
-    // wave-wide totals
-    int incl = cnt;
+    int a_first[kEmitTiles], n_cap[kEmitTiles], cnt[kEmitTiles];
+    int mine = 0;
 #pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int t = __shfl_up(incl, d, kWave);
-        if (lane >= d) incl += t;
-    }
-    const int wave_total = __shfl(incl, kWave - 1, kWave);
-    {
-        unsigned long long wave_base = 0;
-        if (lane == 0 && wave_total) {
-            atomicAdd(&sub_count[u], wave_total);
-            wave_base = atomicAdd(total, (unsigned long long)wave_total);
+    for (int it = 0; it < kEmitTiles; ++it) {
+        const int j = j0 + it * 256;
+        a_first[it] = 0; n_cap[it] = 0; cnt[it] = 0;
+        if (j < n_jobs) {
+            int af = start_tab[int64_t(sub) * n_jobs + j];
+            const int nc = ncap_tab[int64_t(cls) * n_jobs + j];
+            const int2 *dp = atom_dp + seg_off[j];
+            // the table holds the count at the sub-block's first position; a later piece starts further on
+            while (af < nc && dp[af].x <= s_w[0]) ++af;
+            int c = 0;
+            list_visit(dp, s_w, len, af, nc, [&](int, int, int) { ++c; });
+            a_first[it] = af; n_cap[it] = nc; cnt[it] = c;
+            mine += c;
         }
-        wave_base = (unsigned long long)__shfl((long long)wave_base, 0, kWave);
-        if ((long long)(wave_base + wave_total) > entry_cap) return;
-        int64_t slot = int64_t(wave_base) + incl - cnt;
-        const int a0 = live ? abase[j] : 0;
-        visit([&](int a, int lo, int hi) {
-            ekey[slot] = ((((unsigned long long)u << rank_bits) | rank[a0 + a]) << kEntryLaneBits) |
-                         (unsigned long long)((hi << 6) | lo);
-            ++slot;
-        });
+    }
+    int wave_sum = mine;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) wave_sum += __shfl_xor(wave_sum, d, kWave);
+    if (lane == 0 && wave_sum) atomicAdd(&s_total, wave_sum);
+    __syncthreads();
+    if (threadIdx.x == 0 && s_total) {
+        atomicAdd(&sub_count[u], s_total);
+        s_base = atomicAdd(total, (unsigned long long)s_total);
+    }
+    __syncthreads();
+    const int block_total = s_total;
+    if (block_total == 0 || (long long)(s_base + block_total) > entry_cap) return;
+#pragma unroll
+    for (int it = 0; it < kEmitTiles; ++it) {
+        int incl = cnt[it];
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int t = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += t;
+        }
+        const int wave_total = __shfl(incl, kWave - 1, kWave);
+        int wave_off = 0;
+        if (lane == 0 && wave_total) wave_off = atomicAdd(&s_cursor, wave_total);
+        wave_off = __shfl(wave_off, 0, kWave);
+        if (cnt[it]) {
+            const int j = j0 + it * 256;
+            int64_t slot = int64_t(s_base) + wave_off + incl - cnt[it];
+            const int a0 = abase[j];
+            list_visit(atom_dp + seg_off[j], s_w, len, a_first[it], n_cap[it], [&](int a, int lo, int hi) {
+                ekey[slot] = ((((unsigned long long)u << rank_bits) | rank[a0 + a]) << kEntryLaneBits) |
+                             (unsigned long long)((hi << 6) | lo);
+                ++slot;
+            });
+        }
     }
 }
 

@@ -233,7 +233,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     // 3. list entries (one pass, counted as they are written), then sorted by (block, rank)
     const int rank_bits = bits_for(n_atoms > 1 ? n_atoms : 2);
     const int sub_bits = bits_for(n_subs > 1 ? n_subs : 2);
-    const dim3 emit_grid((J + 255) / 256, lb_bound);
+    const dim3 emit_grid((J + 256 * kEmitTiles - 1) / (256 * kEmitTiles), lb_bound);
     hipLaunchKernelGGL(k_list_emit, emit_grid, dim3(256), 0, st, J, rank_bits, lb_bound, (long long)L.entry_cap, plan,
                        lb_begin, lb_end, lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank,
                        list_off, reinterpret_cast<unsigned long long *>(counters), ekey[0]);
