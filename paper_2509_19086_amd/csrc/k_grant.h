@@ -304,7 +304,7 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // `propose`, every lane that still needs a job walks on from its own pointer to
 // the first entry that covers it and whose job is not held, and claims it.
 // st = (pointer, candidate job, candidate atom, flag) with flag 0 = active,
-// 1 = granted, 2 = no candidate left.  r[] holds the records at st.x on entry.
+// 1 = granted, 2 = no candidate left (in memory the flag shares its word with the gap index).  r[] holds the records at st.x on entry.
 constexpr int kWalk = 8;         // records a lane reads per trip on its own
 constexpr int kSweep = 4;        // chunks of 64 records the wave reads per trip when it walks together
 constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
@@ -452,7 +452,7 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
 // lost (round k-1), somebody selected (round k); the host only asks those two
 // questions.
 __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
-    int round, int propose, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
+    int round, int propose, int lb_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
     const int32_t *__restrict__ lb_end, const int32_t *__restrict__ list_off,
     const int32_t *__restrict__ gap_order, const uint4 *__restrict__ rec, unsigned long long *claim,
     int4 *state, int32_t *cnt_lost, int32_t *cnt_cand)
@@ -464,17 +464,20 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     __syncthreads();
     const int u = blockIdx.x * (kRoundBlock / kWave) + (threadIdx.x / kWave);
     const int lane = threadIdx.x & (kWave - 1);
+    // The state of a gap lives at (list block, lane) and carries the gap's index, so
+    // that its load needs none of the block tables and travels together with them.
+    const int slot = u * kWave + lane;
+    int4 raw = make_int4(0, -1, -1, 2);
+    if (round > 1 && u < lb_cap) raw = state[slot];
     if (u < plan[kPlanListBlocks]) {
-        const int b0 = lb_begin[u];
-        const bool valid = lane < lb_end[u] - b0;
-        const int s = b0 + lane;
         const int list_begin = list_off[u], list_end = list_off[u + 1];
-        int g = 0;
-        int4 st = make_int4(list_begin, -1, -1, valid ? 0 : 2);
-        if (valid) {
-            g = gap_order[s];
-            if (round > 1) st = state[s];
+        if (round == 1) {
+            const int b0 = lb_begin[u];
+            const bool valid = lane < lb_end[u] - b0;
+            raw = make_int4(list_begin, -1, -1, valid ? (gap_order[b0 + lane] << 2) : 2);
         }
+        const int g = raw.w >> 2;
+        int4 st = make_int4(raw.x, raw.y, raw.z, raw.w & 3);
         uint4 r[kWalk];
         if (st.w == 0 && propose != 0) {
 #pragma unroll
@@ -483,7 +486,7 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
         const int4 before = st;
         bool lost, cand;
         grant_step(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, r, lost, cand, &s_n, s_job, s_word);
-        if (valid && (st.x != before.x || st.w != before.w || round == 1)) state[s] = st;
+        if (st.x != before.x || st.w != before.w || round == 1) state[slot] = make_int4(st.x, st.y, st.z, st.w | (g << 2));
         if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;
         if (__ballot(cand) && lane == 0) cnt_cand[round] = 1;
     }
@@ -505,18 +508,18 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
 
 // After the last round: the grants themselves.  A granted position still holds
 // its winning (job, atom) in its state.
-__global__ void k_grant_finish(int n_gaps, PolicyDev pol, const int32_t *__restrict__ gap_order,
+__global__ void k_grant_finish(int lb_cap, PolicyDev pol, const int32_t *__restrict__ plan,
                                const int4 *__restrict__ state, const int64_t *__restrict__ seg_off,
                                const int2 *__restrict__ atom_dp, const int2 *__restrict__ atom_db,
                                const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
                                int32_t *grant_job, int32_t *grant_cut, int64_t *grant_score,
                                int32_t *job_gap)
 {
-    const int s = blockIdx.x * blockDim.x + threadIdx.x;
-    if (s >= n_gaps) return;
-    const int4 st = state[s];
-    if (st.w != 1) return;
-    const int g = gap_order[s], j = st.y;
+    const int slot = blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot >= min(plan[kPlanListBlocks], lb_cap) * kWave) return;
+    const int4 st = state[slot];
+    if ((st.w & 3) != 1) return;
+    const int g = st.w >> 2, j = st.y;
     const int64_t base = seg_off[j];
     const int2 v = atom_dp[base + st.z];
     unsigned long long mult, tier;

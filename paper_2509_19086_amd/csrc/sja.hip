@@ -270,7 +270,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
 
     // one launch per round, in batches between looks at the flags
     auto launch_round = [&](int64_t k, int propose) {
-        hipLaunchKernelGGL(k_grant_round, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, plan, lb_begin, lb_end,
+        hipLaunchKernelGGL(k_grant_round, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, lb_bound, plan, lb_begin, lb_end,
                            list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand);
         return hipGetLastError();
     };
@@ -299,9 +299,9 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
             next_check = r + 1;
         }
     }
-    hipLaunchKernelGGL(k_grant_finish, dim3((G + 255) / 256), dim3(256), 0, st, G, pol,
-                       ws_ptr<int32_t>(ctx, L.gap_order), ws_ptr<int4>(ctx, L.g_state), ctx->seg_off, atom_dp, atom_db,
-                       wait, sla_class, grant_job, grant_cut, grant_score, job_gap);
+    hipLaunchKernelGGL(k_grant_finish, dim3(unsigned((int64_t(n_subs) * kWave + 255) / 256)), dim3(256), 0, st, lb_bound, pol,
+                       plan, state, ctx->seg_off, atom_dp, atom_db, wait, sla_class, grant_job, grant_cut, grant_score,
+                       job_gap);
     SJA_HIP(hipGetLastError(), "k_grant_finish launch");
     *done = true;
     return SJA_OK;

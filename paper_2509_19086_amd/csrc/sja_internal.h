@@ -69,7 +69,7 @@ struct Layout {
     size_t lb_begin, lb_end, lb_sub;       // [list_bound] int32: grant-list blocks (pieces of sub-blocks)
     size_t lb_off;                         // [sub_bound+2] int32: first list block of a sub-block
     size_t g_list_off;                     // [list_bound+2] int32
-    size_t g_state;                        // [G] int4: pointer, candidate job, candidate atom, flag
+    size_t g_state;                        // [list_bound * 64] int4: pointer, candidate job, candidate atom, flag | gap << 2
     size_t g_cnt_lost, g_cnt_cand;         // [min(G,J)+4] int32
     int64_t atom_cap, entry_cap;
     size_t total;
@@ -171,7 +171,7 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.lb_sub = take(lb * 4);
     L.lb_off = take((ub + 2) * 4);
     L.g_list_off = take((lb + 2) * 4);
-    L.g_state = take(size_t(G) * 16);
+    L.g_state = take(lb * size_t(kWave) * 16);
     const size_t rounds_cap = size_t(G < J ? G : J) + 4;
     L.g_cnt_lost = take(rounds_cap * 4);
     L.g_cnt_cand = take(rounds_cap * 4);
