@@ -34,18 +34,23 @@ def algorithmic_fit_bytes(wl, n_atoms_total):
 # sources are hashed, and a different hash means the counters are stale.
 FIT_TRAFFIC = {
     "workload": ("stress", 0),
-    "sources_sha256": "8a6203e6608af46eeff119d26e4daac2586a6c0849f148f7becc1cdecb7b4b4a",
+    "sources_sha256": "51eb4ae831ffd41086f6319ba49181933bb5fa686ad15f59196931c01fa11c46",
     "fetch_kib": 343947.0, "fetch_scale": 2.0,
     "write_kib": 8388610.0, "write_scale": 1.0,
 }
 
 
 def fit_kernel_sources_sha256():
+    """Hash of what defines k_fit_main: its source file and the tile constants it is built with."""
     import hashlib
+    csrc = os.path.join(ROOT, "paper_2509_19086_amd", "csrc")
     h = hashlib.sha256()
-    for name in ("k_fit.h", "sja_internal.h"):
-        with open(os.path.join(ROOT, "paper_2509_19086_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+    with open(os.path.join(csrc, "k_fit.h"), "rb") as f:
+        h.update(f.read())
+    with open(os.path.join(csrc, "sja_internal.h"), "rb") as f:
+        for line in f.read().splitlines():
+            if line.startswith(b"constexpr int kFit"):
+                h.update(line)
     return h.hexdigest()
 
 
