@@ -20,7 +20,7 @@ constexpr int kFitWindow = 16;        // atoms per job staged ahead in LDS (powe
 constexpr int kFitPeriod = 64;        // steps between window top-ups (multiple of 4)
 constexpr int kMaxClasses = 64;       // distinct capacities served by the table-driven path
 constexpr int kSelBlock = 256;        // threads per select block, one job per thread
-constexpr int kSelGapChunk = 128;     // sorted gap positions walked by one select block
+constexpr int kSelGapChunk = 64;      // sorted gap positions walked by one select block
 constexpr int kListSplits = 40;       // most pieces one capacity class's small windows are split into
 
 // One partial arg-max per (job tile, gap): 32 bytes.

@@ -126,7 +126,7 @@ __device__ __forceinline__ bool key_better(unsigned long long hi_a, unsigned lon
 }
 
 // Steps reduced together by one wave (see k_select_pass).
-constexpr int kSelBatch = 16;
+constexpr int kSelBatch = 8;
 
 template <bool MIXED>
 __global__ __launch_bounds__(kSelBlock) void k_select_pass(
