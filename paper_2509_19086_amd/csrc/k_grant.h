@@ -96,12 +96,6 @@ __global__ __launch_bounds__(256) void k_atom_keys(
     }
 }
 
-struct MovePerm {
-    const uint32_t *src;
-    uint32_t *dst;
-    __device__ void operator()(int64_t i, int64_t o) const { dst[o] = src[i]; }
-};
-
 // rank of every atom, and the (job, atom) that holds each rank
 __global__ void k_rank_from_perm(const int32_t *n_ptr, const uint32_t *__restrict__ perm,
                                  const int2 *__restrict__ atom_ja, uint32_t *__restrict__ rank,

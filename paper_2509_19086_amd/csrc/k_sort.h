@@ -89,92 +89,13 @@ inline hipError_t enqueue_scan(hipStream_t st, int32_t *data, int64_t n, int32_t
 }
 
 // --------------------------------------------------------------------------
-// Stable radix pass.  Items are processed in tiles of 2048 (8 rounds of 256
-// consecutive items); hist is digit-major ([256][n_tiles]) so that one
-// exclusive scan over it yields every (digit, tile) output offset.
-// n lives in device memory (it is produced by earlier kernels).
-// --------------------------------------------------------------------------
-constexpr int kRadixTile = 2048;
-
-// Digit source for sorting a permutation by 64-bit keys it points to.
-struct DigitViaPerm {
-    const unsigned long long *keys;
-    const uint32_t *perm;
-    __device__ unsigned operator()(int64_t i, int shift) const { return unsigned(keys[perm[i]] >> shift) & 255u; }
-};
-// Digit source for items that carry their 64-bit key.
-struct DigitDirect {
-    const unsigned long long *keys;
-    __device__ unsigned operator()(int64_t i, int shift) const { return unsigned(keys[i] >> shift) & 255u; }
-};
-
-template <typename Digit>
-__global__ __launch_bounds__(256) void k_radix_hist(Digit dig, const int32_t *n_ptr, int shift,
-                                                    int32_t *hist, int n_tiles)
-{
-    __shared__ int s_h[256];
-    const int64_t n = *n_ptr;
-    s_h[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
-    if (base < n) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int64_t i = base + r * 256 + threadIdx.x;
-            if (i < n) atomicAdd(&s_h[dig(i, shift)], 1);
-        }
-    }
-    __syncthreads();
-    hist[int64_t(threadIdx.x) * n_tiles + blockIdx.x] = s_h[threadIdx.x];
-}
-
-// Payload mover: called once per item with its source and destination index.
-template <typename Digit, typename Mover>
-__global__ __launch_bounds__(256) void k_radix_scatter(Digit dig, Mover mv, const int32_t *n_ptr, int shift,
-                                                       const int32_t *hist, int n_tiles)
-{
-    __shared__ int s_run[256];          // next output slot per digit for this tile
-    __shared__ int s_wave[4][256];      // per-round, per-wave digit counts
-    const int64_t n = *n_ptr;
-    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
-    if (base >= n) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    s_run[tid] = hist[int64_t(tid) * n_tiles + blockIdx.x];
-    for (int r = 0; r < 8; ++r) {
-#pragma unroll
-        for (int w = 0; w < 4; ++w) s_wave[w][tid] = 0;
-        __syncthreads();
-        const int64_t i = base + r * 256 + tid;
-        const bool valid = i < n;
-        const unsigned d = valid ? dig(i, shift) : 0u;
-        // lanes of this wave with the same digit
-        unsigned long long peers = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const unsigned long long m = __ballot((d >> b) & 1u);
-            peers &= ((d >> b) & 1u) ? m : ~m;
-        }
-        const int rank_in_wave = __popcll(peers & ((1ull << lane) - 1ull));
-        if (valid && rank_in_wave == 0) s_wave[wave][d] = __popcll(peers);
-        __syncthreads();
-        if (valid) {
-            int off = s_run[d] + rank_in_wave;
-            for (int w = 0; w < wave; ++w) off += s_wave[w][d];
-            mv(i, int64_t(off));
-        }
-        __syncthreads();
-        s_run[tid] += s_wave[0][tid] + s_wave[1][tid] + s_wave[2][tid] + s_wave[3][tid];
-        __syncthreads();
-    }
-}
-
-
-// --------------------------------------------------------------------------
 // Stable radix pass over bare 64-bit keys (the grant-list entries), tiles of
 // kKeyTile items.  A tile is ranked per wave (each wave owns a contiguous
 // quarter, walked in order so the pass stays stable), put in digit order in
 // LDS and written out from there, so that items of one digit leave as one
-// contiguous run.
+// contiguous run.  hist is digit-major ([256][n_tiles]) so that one exclusive
+// scan over it yields every (digit, tile) output offset.  n lives in device
+// memory (it is produced by earlier kernels).
 // --------------------------------------------------------------------------
 constexpr int kKeyTile = 4096;
 constexpr int kKeyPerWave = kKeyTile / 4;
@@ -213,11 +134,16 @@ __global__ __launch_bounds__(256) void k_keys_hist(const unsigned long long *__r
     hist[int64_t(tid) * n_tiles + blockIdx.x] = s_h[tid];
 }
 
+// PAY: every key carries a 32-bit payload that moves with it.
+template <bool PAY>
 __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *__restrict__ src,
-                                                      unsigned long long *__restrict__ dst, const int32_t *n_ptr,
+                                                      unsigned long long *__restrict__ dst,
+                                                      const uint32_t *__restrict__ pay_src,
+                                                      uint32_t *__restrict__ pay_dst, const int32_t *n_ptr,
                                                       int shift, const int32_t *__restrict__ hist, int n_tiles)
 {
     __shared__ unsigned long long s_key[kKeyTile];
+    __shared__ uint32_t s_pay[PAY ? kKeyTile : 1];
     __shared__ int s_cnt[4][256];       // per wave and digit: running count, later the offset inside the digit
     __shared__ int s_start[256];        // first tile-local slot of a digit
     __shared__ int s_goff[256];         // where the tile's items of a digit go
@@ -232,10 +158,14 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
     __syncthreads();
 
     unsigned long long key[kKeyChunks];
+    uint32_t pay[PAY ? kKeyChunks : 1];
     int pos[kKeyChunks];
     const int64_t wbase = base + wave * kKeyPerWave + lane;
 #pragma unroll
-    for (int c = 0; c < kKeyChunks; ++c) key[c] = wbase + c * kWave < n ? src[wbase + c * kWave] : ~0ull;
+    for (int c = 0; c < kKeyChunks; ++c) {
+        key[c] = wbase + c * kWave < n ? src[wbase + c * kWave] : ~0ull;
+        if (PAY) pay[c] = wbase + c * kWave < n ? pay_src[wbase + c * kWave] : 0u;
+    }
     volatile int *cnt = &s_cnt[wave][0];
 #pragma unroll
     for (int c = 0; c < kKeyChunks; ++c) {
@@ -272,7 +202,9 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
     for (int c = 0; c < kKeyChunks; ++c) {
         if (wbase + c * kWave < n) {
             const unsigned d = unsigned(key[c] >> shift) & 255u;
-            s_key[s_start[d] + s_cnt[wave][d] + pos[c]] = key[c];
+            const int slot = s_start[d] + s_cnt[wave][d] + pos[c];
+            s_key[slot] = key[c];
+            if (PAY) s_pay[slot] = pay[c];
         }
     }
     __syncthreads();
@@ -280,7 +212,43 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
     for (int k = tid; k < count; k += 256) {
         const unsigned long long v = s_key[k];
         const unsigned d = unsigned(v >> shift) & 255u;
-        dst[int64_t(s_goff[d]) + (k - s_start[d])] = v;
+        const int64_t o = int64_t(s_goff[d]) + (k - s_start[d]);
+        dst[o] = v;
+        if (PAY) pay_dst[o] = s_pay[k];
+    }
+}
+
+// out[i] = keys[idx[i]]: the keys of a permutation, laid out in its order.
+__global__ void k_gather_keys(const int32_t *n_ptr, const unsigned long long *__restrict__ keys,
+                              const uint32_t *__restrict__ idx, unsigned long long *__restrict__ out)
+{
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < *n_ptr) out[i] = keys[idx[i]];
+}
+
+// bits[0] |= ~a[i], bits[1] |= ~b[i] over all items: the bytes in which inverted keys differ from "all ones".
+__global__ __launch_bounds__(256) void k_key_bits(const int32_t *n_ptr, const unsigned long long *__restrict__ a,
+                                                  const unsigned long long *__restrict__ b,
+                                                  unsigned long long *bits)
+{
+    __shared__ unsigned long long s_a[4], s_b[4];
+    const int64_t n = *n_ptr;
+    unsigned long long oa = 0, ob = 0;
+    for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += int64_t(gridDim.x) * blockDim.x) {
+        oa |= ~a[i];
+        ob |= ~b[i];
+    }
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        oa |= (unsigned long long)__shfl_xor((long long)oa, d, kWave);
+        ob |= (unsigned long long)__shfl_xor((long long)ob, d, kWave);
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (lane == 0) { s_a[wave] = oa; s_b[wave] = ob; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        atomicOr(&bits[0], s_a[0] | s_a[1] | s_a[2] | s_a[3]);
+        atomicOr(&bits[1], s_b[0] | s_b[1] | s_b[2] | s_b[3]);
     }
 }
 

@@ -103,46 +103,34 @@ int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const 
 }
 
 
-// Radix-sorts `n` (device count, host copy n_host) items on the key bits
-// [0, key_bits) with the given digit source / mover pair per pass; `flip`
-// reports whether the result ended in the second buffer set.
-template <typename MakeDigit, typename MakeMover>
-int radix_sort_bits(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t *n_dev, int64_t n_host,
-                    int first_bit, int last_bit, bool &flip, MakeDigit make_digit, MakeMover make_mover)
-{
-    if (n_host <= 0) return SJA_OK;
-    const int n_tiles = int((n_host + kRadixTile - 1) / kRadixTile);
-    int32_t *hist = ws_ptr<int32_t>(ctx, L.g_hist);
-    int32_t *tmp = ws_ptr<int32_t>(ctx, L.g_scan_tmp);
-    for (int shift = first_bit; shift < last_bit; shift += 8) {
-        auto dig = make_digit(flip);
-        auto mov = make_mover(flip);
-        hipLaunchKernelGGL((k_radix_hist<decltype(dig)>), dim3(n_tiles), dim3(256), 0, st, dig, n_dev, shift, hist, n_tiles);
-        SJA_HIP(hipGetLastError(), "k_radix_hist launch");
-        SJA_HIP(enqueue_scan(st, hist, int64_t(256) * n_tiles, tmp, nullptr), "radix scan launch");
-        hipLaunchKernelGGL((k_radix_scatter<decltype(dig), decltype(mov)>), dim3(n_tiles), dim3(256), 0, st, dig, mov,
-                           n_dev, shift, hist, n_tiles);
-        SJA_HIP(hipGetLastError(), "k_radix_scatter launch");
-        flip = !flip;
-    }
-    return SJA_OK;
-}
-
-// The same over bare 64-bit keys (key-only tiles), between two buffers.
+// Stable radix passes over bare 64-bit keys (key-only tiles) between two
+// buffers, optionally with a 32-bit payload per key.  Only the bytes named in
+// byte_mask are sorted on, lowest first (a byte that is the same in every key
+// needs no pass).
 int radix_sort_keys(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t *n_dev, int64_t n_host,
-                    int first_bit, int last_bit, bool &flip, unsigned long long *const buf[2])
+                    unsigned byte_mask, int bit_offset, bool &flip, unsigned long long *const buf[2],
+                    uint32_t *const pay[2])
 {
     if (n_host <= 0) return SJA_OK;
     const int n_tiles = int((n_host + kKeyTile - 1) / kKeyTile);
     int32_t *hist = ws_ptr<int32_t>(ctx, L.g_hist);
     int32_t *tmp = ws_ptr<int32_t>(ctx, L.g_scan_tmp);
-    for (int shift = first_bit; shift < last_bit; shift += 8) {
+    for (int b = 0; b < 8; ++b) {
+        if (!((byte_mask >> b) & 1u)) continue;
+        const int shift = bit_offset + 8 * b;
+        if (shift >= 64) break;
         const unsigned long long *src = buf[flip ? 1 : 0];
         unsigned long long *dst = buf[flip ? 0 : 1];
         hipLaunchKernelGGL(k_keys_hist, dim3(n_tiles), dim3(256), 0, st, src, n_dev, shift, hist, n_tiles);
         SJA_HIP(hipGetLastError(), "k_keys_hist launch");
         SJA_HIP(enqueue_scan(st, hist, int64_t(256) * n_tiles, tmp, nullptr), "radix scan launch");
-        hipLaunchKernelGGL(k_keys_scatter, dim3(n_tiles), dim3(256), 0, st, src, dst, n_dev, shift, hist, n_tiles);
+        if (pay)
+            hipLaunchKernelGGL(k_keys_scatter<true>, dim3(n_tiles), dim3(256), 0, st, src, dst, pay[flip ? 1 : 0],
+                               pay[flip ? 0 : 1], n_dev, shift, hist, n_tiles);
+        else
+            hipLaunchKernelGGL(k_keys_scatter<false>, dim3(n_tiles), dim3(256), 0, st, src, dst,
+                               static_cast<const uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), n_dev, shift,
+                               hist, n_tiles);
         SJA_HIP(hipGetLastError(), "k_keys_scatter launch");
         flip = !flip;
     }
@@ -201,7 +189,14 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     hipLaunchKernelGGL(k_reach, dim3((J + 1 + 255) / 256), dim3(256), 0, st, J, plan, ncap_tab, abase);
     SJA_HIP(hipGetLastError(), "k_reach launch");
     SJA_HIP(enqueue_scan(st, abase, int64_t(J) + 1, tmp, counters + 2), "atom scan launch");
-    int32_t host_plan[kPlanWords] = {0}, host_counters[4] = {0};
+    // policy keys of the atoms and the bytes in which they differ (both only need the device-side counts)
+    hipLaunchKernelGGL(k_atom_keys, dim3((J + 3) / 4), dim3(256), 0, st, J, pol, ctx->seg_off, atom_dp, abase, wait,
+                       sla_class, key_hi, key_lo, perm[0], atom_ja);
+    SJA_HIP(hipGetLastError(), "k_atom_keys launch");
+    hipLaunchKernelGGL(k_key_bits, dim3(256), dim3(256), 0, st, counters + 2, key_hi, key_lo,
+                       reinterpret_cast<unsigned long long *>(counters + 4));
+    SJA_HIP(hipGetLastError(), "k_key_bits launch");
+    int32_t host_plan[kPlanWords] = {0}, host_counters[8] = {0};
     SJA_HIP(hipMemcpyAsync(host_plan, plan, sizeof(host_plan), hipMemcpyDeviceToHost, st), "plan readback");
     SJA_HIP(hipMemcpyAsync(host_counters, counters, sizeof(host_counters), hipMemcpyDeviceToHost, st), "count readback");
     SJA_HIP(hipStreamSynchronize(st), "count synchronise");
@@ -209,21 +204,32 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     const int n_subs = host_plan[kPlanListBlocks];          // list blocks from here on
     if (!host_plan[kPlanTabled] || n_subs > lb_bound || n_atoms > L.atom_cap) return SJA_OK;
 
-    // 2. rank the atoms by policy key (descending key, ascending job id)
+    // 2. rank the atoms by policy key (descending key, ascending job id): stable passes over
+    //    (inverted key, atom id) pairs, the secondary key first; the entry buffers serve as the
+    //    second key buffer, they are not in use yet
     if (n_atoms > 0) {
-        hipLaunchKernelGGL(k_atom_keys, dim3((J + 3) / 4), dim3(256), 0, st, J, pol, ctx->seg_off, atom_dp, abase, wait,
-                           sla_class, key_hi, key_lo, perm[0], atom_ja);
-        SJA_HIP(hipGetLastError(), "k_atom_keys launch");
-        bool flip = false;
-        auto mover = [&](bool f) { return MovePerm{perm[f ? 1 : 0], perm[f ? 0 : 1]}; };
+        unsigned long long bits_hi = 0, bits_lo = 0;
+        memcpy(&bits_hi, host_counters + 4, 8);
+        memcpy(&bits_lo, host_counters + 6, 8);
+        auto bytes_of = [](unsigned long long v) {
+            unsigned m = 0;
+            for (int b = 0; b < 8; ++b) if ((v >> (8 * b)) & 0xffull) m |= 1u << b;
+            return m;
+        };
+        bool flip = false;      // where the atom ids are: perm[flip]
         int rc = SJA_OK;
         if (params->policy == SJA_POLICY_MIXED) {
-            rc = radix_sort_bits(ctx, st, L, counters + 2, n_atoms, 0, 64, flip,
-                                 [&](bool f) { return DigitViaPerm{key_lo, perm[f ? 1 : 0]}; }, mover);
+            unsigned long long *kb[2] = {key_lo, ekey[0]};
+            rc = radix_sort_keys(ctx, st, L, counters + 2, n_atoms, bytes_of(bits_lo), 0, flip, kb, perm);
             if (rc != SJA_OK) return rc;
         }
-        rc = radix_sort_bits(ctx, st, L, counters + 2, n_atoms, 0, 64, flip,
-                             [&](bool f) { return DigitViaPerm{key_hi, perm[f ? 1 : 0]}; }, mover);
+        // the primary keys in the order reached so far
+        unsigned long long *kh[2] = {ekey[1], ekey[0]};
+        if (flip) { kh[0] = ekey[0]; kh[1] = ekey[1]; }      // buffer index must follow the id buffers
+        hipLaunchKernelGGL(k_gather_keys, dim3(unsigned((n_atoms + 255) / 256)), dim3(256), 0, st, counters + 2, key_hi,
+                           perm[flip ? 1 : 0], kh[flip ? 1 : 0]);
+        SJA_HIP(hipGetLastError(), "k_gather_keys launch");
+        rc = radix_sort_keys(ctx, st, L, counters + 2, n_atoms, bytes_of(bits_hi), 0, flip, kh, perm);
         if (rc != SJA_OK) return rc;
         hipLaunchKernelGGL(k_rank_from_perm, dim3(unsigned((n_atoms + 255) / 256)), dim3(256), 0, st, counters + 2,
                            perm[flip ? 1 : 0], atom_ja, rank, ranked);
@@ -245,8 +251,9 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(enqueue_scan(st, list_off, int64_t(lb_bound) + 2, tmp, nullptr), "list offset scan launch");
     bool eflip = false;
     if (n_entries > 0) {
-        int rc = radix_sort_keys(ctx, st, L, counters, n_entries, kEntryLaneBits,
-                                 kEntryLaneBits + rank_bits + sub_bits, eflip, ekey);
+        const int key_bytes = (rank_bits + sub_bits + 7) / 8;
+        int rc = radix_sort_keys(ctx, st, L, counters, n_entries, (1u << key_bytes) - 1u, kEntryLaneBits, eflip, ekey,
+                                 nullptr);
         if (rc != SJA_OK) return rc;
     }
     const int fb = eflip ? 1 : 0;

@@ -151,8 +151,7 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     const size_t lb = size_t(list_block_bound(G, J));
     L.entry_cap = int64_t(ub + 128) * J + 2 * S + 8;
     const size_t ac = size_t(L.atom_cap), ec = size_t(L.entry_cap);
-    const size_t tiles_a = (ac + 2047) / 2048, tiles_e = (ec + 4095) / 4096;
-    const size_t hist_ints = 256 * (tiles_a > tiles_e ? tiles_a : tiles_e);
+    const size_t hist_ints = 256 * ((ec + 4095) / 4096);      // ec >= ac: the atom sort fits too
     L.g_abase = take(size_t(J + 2) * 4);
     L.g_scan_tmp = take(((hist_ints + 2047) / 2048 + size_t(J) / 2048 + lb / 2048 + 16) * 4);
     L.g_key_hi = take(ac * 8);
