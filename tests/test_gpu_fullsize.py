@@ -11,7 +11,7 @@ from gen import make_workload
 pytestmark = [pytest.mark.gpu, pytest.mark.slow]
 
 
-def _check_full_size(oracle, name, n_pairs, n_rows, max_rounds):
+def _check_full_size(oracle, name, n_pairs, n_rows, max_rounds, until_stable=False):
     import torch
     import paper_2509_19086_amd as P
     wl = make_workload(name, 0)
@@ -55,40 +55,57 @@ def _check_full_size(oracle, name, n_pairs, n_rows, max_rounds):
     np.testing.assert_array_equal(t.cand_score[rows_t].cpu().numpy(), cs)
 
     # resolve: invariants that hold at any size, with the oracle evaluating each granted pair
-    t.resolve(par)
-    gj = t.grant_job.cpu().numpy(); gc = t.grant_cut.cpu().numpy(); gs = t.grant_score.cpu().numpy()
-    jg = t.job_gap.cpu().numpy()
-    rounds, stable = t.rounds.cpu().tolist()
-    granted = np.nonzero(gj >= 0)[0]
-    assert len(granted) > 0
-    assert len(np.unique(gj[granted])) == len(granted)                  # no job holds two gaps
-    np.testing.assert_array_equal(jg[gj[granted]], granted)             # job_gap inverts grant_job
-    assert (jg >= 0).sum() == len(granted)
-    ocut, sd, sp = oracle.fit_pairs(granted.astype(np.int32), gj[granted], wl.seg_off, wl.dur,
-                                    wl.mem, wl.safe, wl.progress, wl.W, wl.C)
-    np.testing.assert_array_equal(gc[granted], ocut)                    # an interested pair, same cut
-    assert (ocut >= 0).all()
-    assert (sd <= wl.W[granted]).all() and (sp <= wl.C[granted]).all()  # fits by construction
-    F = sd * sp
-    wait = wl.wait[gj[granted]].astype(np.int64)
-    cls = wl.sla_class[gj[granted]]
-    score = {0: F, 1: F * (wl.wait_scale + wait), 2: F * np.asarray(wl.sla_weight, np.int64)[cls],
-             3: F * (wl.wait_scale + wait)}[wl.policy]
-    np.testing.assert_array_equal(gs[granted], score)
-    assert (gs[gj < 0] == 0).all() and (gc[gj < 0] == -1).all()
-    if 0 in rows:                                                        # gap 0 always keeps its first choice
-        assert gj[0] == cj[0] and gc[0] == cc[0] and gs[0] == cs[0]
-    assert 1 <= rounds <= (max_rounds if max_rounds else min(G, J) + 1)
-    if max_rounds and rounds == max_rounds and stable == 0:
-        pass
-    else:
-        assert stable == 1
-        # stable: a sampled ungranted gap has no un-held interested job left
-        ung = [i for i, g in enumerate(rows) if gj[g] < 0]
-        if ung:
-            sub = cut_r[ung]
-            rj, _, _ = oracle.select(sub, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class, jg)
-            assert (rj == -1).all()
+    def check_grants(cap):
+        p = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, cap)
+        t.resolve(p)
+        gj = t.grant_job.cpu().numpy(); gc = t.grant_cut.cpu().numpy(); gs = t.grant_score.cpu().numpy()
+        jg = t.job_gap.cpu().numpy()
+        rounds, stable = t.rounds.cpu().tolist()
+        granted = np.nonzero(gj >= 0)[0]
+        assert len(granted) > 0
+        assert len(np.unique(gj[granted])) == len(granted)                  # no job holds two gaps
+        np.testing.assert_array_equal(jg[gj[granted]], granted)             # job_gap inverts grant_job
+        assert (jg >= 0).sum() == len(granted)
+        ocut, sd, sp = oracle.fit_pairs(granted.astype(np.int32), gj[granted], wl.seg_off, wl.dur,
+                                        wl.mem, wl.safe, wl.progress, wl.W, wl.C)
+        np.testing.assert_array_equal(gc[granted], ocut)                    # an interested pair, same cut
+        assert (ocut >= 0).all()
+        assert (sd <= wl.W[granted]).all() and (sp <= wl.C[granted]).all()  # fits by construction
+        F = sd * sp
+        wait = wl.wait[gj[granted]].astype(np.int64)
+        cls = wl.sla_class[gj[granted]]
+        score = {0: F, 1: F * (wl.wait_scale + wait), 2: F * np.asarray(wl.sla_weight, np.int64)[cls],
+                 3: F * (wl.wait_scale + wait)}[wl.policy]
+        np.testing.assert_array_equal(gs[granted], score)
+        assert (gs[gj < 0] == 0).all() and (gc[gj < 0] == -1).all()
+        if 0 in rows:                                                        # gap 0 always keeps its first choice
+            assert gj[0] == cj[0] and gc[0] == cc[0] and gs[0] == cs[0]
+        assert 1 <= rounds <= (cap if cap else min(G, J) + 1)
+        if not (cap and rounds == cap and stable == 0):
+            assert stable == 1
+            # stable: a sampled ungranted gap has no un-held interested job left
+            ung = [i for i, g in enumerate(rows) if gj[g] < 0]
+            if ung:
+                sub = cut_r[ung]
+                rj, _, _ = oracle.select(sub, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class, jg)
+                assert (rj == -1).all()
+        return gj, gc, gs, jg, rounds, stable
+
+    first = check_grants(max_rounds)
+    # the two implementations of the rounds agree bit for bit at full size
+    try:
+        eng.sja_set_resolve_mode(1)
+        other = check_grants(max_rounds)
+    finally:
+        eng.sja_set_resolve_mode(0)
+    for a, b in zip(first, other):
+        np.testing.assert_array_equal(a, b)
+    if until_stable:
+        gj, _, _, _, rounds, stable = check_grants(0)
+        assert stable == 1 and rounds > max_rounds
+        # with the cap gone nothing granted before is taken back
+        keep = first[0] >= 0
+        np.testing.assert_array_equal(gj[keep], first[0][keep])
 
 
 def test_large_full_size(oracle):
@@ -96,4 +113,4 @@ def test_large_full_size(oracle):
 
 
 def test_stress_full_size(oracle):
-    _check_full_size(oracle, "stress", n_pairs=300_000, n_rows=12, max_rounds=8)
+    _check_full_size(oracle, "stress", n_pairs=300_000, n_rows=12, max_rounds=8, until_stable=True)
