@@ -7,17 +7,19 @@
 // (an atom is a safe cut of a job; the key depends on the job and on the cut,
 // not on the gap), and in sorted gap order an atom is the answer of a job for
 // one contiguous range of positions.  So:
-//   1. all reachable atoms are ranked once by policy key (stable radix sort:
+//   1. all reachable atoms are ranked once by policy key (stable radix passes:
 //      key descending, job id ascending);
-//   2. for every sub-block of <= 64 sorted gap positions the atoms some position
-//      of it would get are listed in rank order, each with the range of lanes
-//      (positions) it applies to;
-//   3. a round is one small kernel: a wave per sub-block, a lane per gap; a lane
-//      that lost walks on through its sub-block's list to the next entry that
+//   2. for every list block (<= 64 sorted gap positions of one capacity class
+//      whose windows are of similar length) the atoms some position of it would
+//      get are listed in rank order, each with the range of lanes (positions)
+//      it applies to;
+//   3. a round is one small kernel: a wave per list block, a lane per gap; a
+//      lane that lost walks on through its block's list to the next entry that
 //      covers it and whose job is not held, and claims that job with an
-//      atomicMax of (round, ~gap index); the next round's kernel first checks
-//      who won.  Claims carry the round number, so nothing is ever reset and a
-//      claim made in the current round is not mistaken for a hold.
+//      atomicMax of (round, ~gap index), the claims of a thread block merged
+//      first; the next round's kernel first checks who won.  Claims carry the
+//      round number, so nothing is ever reset and a claim made in the current
+//      round is not mistaken for a hold.
 #pragma once
 
 #include "k_sort.h"
@@ -298,7 +300,8 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // `propose`, every lane that still needs a job walks on from its own pointer to
 // the first entry that covers it and whose job is not held, and claims it.
 // st = (pointer, candidate job, candidate atom, flag) with flag 0 = active,
-// 1 = granted, 2 = no candidate left (in memory the flag shares its word with the gap index).  r[] holds the records at st.x on entry.
+// 1 = granted, 2 = no candidate left (in memory the flag shares its word with
+// the gap index).  r[] holds the records at st.x on entry.
 constexpr int kWalk = 8;         // records a lane reads per trip on its own
 constexpr int kSweep = 4;        // chunks of 64 records the wave reads per trip when it walks together
 constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together

@@ -160,7 +160,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     int32_t *plan = ws_ptr<int32_t>(ctx, L.plan);
     int32_t *abase = ws_ptr<int32_t>(ctx, L.g_abase);
     int32_t *tmp = ws_ptr<int32_t>(ctx, L.g_scan_tmp);
-    int32_t *counters = ws_ptr<int32_t>(ctx, L.res_counters);      // [0] entries, [1] cursor, [2] atoms
+    int32_t *counters = ws_ptr<int32_t>(ctx, L.res_counters);      // [0..1] entries (64 bit), [2] atoms, [4..7] key bits
     int32_t *list_off = ws_ptr<int32_t>(ctx, L.g_list_off);
     const int2 *atom_dp = ws_ptr<int2>(ctx, L.atom_dp);
     const int2 *atom_db = ws_ptr<int2>(ctx, L.atom_db);
@@ -177,7 +177,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     unsigned long long *ekey[2] = {ws_ptr<unsigned long long>(ctx, L.g_ekey0), ws_ptr<unsigned long long>(ctx, L.g_ekey1)};
     int2 *atom_ja = ws_ptr<int2>(ctx, L.g_atom_ja), *ranked = ws_ptr<int2>(ctx, L.g_ranked);
 
-    // 1. reachable atoms per job -> compact atom ids; entry counts per sub-block
+    // 1. list blocks; reachable atoms per job -> compact atom ids
     hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, st, counters, int64_t(16), 0);
     hipLaunchKernelGGL(k_fill_i32, dim3((lb_bound + 2 + 255) / 256), dim3(256), 0, st, list_off, int64_t(lb_bound + 2), 0);
     hipLaunchKernelGGL(k_list_blocks_count, dim3((sub_bound + 1 + 255) / 256), dim3(256), 0, st, sub_bound + 1, plan, sub_begin,
