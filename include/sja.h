@@ -12,6 +12,7 @@
  *                         the longest safe subjob that fits, or decline
  *                         (Sec. 3.5 phase 2, Sec. 3.8 admissibility, Sec. 3.9)
  *   sja_select            scheduler policy arg-max per gap (Sec. 3.5 phase 3)
+ *   sja_fit_select        the two above in one pass, without the pair matrix
  *   sja_resolve           grants, with conflicts settled in rounds so that a job
  *                         holds at most one gap (Sec. 3.1 / 3.5: fragments of a
  *                         job are sequential from one progress point)
@@ -166,6 +167,24 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
 int sja_select(sja_ctx *ctx, void *stream, const sja_params *params, const int32_t *wait,
                const uint8_t *sla_class, const int32_t *job_held, const uint8_t *gap_active,
                int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score);
+
+/*
+ * sja_fit followed by sja_select in one pass that never writes the (gap, job)
+ * replies down (Sec. 3.5: "no subjob state is created until a grant is
+ * issued"; the scheduler only needs the best reply per gap).  Arguments are
+ * those of sja_fit (n_gaps, W, C) and of sja_select (params, wait, sla_class,
+ * job_held, gap_active, cand_*), with the same meaning, layout and results:
+ * cand_job / cand_cut / cand_score equal what sja_select would report after
+ * sja_fit on the same inputs.  No cut matrix and no interest rows exist
+ * afterwards: sja_select needs a sja_fit of its own, sja_resolve works (its
+ * candidate lists need no matrix) unless it is switched to, or has to fall back
+ * to, the matrix-scanning rounds (then SJA_ERR_STATE).  Only enqueues work.
+ * With sja_enable_timing the events bracket this call's stepping kernel.
+ */
+int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
+                   const sja_params *params, const int32_t *wait, const uint8_t *sla_class,
+                   const int32_t *job_held, const uint8_t *gap_active, int32_t *cand_job,
+                   int32_t *cand_cut, int64_t *cand_score);
 
 /*
  * Grants with conflict resolution in deterministic rounds (Sec. 3.5: one job

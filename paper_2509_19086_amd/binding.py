@@ -69,6 +69,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_select.argtypes = [vp, vp, ctypes.POINTER(Params)] + [vp] * 7
     lib.sja_select.restype = ctypes.c_int
     lib.sja_resolve.argtypes = [vp, vp, ctypes.POINTER(Params)] + [vp] * 7
+    lib.sja_fit_select.argtypes = [vp, vp, i32, vp, vp, ctypes.POINTER(Params)] + [vp] * 7
+    lib.sja_fit_select.restype = ctypes.c_int
     lib.sja_resolve.restype = ctypes.c_int
     lib.sja_enable_timing.argtypes = [vp, ctypes.c_int]
     lib.sja_enable_timing.restype = ctypes.c_int
@@ -169,6 +171,18 @@ class Engine:
         args = (_ptr(W, torch.int32, G), _ptr(C, torch.int32, G),
                 _ptr(cut, torch.int32, G * self.n_jobs), _ptr(interest_bits, torch.int32, G * words))
         rc = self.lib.sja_fit(self.h, _stream(), G, *args)
+        self._check(rc, self.h)
+        self.n_gaps = G
+
+    def sja_fit_select(self, W, C, params: Params, wait, sla_class, job_held, gap_active,
+                       cand_job, cand_cut, cand_score):
+        G, J = W.numel(), self.n_jobs
+        args = (_ptr(W, torch.int32, G), _ptr(C, torch.int32, G))
+        rest = (_ptr(wait, torch.int32, J), _ptr(sla_class, torch.uint8, J),
+                _ptr(job_held, torch.int32, J), _ptr(gap_active, torch.uint8, G),
+                _ptr(cand_job, torch.int32, G), _ptr(cand_cut, torch.int32, G),
+                _ptr(cand_score, torch.int64, G))
+        rc = self.lib.sja_fit_select(self.h, _stream(), G, *args, ctypes.byref(params), *rest)
         self._check(rc, self.h)
         self.n_gaps = G
 

@@ -314,6 +314,48 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     return SJA_OK;
 }
 
+// Gap ordering, capacity classes, chunk / sub-block plan and the start tables
+// for a batch of gaps: everything the stepping kernels need before they run.
+int enqueue_gap_plan(sja_ctx *ctx, hipStream_t st, const Layout &L, int32_t n_gaps, const int32_t *W, const int32_t *C)
+{
+    const int J = ctx->n_jobs;
+    const int gc = fit_chunk_len(n_gaps, J);
+    const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
+    const int sb = fit_sub_len(n_gaps, J);
+    const int sub_bound = int(fit_sub_bound(n_gaps, J));
+    const dim3 per_gap((n_gaps + 255) / 256), b256(256);
+    int32_t *rank = ws_ptr<int32_t>(ctx, L.gap_rank);
+    int32_t *gw = ws_ptr<int32_t>(ctx, L.gap_w), *gcap = ws_ptr<int32_t>(ctx, L.gap_c);
+    int32_t *plan = ws_ptr<int32_t>(ctx, L.plan);
+    hipLaunchKernelGGL(k_fill_i32, per_gap, b256, 0, st, rank, int64_t(n_gaps), 0);
+    SJA_HIP(hipGetLastError(), "k_fill_i32 launch");
+    hipLaunchKernelGGL(k_gap_rank, dim3((n_gaps + 255) / 256, (n_gaps + kRankSpan - 1) / kRankSpan), b256, 0, st,
+                       n_gaps, W, C, rank);
+    SJA_HIP(hipGetLastError(), "k_gap_rank launch");
+    hipLaunchKernelGGL(k_gap_scatter, per_gap, b256, 0, st, n_gaps, J, W, C, rank,
+                       ws_ptr<int32_t>(ctx, L.gap_order), gw, gcap, ws_ptr<int64_t>(ctx, L.gap_row));
+    SJA_HIP(hipGetLastError(), "k_gap_scatter launch");
+    if (J > 0) {
+        hipLaunchKernelGGL(k_gap_run_end, per_gap, b256, 0, st, n_gaps, gcap,
+                           ws_ptr<int32_t>(ctx, L.gap_run_end));
+        SJA_HIP(hipGetLastError(), "k_gap_run_end launch");
+        hipLaunchKernelGGL(k_gap_plan, dim3(1), dim3(1024), 0, st, n_gaps, gc, sb, chunk_bound, sub_bound, gcap,
+                           plan, ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0),
+                           ws_ptr<int32_t>(ctx, L.class_sub0), ws_ptr<int32_t>(ctx, L.chunk_begin),
+                           ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
+                           ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.sub_begin),
+                           ws_ptr<int32_t>(ctx, L.sub_end), ws_ptr<int32_t>(ctx, L.sub_class),
+                           ws_ptr<int32_t>(ctx, L.gap_cls));
+        SJA_HIP(hipGetLastError(), "k_gap_plan launch");
+        hipLaunchKernelGGL(k_fit_starts, dim3((J + 255) / 256, kMaxClasses), b256, 0, st, J, sb, plan,
+                           ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_sub0), gw, gcap,
+                           ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int32_t>(ctx, L.n_atoms),
+                           ws_ptr<int32_t>(ctx, L.start_tab), ws_ptr<int32_t>(ctx, L.ncap_tab));
+        SJA_HIP(hipGetLastError(), "k_fit_starts launch");
+    }
+    return SJA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -374,6 +416,7 @@ int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes)
     ctx->ws_bytes = bytes;
     ctx->prepared = false;   // private tables lived in the old workspace
     ctx->fitted = false;
+    ctx->planned = false;
     return SJA_OK;
 }
 
@@ -412,6 +455,7 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
     if (!ctx) return SJA_ERR_NULL;
     ctx->prepared = false;
     ctx->fitted = false;
+    ctx->planned = false;
     if (n_jobs < 0 || n_jobs > SJA_MAX_JOBS) return fail(ctx, SJA_ERR_SIZE, "n_jobs");
     if (n_segments < 0 || n_segments > SJA_MAX_SEGMENTS) return fail(ctx, SJA_ERR_SIZE, "n_segments");
     if (!seg_off || !progress) return fail(ctx, SJA_ERR_NULL, "seg_off / progress");
@@ -445,6 +489,7 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
 {
     if (!ctx) return SJA_ERR_NULL;
     ctx->fitted = false;
+    ctx->planned = false;
     ctx->timed = false;
     if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_fit before sja_prepare_profiles");
     if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
@@ -459,39 +504,13 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_gaps > 0) {
         const int words = (J + 31) / 32;
-        const int gc = fit_chunk_len(n_gaps, J);
         const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
-        const int sb = fit_sub_len(n_gaps, J);
-        const int sub_bound = int(fit_sub_bound(n_gaps, J));
-        const dim3 per_gap((n_gaps + 255) / 256), b256(256);
-        int32_t *rank = ws_ptr<int32_t>(ctx, L.gap_rank);
+        const dim3 b256(256);
         int32_t *gw = ws_ptr<int32_t>(ctx, L.gap_w), *gcap = ws_ptr<int32_t>(ctx, L.gap_c);
         int32_t *plan = ws_ptr<int32_t>(ctx, L.plan);
-        hipLaunchKernelGGL(k_fill_i32, per_gap, b256, 0, st, rank, int64_t(n_gaps), 0);
-        SJA_HIP(hipGetLastError(), "k_fill_i32 launch");
-        hipLaunchKernelGGL(k_gap_rank, dim3((n_gaps + 255) / 256, (n_gaps + kRankSpan - 1) / kRankSpan), b256, 0, st,
-                           n_gaps, W, C, rank);
-        SJA_HIP(hipGetLastError(), "k_gap_rank launch");
-        hipLaunchKernelGGL(k_gap_scatter, per_gap, b256, 0, st, n_gaps, J, W, C, rank,
-                           ws_ptr<int32_t>(ctx, L.gap_order), gw, gcap, ws_ptr<int64_t>(ctx, L.gap_row));
-        SJA_HIP(hipGetLastError(), "k_gap_scatter launch");
+        int rc = enqueue_gap_plan(ctx, st, L, n_gaps, W, C);
+        if (rc != SJA_OK) return rc;
         if (J > 0) {
-            hipLaunchKernelGGL(k_gap_run_end, per_gap, b256, 0, st, n_gaps, gcap,
-                               ws_ptr<int32_t>(ctx, L.gap_run_end));
-            SJA_HIP(hipGetLastError(), "k_gap_run_end launch");
-            hipLaunchKernelGGL(k_gap_plan, dim3(1), dim3(1024), 0, st, n_gaps, gc, sb, chunk_bound, sub_bound, gcap,
-                               plan, ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0),
-                               ws_ptr<int32_t>(ctx, L.class_sub0), ws_ptr<int32_t>(ctx, L.chunk_begin),
-                               ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
-                               ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.sub_begin),
-                               ws_ptr<int32_t>(ctx, L.sub_end), ws_ptr<int32_t>(ctx, L.sub_class),
-                               ws_ptr<int32_t>(ctx, L.gap_cls));
-            SJA_HIP(hipGetLastError(), "k_gap_plan launch");
-            hipLaunchKernelGGL(k_fit_starts, dim3((J + 255) / 256, kMaxClasses), b256, 0, st, J, sb, plan,
-                               ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_sub0), gw, gcap,
-                               ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int32_t>(ctx, L.n_atoms),
-                               ws_ptr<int32_t>(ctx, L.start_tab), ws_ptr<int32_t>(ctx, L.ncap_tab));
-            SJA_HIP(hipGetLastError(), "k_fit_starts launch");
             const int job_tiles = (J + kFitBlock - 1) / kFitBlock;
             const int tiles8 = (job_tiles + 7) / 8 * 8;
             const unsigned grid = unsigned(tiles8) * unsigned(chunk_bound);
@@ -531,6 +550,72 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
     ctx->n_gaps = n_gaps;
     ctx->cut = cut;
     ctx->fitted = true;
+    ctx->planned = true;
+    return SJA_OK;
+}
+
+int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
+                   const sja_params *params, const int32_t *wait, const uint8_t *sla_class,
+                   const int32_t *job_held, const uint8_t *gap_active, int32_t *cand_job, int32_t *cand_cut,
+                   int64_t *cand_score)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    ctx->fitted = false;
+    ctx->planned = false;
+    ctx->timed = false;
+    if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_fit_select before sja_prepare_profiles");
+    if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
+    if (n_gaps > 0 && (!W || !C)) return fail(ctx, SJA_ERR_NULL, "W / C");
+    int rc = check_params(ctx, params, wait, sla_class);
+    if (rc != SJA_OK) return rc;
+    if (n_gaps > 0 && (!cand_job || !cand_cut || !cand_score)) return fail(ctx, SJA_ERR_NULL, "candidate outputs");
+    const int J = ctx->n_jobs;
+    const Layout L = make_layout(n_gaps, J, ctx->n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small for this many gaps");
+
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_gaps > 0) {
+        rc = enqueue_gap_plan(ctx, st, L, n_gaps, W, C);
+        if (rc != SJA_OK) return rc;
+        const int job_tiles = (J + kFusedBlock - 1) / kFusedBlock;
+        if (job_tiles > 0) {
+            const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
+            const int tiles8 = (job_tiles + 7) / 8 * 8;
+            const unsigned grid = unsigned(tiles8) * unsigned(chunk_bound);
+            auto kern = params->policy == SJA_POLICY_MIXED
+                            ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true>
+                            : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false>;
+            if (ctx->timing) {
+                if (!ctx->ev_start) {
+                    SJA_HIP(hipEventCreate(&ctx->ev_start), "hipEventCreate");
+                    SJA_HIP(hipEventCreate(&ctx->ev_stop), "hipEventCreate");
+                }
+                SJA_HIP(hipEventRecord(ctx->ev_start, st), "hipEventRecord");
+            }
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedBlock), 0, st, J, n_gaps, chunk_bound, to_dev(params),
+                               ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int32_t>(ctx, L.plan), ws_ptr<int32_t>(ctx, L.chunk_begin),
+                               ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
+                               ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.start_tab),
+                               ws_ptr<int32_t>(ctx, L.ncap_tab), ws_ptr<int32_t>(ctx, L.gap_w),
+                               ws_ptr<int32_t>(ctx, L.gap_c), ws_ptr<int32_t>(ctx, L.gap_order), wait, sla_class,
+                               job_held, gap_active, ws_ptr<SelPartial>(ctx, L.sel_part));
+            SJA_HIP(hipGetLastError(), "k_fit_select launch");
+            if (ctx->timing) {
+                SJA_HIP(hipEventRecord(ctx->ev_stop, st), "hipEventRecord");
+                ctx->timed = true;
+            }
+        }
+        hipLaunchKernelGGL(k_fused_reduce, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, job_tiles,
+                           ws_ptr<SelPartial>(ctx, L.sel_part), ctx->seg_off, ws_ptr<int2>(ctx, L.atom_db), cand_job,
+                           cand_cut, cand_score);
+        SJA_HIP(hipGetLastError(), "k_fused_reduce launch");
+    }
+    ctx->n_gaps = n_gaps;
+    ctx->cut = nullptr;
+    ctx->planned = true;
     return SJA_OK;
 }
 
@@ -556,7 +641,9 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
                 int64_t *grant_score, int32_t *job_gap, int32_t *rounds_used_and_stable)
 {
     if (!ctx) return SJA_ERR_NULL;
-    if (!ctx->fitted) return fail(ctx, SJA_ERR_STATE, "sja_resolve before sja_fit");
+    if (!ctx->planned) return fail(ctx, SJA_ERR_STATE, "sja_resolve before sja_fit or sja_fit_select");
+    if (ctx->resolve_mode == SJA_RESOLVE_MATRIX && !ctx->fitted)
+        return fail(ctx, SJA_ERR_STATE, "matrix-scanning rounds need the cut matrix of sja_fit");
     int rc = check_params(ctx, params, wait, sla_class);
     if (rc != SJA_OK) return rc;
     const int G = ctx->n_gaps, J = ctx->n_jobs;
@@ -594,6 +681,8 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
                                 result, &done);
         if (rc != SJA_OK) return rc;
     }
+    if (!done && G > 0 && J > 0 && !ctx->fitted)
+        return fail(ctx, SJA_ERR_STATE, "this batch needs the matrix-scanning rounds, which need the cut matrix of sja_fit");
     for (int64_t r = 1; !done && r <= cap; ++r) {
         ++result[0];
         int32_t host_counters[2] = {0, 0};

@@ -202,7 +202,8 @@ struct sja_ctx {
     // how sja_resolve runs its rounds (sja_set_resolve_mode)
     int resolve_mode;
 
-    // state left by sja_fit
+    // state left by sja_fit (planned and fitted) or sja_fit_select (planned only: no cut matrix)
+    bool planned;
     bool fitted;
     int32_t n_gaps;
     const int32_t *cut;

@@ -105,6 +105,7 @@ __global__ __launch_bounds__(256) void k_prepare(
 
 #include "k_fit.h"
 #include "k_grant.h"
+#include "k_fused.h"
 
 namespace sja {
 

@@ -13,7 +13,7 @@ class DeviceTick:
     `wl` is any object with numpy attributes seg_off, dur, mem, safe, progress,
     W, C, wait, sla_class (see gen.workloads.Workload)."""
 
-    def __init__(self, engine: Engine, wl, want_bits: bool = True):
+    def __init__(self, engine: Engine, wl, want_bits: bool = True, want_cut: bool = True):
         dev = f"cuda:{engine.device}"
         self.engine = engine
         self.G, self.J, self.S = int(len(wl.W)), int(len(wl.seg_off) - 1), int(wl.seg_off[-1])
@@ -26,9 +26,9 @@ class DeviceTick:
         self.pre_dur = torch.full((self.S,), -7, **i32)
         self.pre_peak = torch.full((self.S,), -7, **i32)
         self.prev_safe = torch.full((self.S,), -7, **i32)
-        self.cut = torch.empty((self.G, self.J), **i32)
+        self.cut = torch.empty((self.G, self.J), **i32) if want_cut else None
         self.words = (self.J + 31) // 32
-        self.bits = torch.empty((self.G, self.words), **i32) if want_bits else None
+        self.bits = torch.empty((self.G, self.words), **i32) if (want_bits and want_cut) else None
         self.cand_job = torch.empty(self.G, **i32)
         self.cand_cut = torch.empty(self.G, **i32)
         self.cand_score = torch.empty(self.G, dtype=torch.int64, device=dev)
@@ -49,6 +49,10 @@ class DeviceTick:
     def select(self, params: Params, job_held=None, gap_active=None):
         self.engine.sja_select(params, self.wait, self.sla_class, job_held, gap_active,
                                self.cand_job, self.cand_cut, self.cand_score)
+
+    def fit_select(self, params: Params, job_held=None, gap_active=None):
+        self.engine.sja_fit_select(self.W, self.C, params, self.wait, self.sla_class, job_held, gap_active,
+                                   self.cand_job, self.cand_cut, self.cand_score)
 
     def resolve(self, params: Params):
         self.engine.sja_resolve(params, self.wait, self.sla_class, self.grant_job, self.grant_cut,

@@ -204,3 +204,86 @@ def test_repeatable(engine):
         outs.append([x.cpu().numpy().tobytes() for x in
                      (t.cut, t.bits, t.cand_job, t.cand_score, t.grant_job, t.grant_score, t.job_gap, t.rounds)])
     assert outs[0] == outs[1] == outs[2]
+
+
+def fused_check(engine, oracle, wl, policies, held=None, act=None, resolve=True):
+    """sja_fit_select reports what sja_select reports after sja_fit (the oracle's), and
+    sja_resolve works on top of it without any cut matrix."""
+    import torch
+    import paper_2509_19086_amd as P
+    t = P.DeviceTick(engine, wl, want_cut=False)
+    t.prepare()
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cut, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C, False)
+    h = None if held is None else torch.from_numpy(held).cuda()
+    a = None if act is None else torch.from_numpy(act).cuda()
+    for policy in policies:
+        par = P.Params.make(policy, wl.wait_scale, wl.sla_weight, wl.class0_override, wl.max_rounds)
+        opar = _oracle_params(oracle, wl, policy)
+        for out in (t.cand_job, t.cand_cut, t.cand_score):
+            out.fill_(-5)
+        t.fit_select(par, h, a)
+        torch.cuda.synchronize()
+        cj, cc, cs = oracle.select(cut, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class, held, act)
+        np.testing.assert_array_equal(t.cand_job.cpu().numpy(), cj, err_msg=f"policy {policy}")
+        np.testing.assert_array_equal(t.cand_cut.cpu().numpy(), cc, err_msg=f"policy {policy}")
+        np.testing.assert_array_equal(t.cand_score.cpu().numpy(), cs, err_msg=f"policy {policy}")
+        if resolve and held is None and act is None:
+            t.resolve(par)
+            gj, gc, gs, jg, rounds, stable = oracle.resolve(cut, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+            np.testing.assert_array_equal(t.grant_job.cpu().numpy(), gj)
+            np.testing.assert_array_equal(t.grant_cut.cpu().numpy(), gc)
+            np.testing.assert_array_equal(t.grant_score.cpu().numpy(), gs)
+            np.testing.assert_array_equal(t.job_gap.cpu().numpy(), jg)
+            assert t.rounds.cpu().tolist() == [rounds, stable]
+    return t
+
+
+@pytest.mark.parametrize("name,seed", [("tiny", 0), ("tiny", 3), ("small", 0), ("small", 2), ("medium", 0)])
+def test_fused_fit_select(engine, oracle, name, seed):
+    fused_check(engine, oracle, make_workload(name, seed), policies=[0, 1, 2, 3])
+
+
+@pytest.mark.parametrize("name,G,J", [("large", 300, 1000), ("stress", 777, 2500),
+                                      ("stress", 130, 70), ("medium", 1, 1), ("small", 257, 65)])
+def test_fused_ragged_shapes(engine, oracle, name, G, J):
+    wl = make_workload(name, 7, n_gaps=G, n_jobs=J)
+    fused_check(engine, oracle, wl, policies=[wl.policy, 3])
+
+
+def test_fused_with_held_jobs_and_inactive_gaps(engine, oracle):
+    wl = make_workload("small", 5)
+    rng = np.random.default_rng(0)
+    held = np.where(rng.random(wl.n_jobs) < 0.5, 3, -1).astype(np.int32)
+    act = (rng.random(wl.n_gaps) < 0.7).astype(np.uint8)
+    fused_check(engine, oracle, wl, policies=[0, 1, 2, 3], held=held, act=act)
+
+
+@pytest.mark.parametrize("n_classes", [1, 64, 65, 700])
+def test_fused_many_capacity_classes(engine, oracle, n_classes):
+    """Beyond 64 capacities the stepping kernel searches for itself; the candidates stay the same.
+    (There sja_resolve would need the matrix-scanning rounds, so only the candidates are checked.)"""
+    wl = make_workload("small", 9, n_gaps=900, n_jobs=700)
+    rng = np.random.default_rng(n_classes)
+    caps = np.sort(rng.choice(np.arange(2000, 60000), size=n_classes, replace=False)).astype(np.int32)
+    wl.C = caps[rng.integers(0, n_classes, size=wl.n_gaps)].astype(np.int32)
+    fused_check(engine, oracle, wl, policies=[3, 0], resolve=n_classes <= 64)
+
+
+def test_fused_then_matrix_rounds_is_refused(engine):
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("tiny", 0)
+    t = P.DeviceTick(engine, wl, want_cut=False)
+    t.prepare()
+    par = P.Params.make(0)
+    t.fit_select(par)
+    try:
+        engine.sja_set_resolve_mode(1)
+        with pytest.raises(P.SjaError):
+            t.resolve(par)
+        with pytest.raises(P.SjaError):
+            t.select(par)
+    finally:
+        engine.sja_set_resolve_mode(0)
+    torch.cuda.synchronize()
