@@ -180,6 +180,15 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # outside the timed steps: the fused fit -> select call (same candidates, no pair matrix)
+    fused_ms, fused_kernel_ms = [], []
+    for i in range(args.steps + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); tick.fit_select(par); e1.record(); e1.synchronize()
+        if i:
+            fused_ms.append(e0.elapsed_time(e1))
+            fused_kernel_ms.append(eng.sja_last_fit_kernel_ms())
+
     pairs = wl.n_gaps * wl.n_jobs
     ms_per_step = 1e3 * elapsed / args.steps
     mean = lambda xs: sum(xs) / len(xs)
@@ -208,6 +217,11 @@ def main():
         "call_ms": {k: mean(v) for k, v in rec.items()},
         "fit_evals_per_s": pairs / (mean(rec["fit"]) * 1e-3),
         "fit_kernel_evals_per_s": pairs / (fit_kernel_ms * 1e-3),
+        "fused_fit_select": {"call_ms": sum(fused_ms) / len(fused_ms),
+                             "kernel_ms": sum(fused_kernel_ms) / len(fused_kernel_ms),
+                             "evals_per_s": pairs / (sum(fused_ms) / len(fused_ms) * 1e-3),
+                             "note": "sja_fit_select: the candidates of fit + select without the pair matrix; "
+                                     "not part of the timed step"},
         "resolve": {"rounds": rounds, "stable": stable,
                     "grants": int((tick.grant_job >= 0).sum().item())},
         "interest_density": float((tick.cut >= 0).float().mean().item()) if pairs <= 2**29 else None,

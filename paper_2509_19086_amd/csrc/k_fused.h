@@ -22,8 +22,8 @@
 namespace sja {
 
 constexpr int kFusedBlock = kSelBlock;     // the partials are laid out per tile of kSelBlock jobs
-constexpr int kFusedWindow = 16;
-constexpr int kFusedPeriod = 64;
+constexpr int kFusedWindow = 8;
+constexpr int kFusedPeriod = 32;
 
 __device__ __forceinline__ bool fused_better(unsigned long long hi_a, unsigned long long lo_a, int j_a,
                                              unsigned long long hi_b, unsigned long long lo_b, int j_b)
@@ -40,8 +40,10 @@ __device__ __forceinline__ unsigned long long fused_readlane_u64(unsigned long l
     return (static_cast<unsigned long long>(hi) << 32) | lo;
 }
 
+// Eight waves per SIMD (64 registers, a few spilled) beat the 94 registers the
+// compiler takes by itself: the stepping loop is bound by latency (1.5 against 2.1 ms).
 template <int BLOCK, int CAP, int PERIOD, bool MIXED>
-__global__ __launch_bounds__(BLOCK) void k_fit_select(
+__global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_fit_select(
     int n_jobs, int n_gaps, int chunk_bound, PolicyDev pol, const int64_t *__restrict__ seg_off,
     const int2 *__restrict__ atom_dp, const int32_t *__restrict__ n_atoms,
     const int32_t *__restrict__ plan, const int32_t *__restrict__ chunk_begin,
@@ -49,17 +51,21 @@ __global__ __launch_bounds__(BLOCK) void k_fit_select(
     const int32_t *__restrict__ chunk_sub, const int32_t *__restrict__ start_tab,
     const int32_t *__restrict__ ncap_tab, const int32_t *__restrict__ gap_w,
     const int32_t *__restrict__ gap_c, const int32_t *__restrict__ gap_order,
-    const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
+    const int32_t *__restrict__ gap_run_end, const int32_t *__restrict__ wait,
+    const uint8_t *__restrict__ sla_class,
     const int32_t *__restrict__ job_held, const uint8_t *__restrict__ gap_active,
     SelPartial *__restrict__ part)
 {
     static_assert((CAP & (CAP - 1)) == 0 && BLOCK % kWave == 0 && PERIOD <= 64, "tile shape");
     constexpr int WAVES = BLOCK / kWave;
     __shared__ int2 win[CAP][BLOCK];
-    __shared__ unsigned long long s_hi[WAVES][PERIOD];
-    __shared__ unsigned long long s_lo[WAVES][PERIOD];
-    __shared__ int s_lane[WAVES][PERIOD];
-    __shared__ int s_atoms[WAVES][PERIOD];
+    // per wave and period: the steps at which its running best changed, with the new best
+    __shared__ unsigned long long e_hi[WAVES][PERIOD + 1];
+    __shared__ unsigned long long e_lo[WAVES][PERIOD + 1];
+    __shared__ int e_lane[WAVES][PERIOD + 1];
+    __shared__ int e_atoms[WAVES][PERIOD + 1];
+    __shared__ int e_step[WAVES][PERIOD + 1];
+    __shared__ int e_count[WAVES];
 
     const int xcd = blockIdx.x & 7;
     const int k = blockIdx.x >> 3;
@@ -91,6 +97,27 @@ __global__ __launch_bounds__(BLOCK) void k_fit_select(
     // the wave's running best, the same values in every lane
     unsigned long long best_hi = 0, best_lo = 0;
     int best_lane = kWave, best_atoms = 0;
+    int q_now = 0;       // step of the current period (for the change list)
+    int n_events = 0;    // entries of this wave's change list (the same in every lane)
+    int q_noted = -1;    // step of the list's last entry
+    auto uniform64 = [](unsigned long long v) {
+        const unsigned int lo = __builtin_amdgcn_readfirstlane(int(uint32_t(v)));
+        const unsigned int hi = __builtin_amdgcn_readfirstlane(int(uint32_t(v >> 32)));
+        return (static_cast<unsigned long long>(hi) << 32) | lo;
+    };
+    auto note = [&]() {
+        // at most one entry per step: a second change in the same step overwrites the first
+        if (n_events > 0 && q_noted == q_now) --n_events;
+        q_noted = q_now;
+        if (lane == 0) {
+            e_step[wave][n_events] = q_now;
+            e_hi[wave][n_events] = best_hi;
+            e_lo[wave][n_events] = best_lo;
+            e_lane[wave][n_events] = best_lane;
+            e_atoms[wave][n_events] = best_atoms;
+        }
+        ++n_events;
+    };
 
     auto key_of = [&](int d, int p) {
         const unsigned long long F = (unsigned long long)d * (unsigned long long)p;
@@ -115,10 +142,12 @@ __global__ __launch_bounds__(BLOCK) void k_fit_select(
             // best lane's own new key; a best lane that changed without being this maximum is beaten by it
             const bool own = (ch >> (best_lane & (kWave - 1))) & 1ull && best_lane < kWave;
             if (own || fused_better(bh, bl, bj, best_hi, best_lo, best_lane)) {
-                best_hi = bh; best_lo = bl; best_lane = bj;
-                best_atoms = __builtin_amdgcn_readlane(a, bj & (kWave - 1));
+                best_hi = uniform64(bh); best_lo = uniform64(bl); best_lane = __builtin_amdgcn_readfirstlane(bj);
+                best_atoms = __builtin_amdgcn_readlane(a, best_lane & (kWave - 1));
+                note();
             }
         } else {
+            bool moved = false;
             while (ch) {
                 const int l = __ffsll((long long)ch) - 1;
                 ch &= ch - 1;
@@ -127,8 +156,10 @@ __global__ __launch_bounds__(BLOCK) void k_fit_select(
                 if (l == best_lane || fused_better(kh, kl, l, best_hi, best_lo, best_lane)) {
                     best_hi = kh; best_lo = kl; best_lane = l;
                     best_atoms = __builtin_amdgcn_readlane(a, l);
+                    moved = true;
                 }
             }
+            if (moved) note();
         }
     };
     auto init = [&](int s) {
@@ -146,6 +177,7 @@ __global__ __launch_bounds__(BLOCK) void k_fit_select(
         if (a > 0) { const int2 v = dp[a - 1]; key_of(v.x, v.y); }
         hi = a;
         best_hi = 0; best_lo = 0; best_lane = kWave; best_atoms = 0;
+        note();
         challenge(a > 0);
     };
     auto reload = [&]() {
@@ -164,14 +196,15 @@ __global__ __launch_bounds__(BLOCK) void k_fit_select(
         hi = max(hi, want);
         reload();
     };
-    // One step: move every lane past the atoms that window w has reached, keep the
-    // running best, and note it for position s (slot q of this period).
-    auto step = [&](int w, int s, int q) {
+    // One step: move every lane past the atoms that window w has reached and keep the
+    // running best (q = step within the period).
+    auto step = [&](int w, int q) {
         bool adv = a < hi && nd <= w;
         if (__any(adv)) {
             bool changed = false;
+            int ld = 0, lp = 0;                  // (duration, peak) of the last atom passed
             do {
-                if (adv) { key_of(nd, np); ++a; nd = nd2; np = np2; changed = true; }
+                if (adv) { ld = nd; lp = np; ++a; nd = nd2; np = np2; changed = true; }
                 {
                     const int2 y = win[(a + 1) & (CAP - 1)][tid];
                     nd2 = y.x; np2 = y.y;
@@ -188,42 +221,54 @@ __global__ __launch_bounds__(BLOCK) void k_fit_select(
                 }
                 adv = a < hi && nd <= w;
             } while (__any(adv));
+            q_now = q;
+            if (changed) key_of(ld, lp);         // once per step, for the last atom passed
             challenge(changed && key_hi >= best_hi);
-        }
-        const int g = gap_order[s];
-        const bool on = !gap_active || gap_active[g];
-        if (lane == 0) {
-            const bool has = on && best_hi != 0;
-            s_hi[wave][q] = has ? best_hi : 0ull;
-            s_lo[wave][q] = has ? best_lo : 0ull;
-            s_lane[wave][q] = best_lane;
-            s_atoms[wave][q] = best_atoms;
         }
     };
 
     for (int s0 = s_begin; s0 < s_end; s0 += PERIOD) {
         const int s1 = min(s_end, s0 + PERIOD);
-        if (s0 == s_begin || gap_c[s0] != c_cur) init(s0);
+        n_events = 0;
+        q_now = 0;
+        q_noted = -1;
+        if (s0 == s_begin || gap_c[s0] != c_cur) init(s0); else note();     // the list starts with the best so far
         topup();
         dry_mask = __ballot(hi < n_cap);
-        for (int s = s0; s < s1; ++s) {
-            if (gap_c[s] != c_cur) { init(s); topup(); dry_mask = __ballot(hi < n_cap); }
-            step(gap_w[s], s, s - s0);
+        if (s1 - s0 == PERIOD && gap_run_end[s0] >= s1) {
+#pragma unroll
+            for (int u4 = 0; u4 < PERIOD; u4 += 4) {
+                const int wv[4] = {gap_w[s0 + u4], gap_w[s0 + u4 + 1], gap_w[s0 + u4 + 2], gap_w[s0 + u4 + 3]};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) step(wv[u], u4 + u);
+            }
+        } else {
+            for (int s = s0; s < s1; ++s) {
+                q_now = s - s0;
+                if (gap_c[s] != c_cur) { init(s); topup(); dry_mask = __ballot(hi < n_cap); }
+                step(gap_w[s], s - s0);
+            }
         }
+        if (lane == 0) e_count[wave] = n_events;
         __syncthreads();
-        // one partial per position of this period: the best of the block's waves
+        // one partial per position of this period: the best of the block's waves at that step
         for (int q = tid; q < s1 - s0; q += BLOCK) {
+            const int g = gap_order[s0 + q];
+            const bool on = !gap_active || gap_active[g];
             unsigned long long bh = 0, bl = 0;
             int bj = INT32_MAX, ba = 0;
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) {
-                const unsigned long long oh = s_hi[w][q], ol = s_lo[w][q];
-                const int oj = oh ? job_tile * BLOCK + w * kWave + s_lane[w][q] : INT32_MAX;
-                if (fused_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; ba = s_atoms[w][q]; }
+                const int ne = e_count[w];
+                int e = 0;                                   // the last change at or before step q
+                for (int i = 1; i < ne && e_step[w][i] <= q; ++i) e = i;
+                const unsigned long long oh = on ? e_hi[w][e] : 0ull, ol = e_lo[w][e];
+                const int oj = oh ? job_tile * BLOCK + w * kWave + e_lane[w][e] : INT32_MAX;
+                if (fused_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; ba = e_atoms[w][e]; }
             }
             SelPartial out;
             out.hi = bh; out.lo = bl; out.job = bh ? bj : -1; out.cut = bh ? ba : -1; out.pad = 0;
-            part[int64_t(job_tile) * n_gaps + gap_order[s0 + q]] = out;
+            part[int64_t(job_tile) * n_gaps + g] = out;
         }
         __syncthreads();
     }

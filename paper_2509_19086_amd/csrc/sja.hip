@@ -600,8 +600,9 @@ int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W,
                                ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
                                ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.start_tab),
                                ws_ptr<int32_t>(ctx, L.ncap_tab), ws_ptr<int32_t>(ctx, L.gap_w),
-                               ws_ptr<int32_t>(ctx, L.gap_c), ws_ptr<int32_t>(ctx, L.gap_order), wait, sla_class,
-                               job_held, gap_active, ws_ptr<SelPartial>(ctx, L.sel_part));
+                               ws_ptr<int32_t>(ctx, L.gap_c), ws_ptr<int32_t>(ctx, L.gap_order),
+                               ws_ptr<int32_t>(ctx, L.gap_run_end), wait, sla_class, job_held, gap_active,
+                               ws_ptr<SelPartial>(ctx, L.sel_part));
             SJA_HIP(hipGetLastError(), "k_fit_select launch");
             if (ctx->timing) {
                 SJA_HIP(hipEventRecord(ctx->ev_stop, st), "hipEventRecord");

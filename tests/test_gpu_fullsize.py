@@ -91,6 +91,18 @@ def _check_full_size(oracle, name, n_pairs, n_rows, max_rounds, until_stable=Fal
                 assert (rj == -1).all()
         return gj, gc, gs, jg, rounds, stable
 
+    # the fused call reports the same candidates as sja_select after sja_fit, for every gap
+    sel = (t.cand_job.clone(), t.cand_cut.clone(), t.cand_score.clone())
+    for out in (t.cand_job, t.cand_cut, t.cand_score):
+        out.fill_(-5)
+    t.fit_select(par)
+    torch.cuda.synchronize()
+    for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
+        assert torch.equal(a, b)
+    np.testing.assert_array_equal(t.cand_job[rows_t].cpu().numpy(), cj)
+    t.fit()                                   # the cut matrix again, for the matrix-scanning rounds below
+    torch.cuda.synchronize()
+
     first = check_grants(max_rounds)
     # the two implementations of the rounds agree bit for bit at full size
     try:
@@ -101,6 +113,7 @@ def _check_full_size(oracle, name, n_pairs, n_rows, max_rounds, until_stable=Fal
     for a, b in zip(first, other):
         np.testing.assert_array_equal(a, b)
     if until_stable:
+        t.fit_select(par)                     # resolve on top of the fused call: no cut matrix involved
         gj, _, _, _, rounds, stable = check_grants(0)
         assert stable == 1 and rounds > max_rounds
         # with the cap gone nothing granted before is taken back
