@@ -221,3 +221,15 @@ def make_workload(name: str, seed: int = 0, *, n_gaps: Optional[int] = None,
         wait=wait, sla_class=sla_class,
         policy=cfg.policy, max_rounds=cfg.max_rounds,
     )
+
+
+def make_gaps(name: str, seed: int, tick: int, n_gaps: Optional[int] = None):
+    """The gaps a scheduler advertises at a later tick of the same workload: a fresh (W, C)
+    batch with the config's distributions, from its own stream (seed, tick)."""
+    cfg = CONFIGS[name]
+    G = cfg.n_gaps if n_gaps is None else int(n_gaps)
+    rng = np.random.Generator(np.random.PCG64([int(seed), 1000003 + int(tick)]))
+    W = rng.integers(cfg.w_range[0], cfg.w_range[1] + 1, size=G, dtype=np.int64).astype(np.int32)
+    c_set = np.asarray(cfg.c_set, dtype=np.int32)
+    C = c_set[rng.integers(0, len(c_set), size=G)]
+    return np.ascontiguousarray(W), np.ascontiguousarray(C)

@@ -5,6 +5,6 @@ this package.  It shares nothing with the GPU path.
 """
 from .sja_oracle import (  # noqa: F401
     Params, build, lib_path, num_threads, set_num_threads,
-    prepare, fit, fit_pairs, select, resolve,
+    prepare, fit, fit_pairs, select, resolve, advance,
     POLICY_EFFICIENCY, POLICY_FAIRNESS, POLICY_SLA, POLICY_MIXED,
 )

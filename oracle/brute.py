@@ -121,3 +121,32 @@ def resolve(cut, seg_off, dur, mem, progress, wait, sla_class, policy, max_round
     grant_score = [grant[g][2] if grant[g] else 0 for g in range(G)]
     job_gap = [holder.get(j, -1) for j in range(J)]
     return grant_job, grant_cut, grant_score, job_gap, rounds, stable
+
+
+def advance(seg_off, dur, mem, W, C, grant_job, grant_cut, progress, wait, wait_step):
+    """One tick's bookkeeping straight from the raw segments (Sec. 3.1, 3.5; metrics of Sec. 5):
+    returns (progress', wait', [filled, offered, grants, finished])."""
+    J = len(seg_off) - 1
+    prog = [int(x) for x in progress]
+    wt = [int(x) for x in wait]
+    took = {}
+    for g, j in enumerate(grant_job):
+        if int(j) >= 0:
+            assert int(j) not in took
+            took[int(j)] = g
+    filled = 0
+    for j, g in took.items():
+        d = job_slices(seg_off, dur, j)[prog[j]:int(grant_cut[g])]
+        m = job_slices(seg_off, mem, j)[prog[j]:int(grant_cut[g])]
+        filled += sum(d) * max(m)
+    offered = sum(max(int(w), 0) * max(int(c), 0) for w, c in zip(W, C))
+    finished = 0
+    for j in range(J):
+        L = int(seg_off[j + 1]) - int(seg_off[j])
+        if j in took:
+            prog[j] = int(grant_cut[took[j]])
+            wt[j] = 0
+        elif prog[j] < L:
+            wt[j] = min(wt[j] + wait_step, 2**31 - 1)
+        finished += prog[j] >= L
+    return prog, wt, [filled, offered, len(took), finished]

@@ -21,6 +21,9 @@
  *     boundary (Sec. 3.9: prefer longer fragments), or declines (cut = -1).
  *   - The scheduler picks one interested job per gap by policy (Sec. 3.5, 4.2)
  *     and conflicts are settled in rounds so that a job holds at most one gap.
+ *   - Between ticks a granted job moves its progress point to the granted
+ *     boundary, the others wait longer (sjo_advance; pinned against a brute
+ *     force over the raw segments and the invariants of a chain of ticks).
  *
  * All sums and products are int64; a product that would overflow int64 makes
  * the call return SJO_ERR_OVERFLOW.  The outer loops over gaps may be split
@@ -330,3 +333,52 @@ int sjo_resolve(int32_t n_gaps, int32_t n_jobs, const int32_t *cut, const int64_
     free(cj); free(cc); free(cs); free(active);
     return rc;
 }
+
+/* ------------------------------------------------------------------------
+ * Advance to the next tick (Sec. 3.1 / 3.5: a parent job resumes from its last
+ * completed fragment; the metrics are those the paper plans to report in its
+ * evaluation, Sec. 5: utilisation, queueing delay, rejections).
+ * For every job that holds a gap: progress = the granted cut, wait = 0.  Every
+ * other job that still has segments left waits wait_step longer (saturating at
+ * INT32_MAX); a finished job keeps its wait.  wait may be NULL.
+ * pre_dur / pre_peak are sjo_prepare's outputs for the progress points BEFORE
+ * the advance.  metrics[0] = sum over granted gaps of duration * peak of the
+ * granted subjob, metrics[1] = sum over all gaps of max(W,0) * max(C,0),
+ * metrics[2] = number of grants, metrics[3] = jobs with nothing left after the
+ * advance.
+ * ---------------------------------------------------------------------- */
+int sjo_advance(int32_t n_gaps, int32_t n_jobs, const int64_t *seg_off, const int64_t *pre_dur,
+                const int64_t *pre_peak, const int32_t *W, const int32_t *C,
+                const int32_t *grant_job, const int32_t *grant_cut, const int32_t *job_gap,
+                int32_t *progress, int32_t *wait, int32_t wait_step, int64_t *metrics)
+{
+    if (n_gaps < 0 || n_jobs < 0 || wait_step < 0 || !metrics) return SJO_ERR_ARG;
+    int64_t filled = 0, offered = 0, grants = 0, finished = 0;
+    for (int32_t g = 0; g < n_gaps; ++g) {
+        int64_t w = W[g] > 0 ? W[g] : 0, c = C[g] > 0 ? C[g] : 0;
+        offered += w * c;
+        int32_t j = grant_job[g];
+        if (j < 0) continue;
+        if (j >= n_jobs || job_gap[j] != g) return SJO_ERR_ARG;
+        int64_t k = seg_off[j] + grant_cut[g] - 1;
+        if (grant_cut[g] <= progress[j] || k >= seg_off[j + 1]) return SJO_ERR_ARG;
+        filled += pre_dur[k] * pre_peak[k];
+        ++grants;
+    }
+    for (int32_t j = 0; j < n_jobs; ++j) {
+        int64_t L = seg_off[j + 1] - seg_off[j];
+        int32_t g = job_gap[j];
+        if (g >= 0) {
+            if (g >= n_gaps || grant_job[g] != j) return SJO_ERR_ARG;
+            progress[j] = grant_cut[g];
+            if (wait) wait[j] = 0;
+        } else if (progress[j] < L && wait) {
+            int64_t w = (int64_t)wait[j] + wait_step;
+            wait[j] = w > INT32_MAX ? INT32_MAX : (int32_t)w;
+        }
+        if (progress[j] >= L) ++finished;
+    }
+    metrics[0] = filled; metrics[1] = offered; metrics[2] = grants; metrics[3] = finished;
+    return SJO_OK;
+}
+

@@ -157,3 +157,21 @@ def resolve(cut, seg_off, pre_dur, pre_peak, params: Params, wait, sla_class):
                              _p(gs, np.int64), _p(jg, np.int32), _p(rs, np.int32))
     _check(rc, "sjo_resolve")
     return gj, gc, gs, jg, int(rs[0]), int(rs[1])
+
+
+def advance(seg_off, pre_dur, pre_peak, W, C, grant_job, grant_cut, job_gap, progress, wait, wait_step):
+    """Next tick's (progress, wait) and the tick's metrics (filled, offered, grants, finished).
+    progress and wait are copied, not changed in place; wait may be None."""
+    G, J = len(W), len(seg_off) - 1
+    prog = np.array(progress, dtype=np.int32, copy=True)
+    wt = None if wait is None else np.array(wait, dtype=np.int32, copy=True)
+    metrics = np.zeros(4, dtype=np.int64)
+    rc = _load().sjo_advance(ctypes.c_int32(G), ctypes.c_int32(J), _p(seg_off, np.int64),
+                             _p(pre_dur, np.int64), _p(pre_peak, np.int64), _p(W, np.int32),
+                             _p(C, np.int32), _p(grant_job, np.int32), _p(grant_cut, np.int32),
+                             _p(job_gap, np.int32), _p(prog, np.int32),
+                             _p(wt, np.int32) if wt is not None else None,
+                             ctypes.c_int32(wait_step), _p(metrics, np.int64))
+    _check(rc, "sjo_advance")
+    return prog, wt, metrics
+
