@@ -16,6 +16,8 @@
  *   sja_resolve           grants, with conflicts settled in rounds so that a job
  *                         holds at most one gap (Sec. 3.1 / 3.5: fragments of a
  *                         job are sequential from one progress point)
+ *   sja_advance           end of the tick: granted jobs move to their cut and
+ *                         only their tables are rebuilt (Sec. 3.1 / 3.5)
  *
  * Conventions
  *   - Every array argument is a DEVICE pointer owned by the caller, unless the
@@ -170,8 +172,8 @@ int sja_select(sja_ctx *ctx, void *stream, const sja_params *params, const int32
 
 /*
  * sja_fit followed by sja_select in one pass that never writes the (gap, job)
- * replies down (Sec. 3.5: "no subjob state is created until a grant is
- * issued"; the scheduler only needs the best reply per gap).  Arguments are
+ * replies down (Sec. 3.5: subjob state comes into being only at a grant, and
+ * the scheduler only needs the best reply per gap).  Arguments are
  * those of sja_fit (n_gaps, W, C) and of sja_select (params, wait, sla_class,
  * job_held, gap_active, cand_*), with the same meaning, layout and results:
  * cand_job / cand_cut / cand_score equal what sja_select would report after
@@ -203,6 +205,39 @@ int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W,
 int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int32_t *wait,
                 const uint8_t *sla_class, int32_t *grant_job, int32_t *grant_cut,
                 int64_t *grant_score, int32_t *job_gap, int32_t *rounds_used_and_stable);
+
+/*
+ * End of a tick: apply the grants and get the job table ready for the next
+ * batch of gaps (Sec. 3.1 / 3.5: a parent job resumes from its last completed
+ * fragment; the totals are the quantities Sec. 5 plans to report: utilisation,
+ * queueing delay, grants against offers).
+ *   W, C [n_gaps]                    the gaps the grants were made for
+ *   grant_job, grant_cut [n_gaps]    as sja_resolve left them
+ *   job_gap [n_jobs]                 as sja_resolve left it
+ *   progress [n_jobs] int32, in/out  a job holding a gap moves to its granted cut
+ *   wait [n_jobs] int32, in/out      0 for a job holding a gap; any other job
+ *                                    with segments left waits wait_step (>= 0)
+ *                                    longer, saturating at 2^31-1; a finished job
+ *                                    keeps its value.  May be NULL.
+ *   metrics [4] int64, out           [0] sum over grants of duration x peak of the
+ *                                    granted subjob, [1] sum over gaps of
+ *                                    max(W,0) x max(C,0), [2] grants, [3] jobs with
+ *                                    no segment left after the move
+ * The running tables of the last sja_prepare_profiles (pre_dur, pre_peak,
+ * prev_safe, still owned by the caller, and the library's own per-job tables)
+ * are rebuilt for the jobs that moved and left as they are for the others, so
+ * the next sja_fit / sja_fit_select needs no sja_prepare_profiles; this call
+ * reads dur, mem, safe and seg_off through the pointers given to that call,
+ * which must still be alive and unchanged.  `progress` may be the array given
+ * to sja_prepare_profiles or a copy of it.  A grant counts when grant_job[g] = j
+ * and job_gap[j] = g point at each other and progress[j] < grant_cut[g] <= L_j;
+ * any other entry is ignored (no grant).  The cut matrix, candidates and lists
+ * of the last fit are stale afterwards: sja_select / sja_resolve need a new
+ * sja_fit or sja_fit_select.  Only enqueues work.
+ */
+int sja_advance(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
+                const int32_t *grant_job, const int32_t *grant_cut, const int32_t *job_gap,
+                int32_t *progress, int32_t *wait, int32_t wait_step, int64_t *metrics);
 
 /*
  * Measurement aid for benchmarks (callers that report the pair-evaluation

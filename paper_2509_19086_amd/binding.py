@@ -72,6 +72,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_fit_select.argtypes = [vp, vp, i32, vp, vp, ctypes.POINTER(Params)] + [vp] * 7
     lib.sja_fit_select.restype = ctypes.c_int
     lib.sja_resolve.restype = ctypes.c_int
+    lib.sja_advance.argtypes = [vp, vp, i32] + [vp] * 7 + [i32, vp]
+    lib.sja_advance.restype = ctypes.c_int
     lib.sja_enable_timing.argtypes = [vp, ctypes.c_int]
     lib.sja_enable_timing.restype = ctypes.c_int
     lib.sja_last_fit_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
@@ -204,4 +206,12 @@ class Engine:
                 _ptr(grant_score, torch.int64, G), _ptr(job_gap, torch.int32, J),
                 _ptr(rounds_used_and_stable, torch.int32, 2))
         rc = self.lib.sja_resolve(self.h, _stream(), ctypes.byref(params), *args)
+        self._check(rc, self.h)
+
+    def sja_advance(self, W, C, grant_job, grant_cut, job_gap, progress, wait, wait_step, metrics):
+        G, J = W.numel(), self.n_jobs
+        args = (_ptr(W, torch.int32, G), _ptr(C, torch.int32, G), _ptr(grant_job, torch.int32, G),
+                _ptr(grant_cut, torch.int32, G), _ptr(job_gap, torch.int32, J),
+                _ptr(progress, torch.int32, J), _ptr(wait, torch.int32, J))
+        rc = self.lib.sja_advance(self.h, _stream(), G, *args, int(wait_step), _ptr(metrics, torch.int64, 4))
         self._check(rc, self.h)

@@ -420,6 +420,47 @@ int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes)
     return SJA_OK;
 }
 
+int sja_advance(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
+                const int32_t *grant_job, const int32_t *grant_cut, const int32_t *job_gap, int32_t *progress,
+                int32_t *wait, int32_t wait_step, int64_t *metrics)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_advance before sja_prepare_profiles");
+    if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
+    if (wait_step < 0) return fail(ctx, SJA_ERR_SIZE, "wait_step");
+    if (n_gaps > 0 && (!W || !C || !grant_job || !grant_cut)) return fail(ctx, SJA_ERR_NULL, "gap arrays");
+    const int J = ctx->n_jobs;
+    if (J > 0 && (!job_gap || !progress)) return fail(ctx, SJA_ERR_NULL, "job_gap / progress");
+    if (!metrics) return fail(ctx, SJA_ERR_NULL, "metrics");
+    const Layout L = make_layout(0, J, ctx->n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small");
+
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the profiles of the granted jobs change: whatever the last fit left no longer describes them
+    ctx->fitted = false;
+    ctx->planned = false;
+    unsigned long long *m = reinterpret_cast<unsigned long long *>(metrics);
+    hipLaunchKernelGGL(k_fill_i64, dim3(1), dim3(64), 0, st, 4, int64_t(0), metrics);
+    SJA_HIP(hipGetLastError(), "k_fill_i64 launch");
+    if (n_gaps > 0) {
+        hipLaunchKernelGGL(k_advance_gaps, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, J, ctx->seg_off,
+                           ctx->pre_dur, ctx->pre_peak, W, C, grant_job, grant_cut, job_gap, progress, m);
+        SJA_HIP(hipGetLastError(), "k_advance_gaps launch");
+    }
+    if (J > 0) {
+        const int jobs_per_block = 256 / kWave;
+        hipLaunchKernelGGL(k_advance_jobs, dim3((J + jobs_per_block - 1) / jobs_per_block), dim3(256), 0, st,
+                           n_gaps, J, ctx->seg_off, ctx->dur, ctx->mem, ctx->safe, grant_job, grant_cut, job_gap,
+                           progress, wait, wait_step, ctx->pre_dur, ctx->pre_peak, ctx->prev_safe,
+                           ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),
+                           ws_ptr<int32_t>(ctx, L.n_atoms), ws_ptr<int2>(ctx, L.first_dp), m);
+        SJA_HIP(hipGetLastError(), "k_advance_jobs launch");
+    }
+    return SJA_OK;
+}
+
 int sja_enable_timing(sja_ctx *ctx, int on)
 {
     if (!ctx) return SJA_ERR_NULL;
@@ -478,8 +519,12 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
     ctx->n_jobs = n_jobs;
     ctx->n_segments = n_segments;
     ctx->seg_off = seg_off;
+    ctx->dur = dur;
+    ctx->mem = mem;
+    ctx->safe = safe;
     ctx->pre_dur = pre_dur;
     ctx->pre_peak = pre_peak;
+    ctx->prev_safe = prev_safe;
     ctx->prepared = true;
     return SJA_OK;
 }

@@ -191,8 +191,12 @@ struct sja_ctx {
     int32_t n_jobs;
     int64_t n_segments;
     const int64_t *seg_off;
-    const int32_t *pre_dur;
-    const int32_t *pre_peak;
+    const int32_t *dur;
+    const int32_t *mem;
+    const uint8_t *safe;
+    int32_t *pre_dur;
+    int32_t *pre_peak;
+    int32_t *prev_safe;
 
     // optional timing of the pair-evaluation kernel
     bool timing;

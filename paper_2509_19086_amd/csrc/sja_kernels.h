@@ -41,22 +41,14 @@ __device__ __forceinline__ void wave_scan_add_max_max(int &s, int &m, int &l, in
 // cut after the progress point) into the workspace at the job's segment base,
 // as (duration, peak) and (duration, boundary) pairs.
 // --------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_prepare(
-    int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
-    const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
-    const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
+// One wave walks job j's segments from boundary p to the job's end.
+__device__ __forceinline__ void prepare_job(
+    int j, int lane, int64_t base, int L, int p, const int32_t *__restrict__ dur,
+    const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
     int2 *__restrict__ atom_dp, int2 *__restrict__ atom_db, int32_t *__restrict__ n_atoms,
     int2 *__restrict__ first_dp)
 {
-    const int lane = lane_id();
-    const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-    if (j >= n_jobs) return;
-    const int64_t base = seg_off[j];
-    const int L = int(seg_off[j + 1] - base);
-    int p = progress[j];
-    p = p < 0 ? 0 : (p > L ? L : p);
-
     int carry_sum = 0, carry_peak = INT32_MIN, carry_last = -1, count = 0;
     int first_d = INT32_MAX, first_p = INT32_MAX;     // the first atom, if there is one
     for (int k0 = p; k0 < L; k0 += kWave) {
@@ -98,6 +90,142 @@ __global__ __launch_bounds__(256) void k_prepare(
     if (lane == 0) {
         n_atoms[j] = count;
         first_dp[j] = make_int2(first_d, first_p);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_prepare(
+    int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
+    const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
+    int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
+    int2 *__restrict__ atom_dp, int2 *__restrict__ atom_db, int32_t *__restrict__ n_atoms,
+    int2 *__restrict__ first_dp)
+{
+    const int lane = lane_id();
+    const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (j >= n_jobs) return;
+    const int64_t base = seg_off[j];
+    const int L = int(seg_off[j + 1] - base);
+    int p = progress[j];
+    p = p < 0 ? 0 : (p > L ? L : p);
+    prepare_job(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db, n_atoms,
+                first_dp);
+}
+
+// --------------------------------------------------------------------------
+// Tick advance (Sec. 3.1 / 3.5: the parent resumes from its last completed
+// fragment).  A grant counts when the two tables point at each other and the
+// cut lies in (progress, L]; anything else is treated as no grant.
+// --------------------------------------------------------------------------
+__device__ __forceinline__ bool grant_holds(int g, int j, int n_gaps, int n_jobs,
+                                            const int64_t *__restrict__ seg_off,
+                                            const int32_t *__restrict__ grant_job,
+                                            const int32_t *__restrict__ grant_cut,
+                                            const int32_t *__restrict__ job_gap,
+                                            const int32_t *__restrict__ progress, int &cut_out)
+{
+    if (g < 0 || g >= n_gaps || j < 0 || j >= n_jobs) return false;
+    if (grant_job[g] != j || job_gap[j] != g) return false;
+    const int L = int(seg_off[j + 1] - seg_off[j]);
+    int p = progress[j];
+    p = p < 0 ? 0 : (p > L ? L : p);
+    const int c = grant_cut[g];
+    cut_out = c;
+    return c > p && c <= L;
+}
+
+__global__ __launch_bounds__(64) void k_fill_i64(int n, int64_t value, int64_t *__restrict__ out)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = value;
+}
+
+// The tick's totals over gaps: filled area of the grants (from the running
+// duration and peak at the granted boundary, before progress moves), offered
+// area, number of grants.  One atomic per block and counter.
+__global__ __launch_bounds__(256) void k_advance_gaps(
+    int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ pre_dur,
+    const int32_t *__restrict__ pre_peak, const int32_t *__restrict__ W, const int32_t *__restrict__ C,
+    const int32_t *__restrict__ grant_job, const int32_t *__restrict__ grant_cut,
+    const int32_t *__restrict__ job_gap, const int32_t *__restrict__ progress,
+    unsigned long long *__restrict__ metrics)
+{
+    __shared__ unsigned long long s_sum[3][256 / kWave];
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned long long filled = 0, offered = 0, grants = 0;
+    if (g < n_gaps) {
+        const int w = W[g], c = C[g];
+        offered = (unsigned long long)(w > 0 ? w : 0) * (unsigned long long)(c > 0 ? c : 0);
+        const int j = grant_job[g];
+        int cut;
+        if (grant_holds(g, j, n_gaps, n_jobs, seg_off, grant_job, grant_cut, job_gap, progress, cut)) {
+            const int64_t k = seg_off[j] + cut - 1;
+            filled = (unsigned long long)pre_dur[k] * (unsigned long long)pre_peak[k];
+            grants = 1;
+        }
+    }
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        filled += __shfl_xor(filled, d, kWave);
+        offered += __shfl_xor(offered, d, kWave);
+        grants += __shfl_xor(grants, d, kWave);
+    }
+    const int wave = threadIdx.x / kWave;
+    if (lane_id() == 0) {
+        s_sum[0][wave] = filled;
+        s_sum[1][wave] = offered;
+        s_sum[2][wave] = grants;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        unsigned long long t = 0;
+        for (int i = 0; i < 256 / kWave; ++i) t += s_sum[threadIdx.x][i];
+        if (t) atomicAdd(&metrics[threadIdx.x], t);
+    }
+}
+
+// One wave per job: a granted job moves to its cut, stops waiting and has its
+// running tables and atoms rebuilt from there; any other unfinished job waits
+// wait_step longer.  metrics[3] counts the jobs with nothing left afterwards.
+__global__ __launch_bounds__(256) void k_advance_jobs(
+    int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
+    const int32_t *__restrict__ grant_job, const int32_t *__restrict__ grant_cut,
+    const int32_t *__restrict__ job_gap, int32_t *__restrict__ progress, int32_t *__restrict__ wait,
+    int wait_step, int32_t *__restrict__ pre_dur, int32_t *__restrict__ pre_peak,
+    int32_t *__restrict__ prev_safe, int2 *__restrict__ atom_dp, int2 *__restrict__ atom_db,
+    int32_t *__restrict__ n_atoms, int2 *__restrict__ first_dp, unsigned long long *__restrict__ metrics)
+{
+    __shared__ int s_done[256 / kWave];
+    const int lane = lane_id();
+    const int wave = threadIdx.x / kWave;
+    const int j = blockIdx.x * (blockDim.x / kWave) + wave;
+    int done = 0;
+    if (j < n_jobs) {
+        const int64_t base = seg_off[j];
+        const int L = int(seg_off[j + 1] - base);
+        int p = progress[j];
+        int cut;
+        // every lane evaluates the same scalars, so the branch is uniform over the wave
+        if (grant_holds(job_gap[j], j, n_gaps, n_jobs, seg_off, grant_job, grant_cut, job_gap, progress, cut)) {
+            p = cut;
+            prepare_job(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db,
+                        n_atoms, first_dp);
+            if (lane == 0) {
+                progress[j] = p;
+                if (wait) wait[j] = 0;
+            }
+        } else if (p < L && wait && lane == 0) {
+            const int64_t t = int64_t(wait[j]) + wait_step;
+            wait[j] = t > INT32_MAX ? INT32_MAX : int32_t(t);
+        }
+        done = p >= L;
+    }
+    if (lane == 0) s_done[wave] = done;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long t = 0;
+        for (int i = 0; i < 256 / kWave; ++i) t += s_done[i];
+        if (t) atomicAdd(&metrics[3], t);
     }
 }
 

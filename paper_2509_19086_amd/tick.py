@@ -37,6 +37,7 @@ class DeviceTick:
         self.grant_score = torch.empty(self.G, dtype=torch.int64, device=dev)
         self.job_gap = torch.empty(self.J, **i32)
         self.rounds = torch.zeros(2, **i32)
+        self.metrics = torch.zeros(4, dtype=torch.int64, device=dev)
         engine.ensure_workspace(self.G, self.J, self.S)
 
     def prepare(self):
@@ -53,6 +54,15 @@ class DeviceTick:
     def fit_select(self, params: Params, job_held=None, gap_active=None):
         self.engine.sja_fit_select(self.W, self.C, params, self.wait, self.sla_class, job_held, gap_active,
                                    self.cand_job, self.cand_cut, self.cand_score)
+
+    def set_gaps(self, W, C):
+        """The next tick's gaps (numpy int32, the same count as before), copied into place."""
+        self.W.copy_(torch.from_numpy(np.ascontiguousarray(W)))
+        self.C.copy_(torch.from_numpy(np.ascontiguousarray(C)))
+
+    def advance(self, wait_step: int):
+        self.engine.sja_advance(self.W, self.C, self.grant_job, self.grant_cut, self.job_gap,
+                                self.progress, self.wait, wait_step, self.metrics)
 
     def resolve(self, params: Params):
         self.engine.sja_resolve(params, self.wait, self.sla_class, self.grant_job, self.grant_cut,

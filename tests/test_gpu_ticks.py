@@ -1,0 +1,197 @@
+"""GPU parity over a chain of scheduling ticks: fit, grants, then sja_advance
+moves the granted jobs and rebuilds only their tables.  The oracle side runs a
+full prepare from the new progress points every tick, so a stale or wrongly
+rebuilt table shows up in the next tick's fit.  Integer work: bit-exact."""
+import numpy as np
+import pytest
+
+from gen import make_gaps, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def engine():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2509_19086_amd as P
+    return P.Engine(0)
+
+
+def _live_mask(seg_off, progress):
+    """Segments at or after each job's progress point: the part of the running tables that is defined."""
+    S = int(seg_off[-1])
+    job = np.repeat(np.arange(len(progress)), np.diff(seg_off))
+    k = np.arange(S) - seg_off[:-1][job]
+    return k >= progress[job]
+
+
+def _check_tables(t, oracle, wl, progress):
+    pd, pp, ps = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, progress)
+    live = _live_mask(wl.seg_off, progress)
+    np.testing.assert_array_equal(t.pre_dur.cpu().numpy().astype(np.int64)[live], pd[live])
+    np.testing.assert_array_equal(t.pre_peak.cpu().numpy().astype(np.int64)[live], pp[live])
+    np.testing.assert_array_equal(t.prev_safe.cpu().numpy()[live], ps[live])
+    return pd, pp
+
+
+def run_ticks(engine, oracle, name, seed, n_ticks, policy, fused, wait_step, n_gaps=None, n_jobs=None,
+              with_wait=True):
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload(name, seed, n_gaps=n_gaps, n_jobs=n_jobs)
+    par = P.Params.make(policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    opar = oracle.Params.make(policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    t = P.DeviceTick(engine, wl, want_bits=False, want_cut=not fused)
+    t.prepare()
+    progress, wait = wl.progress.copy(), wl.wait.copy()
+    lens = np.diff(wl.seg_off)
+    moved_total = 0
+    for tick in range(n_ticks):
+        W, C = (wl.W, wl.C) if tick == 0 else make_gaps(name, seed, tick, wl.n_gaps)
+        t.set_gaps(W, C)
+        if fused:
+            t.fit_select(par)
+        else:
+            t.fit()
+        t.resolve(par)
+        pd, pp = _check_tables(t, oracle, wl, progress)
+        cut, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, progress, W, C, False)
+        if not fused:
+            np.testing.assert_array_equal(t.cut.cpu().numpy(), cut, err_msg=f"tick {tick}")
+        gj, gc, gs, jg, rounds, stable = oracle.resolve(cut, wl.seg_off, pd, pp, opar, wait, wl.sla_class)
+        np.testing.assert_array_equal(t.grant_job.cpu().numpy(), gj, err_msg=f"tick {tick}")
+        np.testing.assert_array_equal(t.grant_cut.cpu().numpy(), gc, err_msg=f"tick {tick}")
+        np.testing.assert_array_equal(t.grant_score.cpu().numpy(), gs, err_msg=f"tick {tick}")
+        np.testing.assert_array_equal(t.job_gap.cpu().numpy(), jg, err_msg=f"tick {tick}")
+        assert t.rounds.cpu().tolist() == [rounds, stable]
+
+        t.metrics.fill_(-9)
+        if with_wait:
+            t.advance(wait_step)
+        else:
+            engine.sja_advance(t.W, t.C, t.grant_job, t.grant_cut, t.job_gap, t.progress, None, wait_step,
+                               t.metrics)
+        torch.cuda.synchronize()
+        p2, w2, m = oracle.advance(wl.seg_off, pd, pp, W, C, gj, gc, jg, progress, wait if with_wait else None,
+                                   wait_step)
+        np.testing.assert_array_equal(t.progress.cpu().numpy(), p2, err_msg=f"tick {tick}")
+        if with_wait:
+            np.testing.assert_array_equal(t.wait.cpu().numpy(), w2, err_msg=f"tick {tick}")
+            wait = w2
+        else:
+            np.testing.assert_array_equal(t.wait.cpu().numpy(), wait)
+        assert t.metrics.cpu().tolist() == m.tolist(), f"tick {tick}"
+        moved_total += int((p2 != progress).sum())
+        progress = p2
+    _check_tables(t, oracle, wl, progress)
+    assert moved_total > 0
+    return progress, lens
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3])
+@pytest.mark.parametrize("fused", [False, True])
+def test_tiny_chain_of_ticks(engine, oracle, policy, fused):
+    run_ticks(engine, oracle, "tiny", 1, 6, policy, fused, wait_step=250)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_small_chain_of_ticks(engine, oracle, fused):
+    run_ticks(engine, oracle, "small", 2, 5, 3, fused, wait_step=1000)
+
+
+def test_medium_chain_of_ticks(engine, oracle):
+    run_ticks(engine, oracle, "medium", 0, 3, 3, True, wait_step=1000)
+
+
+def test_ragged_chain_without_wait(engine, oracle):
+    """Odd sizes; no waiting-time array; jobs longer than one 64-segment stride are rebuilt mid-profile."""
+    run_ticks(engine, oracle, "stress", 7, 4, 0, True, wait_step=1, n_gaps=333, n_jobs=1111, with_wait=False)
+
+
+def test_ticks_until_every_job_is_done(engine, oracle):
+    """More gap capacity than work: the chain ends with every progress point at its job's end."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("tiny", 3)
+    lens = np.diff(wl.seg_off)
+    wl.W = np.full(wl.n_gaps, 2**24, dtype=np.int32)
+    wl.C = np.full(wl.n_gaps, 2**20, dtype=np.int32)
+    par = P.Params.make(1, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    t = P.DeviceTick(engine, wl, want_bits=False, want_cut=False)
+    t.prepare()
+    left = int((wl.progress < lens).sum())
+    work = sum(int(wl.dur[wl.seg_off[j] + wl.progress[j]:wl.seg_off[j + 1]].sum()) *
+               int(wl.mem[wl.seg_off[j] + wl.progress[j]:wl.seg_off[j + 1]].max())
+               for j in range(wl.n_jobs) if wl.progress[j] < lens[j])
+    filled = 0
+    for tick in range((left + wl.n_gaps - 1) // wl.n_gaps + 1):
+        t.fit_select(par)
+        t.resolve(par)
+        t.advance(1)
+        m = t.metrics.cpu().tolist()
+        filled += m[0]
+        left -= m[2]
+        assert m[2] == min(wl.n_gaps, left + m[2]) and m[3] == wl.n_jobs - left
+    assert left == 0 and filled == work
+    np.testing.assert_array_equal(t.progress.cpu().numpy(), lens.astype(np.int32))
+    t.fit_select(par)                                          # nothing left to offer
+    torch.cuda.synchronize()
+    assert (t.cand_job.cpu().numpy() == -1).all()
+
+
+def test_entries_that_do_not_hold_are_ignored(engine, oracle):
+    """Grant tables that do not point at each other, or cuts outside (progress, L], move nothing."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("small", 4, n_gaps=40, n_jobs=200)
+    lens = np.diff(wl.seg_off).astype(np.int32)
+    par = P.Params.make(0, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    t = P.DeviceTick(engine, wl, want_bits=False, want_cut=False)
+    t.prepare(); t.fit_select(par); t.resolve(par)
+    gj, gc, jg = (x.cpu().numpy().copy() for x in (t.grant_job, t.grant_cut, t.job_gap))
+    granted = np.nonzero(gj >= 0)[0]
+    assert len(granted) >= 8
+    bad_gj, bad_gc, bad_jg = gj.copy(), gc.copy(), jg.copy()
+    a, b, c, d, e = granted[:5]
+    bad_jg[gj[a]] = -1                                          # job does not point back
+    bad_gc[b] = lens[gj[b]] + 1                                 # beyond the job's end
+    bad_gc[c] = wl.progress[gj[c]]                              # does not move forward
+    bad_gj[d] = wl.n_jobs + 5                                   # no such job
+    bad_jg[gj[e]] = wl.n_gaps + 3                               # no such gap
+    clean_gj, clean_gc, clean_jg = gj.copy(), gc.copy(), jg.copy()
+    for g in (a, b, c, d, e):
+        clean_jg[gj[g]] = -1
+        clean_gj[g] = -1
+        clean_gc[g] = -1
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    p2, w2, m = oracle.advance(wl.seg_off, pd, pp, wl.W, wl.C, clean_gj, clean_gc, clean_jg, wl.progress,
+                               wl.wait, 7)
+    dev = t.W.device
+    t.grant_job.copy_(torch.from_numpy(bad_gj)); t.grant_cut.copy_(torch.from_numpy(bad_gc))
+    t.job_gap.copy_(torch.from_numpy(bad_jg))
+    t.advance(7)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t.progress.cpu().numpy(), p2)
+    np.testing.assert_array_equal(t.wait.cpu().numpy(), w2)
+    assert t.metrics.cpu().tolist() == m.tolist()
+    _check_tables(t, oracle, wl, p2)
+
+
+def test_advance_state_and_argument_checks(engine):
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("tiny", 0)
+    eng = P.Engine(0)
+    t = P.DeviceTick(eng, wl, want_bits=False, want_cut=False)
+    par = P.Params.make(0, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    with pytest.raises(RuntimeError):                          # nothing prepared yet
+        t.advance(1)
+    t.prepare(); t.fit_select(par); t.resolve(par)
+    with pytest.raises(RuntimeError):
+        t.advance(-1)
+    t.advance(1)
+    with pytest.raises(RuntimeError):                          # the lists of the last fit are stale now
+        t.resolve(par)
+    t.fit_select(par); t.resolve(par)                          # a new fit needs no new prepare
+    torch.cuda.synchronize()
