@@ -119,6 +119,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (reference reading for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE) and exit")
+    ap.add_argument("--chain-ticks", type=int, default=4,
+                    help="ticks in the carried-over chain measured after the timed steps")
     args = ap.parse_args()
     if args.copy_calibration:
         import torch
@@ -196,6 +198,30 @@ def main():
     alg_bytes = algorithmic_fit_bytes(wl, n_atoms)
     achieved = alg_bytes / (fit_kernel_ms * 1e-3) / 1e9
     rounds, stable = tick.rounds.cpu().tolist()
+    grants = int((tick.grant_job >= 0).sum().item())
+    interest_density = float((tick.cut >= 0).float().mean().item()) if pairs <= 2**29 else None
+
+    # outside the timed steps: a chain of ticks with fresh gaps each tick (fused fit-select,
+    # grants, advance), the job tables carried over instead of prepared again
+    from gen import make_gaps
+    chain_gaps = [(tick.W, tick.C)] + [tuple(torch.from_numpy(a).cuda() for a in
+                                             make_gaps(args.workload, args.seed, k)) for k in range(1, args.chain_ticks)]
+    chain = {"tick_ms": [], "advance_ms": [], "grants": [], "rounds": [], "utilisation": []}
+    tick.prepare()
+    for W_k, C_k in chain_gaps:
+        tick.W, tick.C = W_k, C_k
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record(); tick.fit_select(par); tick.resolve(par)
+        e[1].record(); tick.advance(1000)
+        e[2].record(); e[2].synchronize()
+        m = tick.metrics.cpu().tolist()
+        chain["tick_ms"].append(e[0].elapsed_time(e[2]))
+        chain["advance_ms"].append(e[1].elapsed_time(e[2]))
+        chain["grants"].append(m[2])
+        chain["rounds"].append(tick.rounds.cpu().tolist()[0])
+        chain["utilisation"].append(m[0] / m[1] if m[1] else None)
+    chain["note"] = ("sja_fit_select + sja_resolve + sja_advance per tick, new gaps every tick, no prepare "
+                     "after the first; not part of the timed step")
 
     out = {
         "metric": "gap-job fit evaluations/sec (whole tick: prepare+fit+select+resolve), 1 GPU",
@@ -222,9 +248,9 @@ def main():
                              "evals_per_s": pairs / (sum(fused_ms) / len(fused_ms) * 1e-3),
                              "note": "sja_fit_select: the candidates of fit + select without the pair matrix; "
                                      "not part of the timed step"},
-        "resolve": {"rounds": rounds, "stable": stable,
-                    "grants": int((tick.grant_job >= 0).sum().item())},
-        "interest_density": float((tick.cut >= 0).float().mean().item()) if pairs <= 2**29 else None,
+        "tick_chain": chain,
+        "resolve": {"rounds": rounds, "stable": stable, "grants": grants},
+        "interest_density": interest_density,
         "roofline": {"kernel": "k_fit_main", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_fit_traffic(args.workload, args.seed),

@@ -127,3 +127,65 @@ def test_large_full_size(oracle):
 
 def test_stress_full_size(oracle):
     _check_full_size(oracle, "stress", n_pairs=300_000, n_rows=12, max_rounds=8, until_stable=True)
+
+
+def test_stress_chain_of_ticks(oracle):
+    """Three ticks at the full Stress size: fused fit-select, grants until stable, advance.
+    Each tick the oracle evaluates every granted pair from the progress points it tracks itself,
+    which fixes the cuts, the filled area and the new progress points; whole running tables are
+    compared after each advance, and sampled gap rows pin the next tick's candidates."""
+    import torch
+    import paper_2509_19086_amd as P
+    from gen import make_gaps
+    wl = make_workload("stress", 0)
+    G, J = wl.n_gaps, wl.n_jobs
+    lens = np.diff(wl.seg_off)
+    eng = P.Engine(0)
+    t = P.DeviceTick(eng, wl, want_bits=False, want_cut=False)
+    par = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    opar = oracle.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    t.prepare()
+    progress, wait = wl.progress.copy(), wl.wait.copy()
+    rng = np.random.default_rng(5)
+    job_of_seg = np.repeat(np.arange(J), lens)
+    k_in_job = np.arange(int(wl.seg_off[-1])) - wl.seg_off[:-1][job_of_seg]
+    for tick in range(3):
+        W, C = (wl.W, wl.C) if tick == 0 else make_gaps("stress", 0, tick)
+        t.set_gaps(W, C)
+        t.fit_select(par)
+        torch.cuda.synchronize()
+        pd, pp, ps = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, progress)
+        rows = np.unique(np.concatenate([[0, G - 1], rng.integers(0, G, size=6)])).astype(np.int64)
+        cut_r, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, progress,
+                              np.ascontiguousarray(W[rows]), np.ascontiguousarray(C[rows]), False)
+        cj, cc, cs = oracle.select(cut_r, wl.seg_off, pd, pp, opar, wait, wl.sla_class)
+        rows_t = torch.from_numpy(rows).cuda()
+        np.testing.assert_array_equal(t.cand_job[rows_t].cpu().numpy(), cj, err_msg=f"tick {tick}")
+        np.testing.assert_array_equal(t.cand_cut[rows_t].cpu().numpy(), cc, err_msg=f"tick {tick}")
+        np.testing.assert_array_equal(t.cand_score[rows_t].cpu().numpy(), cs, err_msg=f"tick {tick}")
+
+        t.resolve(par)
+        gj = t.grant_job.cpu().numpy(); gc = t.grant_cut.cpu().numpy(); jg = t.job_gap.cpu().numpy()
+        assert t.rounds.cpu().tolist()[1] == 1
+        granted = np.nonzero(gj >= 0)[0]
+        assert len(granted) > 0 and len(np.unique(gj[granted])) == len(granted)
+        np.testing.assert_array_equal(jg[gj[granted]], granted)
+        assert (jg >= 0).sum() == len(granted)
+        ocut, sd, sp = oracle.fit_pairs(granted.astype(np.int32), gj[granted], wl.seg_off, wl.dur, wl.mem,
+                                        wl.safe, progress, W, C)
+        np.testing.assert_array_equal(gc[granted], ocut)
+        assert gj[0] == cj[0] and gc[0] == cc[0]               # gap 0 keeps its first choice
+
+        t.advance(1000)
+        torch.cuda.synchronize()
+        p2, w2, m = oracle.advance(wl.seg_off, pd, pp, W, C, gj, gc, jg, progress, wait, 1000)
+        assert m[0] == int((sd * sp).sum())                     # the oracle's own two routes agree
+        np.testing.assert_array_equal(t.progress.cpu().numpy(), p2)
+        np.testing.assert_array_equal(t.wait.cpu().numpy(), w2)
+        assert t.metrics.cpu().tolist() == m.tolist()
+        progress, wait = p2, w2
+        pd2, pp2, ps2 = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, progress)
+        live = k_in_job >= progress[job_of_seg]
+        np.testing.assert_array_equal(t.pre_dur.cpu().numpy().astype(np.int64)[live], pd2[live])
+        np.testing.assert_array_equal(t.pre_peak.cpu().numpy().astype(np.int64)[live], pp2[live])
+        np.testing.assert_array_equal(t.prev_safe.cpu().numpy()[live], ps2[live])
