@@ -150,3 +150,32 @@ def advance(seg_off, dur, mem, W, C, grant_job, grant_cut, progress, wait, wait_
             wt[j] = min(wt[j] + wait_step, 2**31 - 1)
         finished += prog[j] >= L
     return prog, wt, [filled, offered, len(took), finished]
+
+
+def fit_one_limited(dur, mem, safe, p, W, C, tau_min=0, tau_max=None, power=None, power_cap=None,
+                    deadline=None, now=0) -> int:
+    """fit_one under the admission limits of Sec. 4.3 (duration bounds) and Sec. 4.4 (power cap,
+    deadline): every test written out for every boundary, longest first."""
+    L = len(dur)
+    for b in range(L, p, -1):
+        if not ((b == L) or bool(safe[b - 1])):
+            continue
+        total = sum(dur[p:b])
+        ok = total <= W and max(mem[p:b]) <= C
+        if tau_max is not None:
+            ok = ok and total <= tau_max
+        if b != L:
+            ok = ok and total >= tau_min
+        if power is not None:
+            ok = ok and max(power[p:b]) <= power_cap
+        if deadline is not None:
+            ok = ok and now + total <= deadline
+        if ok:
+            return b
+    return -1
+
+
+def cover_one(peak: int, cap_set: Sequence[int]):
+    """Smallest capacity of the set that covers the peak (Sec. 3.9), or None."""
+    fits = [int(c) for c in cap_set if int(c) >= peak]
+    return min(fits) if fits else None

@@ -106,25 +106,54 @@ int sjo_prepare(int32_t n_jobs, const int64_t *seg_off, const int32_t *dur,
 }
 
 /* ------------------------------------------------------------------------
+ * Optional admission limits on top of the gap's own window and capacity:
+ *   - a power trace with a cap in force for the tick: the subjob's peak power
+ *     must stay <= power_cap (Sec. 4.4, energy-aware admission: the same
+ *     max-over-the-window test on a second channel);
+ *   - a deadline per job: the subjob has to complete by it, i.e. its duration
+ *     is <= deadline[j] - now, the gaps of a tick starting at `now`
+ *     (Sec. 4.4, deadline-aware admission);
+ *   - framework-level bounds on a subjob's duration (Sec. 4.3, granularity):
+ *     at most tau_max, and at least tau_min unless the subjob runs to the
+ *     job's end (a job's tail must be allowed to finish).
+ * A NULL limits pointer, a NULL power trace or a NULL deadline array switches
+ * the corresponding tests off.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t tau_min;   /* >= 0 */
+    int32_t tau_max;   /* >= 0 */
+    int32_t power_cap;
+    int32_t now;
+} sjo_limits;
+
+/* ------------------------------------------------------------------------
  * Fit for one (gap, job) pair: walk boundaries forward from the progress
- * point while the subjob still fits, remembering the last safe boundary.
- * Both the running duration and the running peak never decrease, so the
- * first violation ends the walk.  Returns the cut (or -1) and, for an
- * interested pair, the subjob's duration and peak.
+ * point while the subjob still fits, remembering the last safe boundary that
+ * may be offered.  The running duration and the running peaks never decrease,
+ * so the first violation of an upper bound ends the walk.  Returns the cut (or
+ * -1) and, for an interested pair, the subjob's duration and memory peak.
  * ---------------------------------------------------------------------- */
 static int32_t fit_pair(int64_t L, int64_t p, const int32_t *dur, const int32_t *mem,
-                        const uint8_t *safe, int64_t W, int64_t C,
+                        const uint8_t *safe, int64_t W, int64_t C, const sjo_limits *lim,
+                        const int32_t *power, const int32_t *deadline_j,
                         int64_t *out_dur, int64_t *out_peak)
 {
-    int64_t sum = 0, peak = 0;
+    int64_t sum = 0, peak = 0, ppeak = 0;
     int32_t cut = -1;
     int64_t cut_dur = 0, cut_peak = 0;
     for (int64_t b = p + 1; b <= L; ++b) {
         int64_t k = b - 1;
         sum += dur[k];
         if (b == p + 1 || mem[k] > peak) peak = mem[k];
+        if (power && (b == p + 1 || power[k] > ppeak)) ppeak = power[k];
         if (sum > W || peak > C) break;
+        if (lim) {
+            if (sum > lim->tau_max) break;
+            if (power && ppeak > lim->power_cap) break;
+            if (deadline_j && sum > (int64_t)*deadline_j - lim->now) break;
+        }
         if (b == L || safe[k]) {
+            if (lim && b != L && sum < lim->tau_min) continue;
             cut = (int32_t)b;
             cut_dur = sum;
             cut_peak = peak;
@@ -137,11 +166,13 @@ static int32_t fit_pair(int64_t L, int64_t p, const int32_t *dur, const int32_t 
 
 /* cut[g*J + j] for every pair; interest_bits (may be NULL) holds bit j%32 of
  * word g*ceil(J/32) + j/32 set iff the job is interested in the gap. */
-int sjo_fit(int32_t n_gaps, int32_t n_jobs, const int64_t *seg_off, const int32_t *dur,
-            const int32_t *mem, const uint8_t *safe, const int32_t *progress,
-            const int32_t *W, const int32_t *C, int32_t *cut, uint32_t *interest_bits)
+int sjo_fit_limited(int32_t n_gaps, int32_t n_jobs, const int64_t *seg_off, const int32_t *dur,
+                    const int32_t *mem, const uint8_t *safe, const int32_t *progress,
+                    const int32_t *W, const int32_t *C, const sjo_limits *lim, const int32_t *power,
+                    const int32_t *deadline, int32_t *cut, uint32_t *interest_bits)
 {
     if (n_gaps < 0 || n_jobs < 0) return SJO_ERR_ARG;
+    if (lim && (lim->tau_min < 0 || lim->tau_max < 0)) return SJO_ERR_ARG;
     int64_t words = ((int64_t)n_jobs + 31) / 32;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int32_t g = 0; g < n_gaps; ++g) {
@@ -152,7 +183,8 @@ int sjo_fit(int32_t n_gaps, int32_t n_jobs, const int64_t *seg_off, const int32_
             int64_t base = seg_off[j];
             int64_t L = seg_off[j + 1] - base;
             int32_t c = fit_pair(L, progress[j], dur + base, mem + base, safe + base,
-                                 W[g], C[g], NULL, NULL);
+                                 W[g], C[g], lim, power ? power + base : NULL,
+                                 deadline ? deadline + j : NULL, NULL, NULL);
             row[j] = c;
             if (bits && c >= 0) bits[j >> 5] |= (uint32_t)1 << (j & 31);
         }
@@ -160,13 +192,23 @@ int sjo_fit(int32_t n_gaps, int32_t n_jobs, const int64_t *seg_off, const int32_
     return SJO_OK;
 }
 
+int sjo_fit(int32_t n_gaps, int32_t n_jobs, const int64_t *seg_off, const int32_t *dur,
+            const int32_t *mem, const uint8_t *safe, const int32_t *progress,
+            const int32_t *W, const int32_t *C, int32_t *cut, uint32_t *interest_bits)
+{
+    return sjo_fit_limited(n_gaps, n_jobs, seg_off, dur, mem, safe, progress, W, C, NULL, NULL, NULL,
+                           cut, interest_bits);
+}
+
 /* The same evaluation on a list of sampled pairs (gap_idx[i], job_idx[i]). */
-int sjo_fit_pairs(int64_t n_pairs, const int32_t *gap_idx, const int32_t *job_idx,
-                  const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
-                  const uint8_t *safe, const int32_t *progress, const int32_t *W,
-                  const int32_t *C, int32_t *cut, int64_t *sub_dur, int64_t *sub_peak)
+int sjo_fit_pairs_limited(int64_t n_pairs, const int32_t *gap_idx, const int32_t *job_idx,
+                          const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                          const uint8_t *safe, const int32_t *progress, const int32_t *W,
+                          const int32_t *C, const sjo_limits *lim, const int32_t *power,
+                          const int32_t *deadline, int32_t *cut, int64_t *sub_dur, int64_t *sub_peak)
 {
     if (n_pairs < 0) return SJO_ERR_ARG;
+    if (lim && (lim->tau_min < 0 || lim->tau_max < 0)) return SJO_ERR_ARG;
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n_pairs; ++i) {
         int32_t g = gap_idx[i], j = job_idx[i];
@@ -174,9 +216,50 @@ int sjo_fit_pairs(int64_t n_pairs, const int32_t *gap_idx, const int32_t *job_id
         int64_t L = seg_off[j + 1] - base;
         int64_t d = 0, pk = 0;
         cut[i] = fit_pair(L, progress[j], dur + base, mem + base, safe + base,
-                          W[g], C[g], &d, &pk);
+                          W[g], C[g], lim, power ? power + base : NULL,
+                          deadline ? deadline + j : NULL, &d, &pk);
         if (sub_dur) sub_dur[i] = d;
         if (sub_peak) sub_peak[i] = pk;
+    }
+    return SJO_OK;
+}
+
+int sjo_fit_pairs(int64_t n_pairs, const int32_t *gap_idx, const int32_t *job_idx,
+                  const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                  const uint8_t *safe, const int32_t *progress, const int32_t *W,
+                  const int32_t *C, int32_t *cut, int64_t *sub_dur, int64_t *sub_peak)
+{
+    return sjo_fit_pairs_limited(n_pairs, gap_idx, job_idx, seg_off, dur, mem, safe, progress, W, C,
+                                 NULL, NULL, NULL, cut, sub_dur, sub_peak);
+}
+
+/* ------------------------------------------------------------------------
+ * Slack-minimising capacity mapping (Sec. 3.9): for each granted gap, the
+ * smallest capacity of the set (ascending, n_caps entries) that covers the
+ * granted subjob's memory peak, and the slack left against the gap's own
+ * capacity.  cover = -1 and slack = 0 for an ungranted gap; cover = -1 and
+ * slack = 0 too when no capacity of the set covers the peak.
+ * ---------------------------------------------------------------------- */
+int sjo_cover(int32_t n_gaps, const int64_t *seg_off, const int64_t *pre_peak, const int32_t *C,
+              const int32_t *grant_job, const int32_t *grant_cut, int32_t n_caps,
+              const int32_t *cap_set, int32_t *cover, int32_t *slack)
+{
+    if (n_gaps < 0 || n_caps < 0) return SJO_ERR_ARG;
+    for (int32_t i = 1; i < n_caps; ++i)
+        if (cap_set[i] < cap_set[i - 1]) return SJO_ERR_ARG;
+    for (int32_t g = 0; g < n_gaps; ++g) {
+        cover[g] = -1;
+        slack[g] = 0;
+        int32_t j = grant_job[g];
+        if (j < 0) continue;
+        int64_t peak = pre_peak[seg_off[j] + grant_cut[g] - 1];
+        for (int32_t i = 0; i < n_caps; ++i) {
+            if (cap_set[i] >= peak) {
+                cover[g] = cap_set[i];
+                slack[g] = C[g] - cap_set[i];
+                break;
+            }
+        }
     }
     return SJO_OK;
 }

@@ -95,6 +95,65 @@ def prepare(seg_off, dur, mem, safe, progress, fill: int = -7):
     return pre_dur, pre_peak, prev_safe
 
 
+class Limits(ctypes.Structure):
+    """Mirror of sjo_limits (admission limits of Sec. 4.3 / 4.4)."""
+    _fields_ = [("tau_min", ctypes.c_int32), ("tau_max", ctypes.c_int32),
+                ("power_cap", ctypes.c_int32), ("now", ctypes.c_int32)]
+
+    @classmethod
+    def make(cls, tau_min: int = 0, tau_max: int = 2**31 - 1, power_cap: int = 2**31 - 1, now: int = 0):
+        return cls(tau_min, tau_max, power_cap, now)
+
+
+def fit_limited(seg_off, dur, mem, safe, progress, W, C, limits, power=None, deadline=None,
+                want_bits: bool = False):
+    """fit() under admission limits: returns (cut [G, J] int32, bits or None)."""
+    G, J = len(W), len(seg_off) - 1
+    cut = np.empty((G, J), dtype=np.int32)
+    bits = np.zeros((G, (J + 31) // 32), dtype=np.uint32) if want_bits else None
+    rc = _load().sjo_fit_limited(ctypes.c_int32(G), ctypes.c_int32(J), _p(seg_off, np.int64),
+                                 _p(dur, np.int32), _p(mem, np.int32), _p(safe, np.uint8),
+                                 _p(progress, np.int32), _p(W, np.int32), _p(C, np.int32),
+                                 ctypes.byref(limits) if limits is not None else None,
+                                 _p(power, np.int32), _p(deadline, np.int32), _p(cut, np.int32),
+                                 _p(bits, np.uint32))
+    _check(rc, "sjo_fit_limited")
+    return cut, bits
+
+
+def fit_pairs_limited(gap_idx, job_idx, seg_off, dur, mem, safe, progress, W, C, limits, power=None,
+                      deadline=None):
+    """fit_pairs() under admission limits; returns (cut int32, sub_dur int64, sub_peak int64)."""
+    n = len(gap_idx)
+    cut = np.empty(n, dtype=np.int32)
+    sd = np.empty(n, dtype=np.int64)
+    sp = np.empty(n, dtype=np.int64)
+    rc = _load().sjo_fit_pairs_limited(ctypes.c_int64(n), _p(gap_idx, np.int32), _p(job_idx, np.int32),
+                                       _p(seg_off, np.int64), _p(dur, np.int32), _p(mem, np.int32),
+                                       _p(safe, np.uint8), _p(progress, np.int32), _p(W, np.int32),
+                                       _p(C, np.int32),
+                                       ctypes.byref(limits) if limits is not None else None,
+                                       _p(power, np.int32), _p(deadline, np.int32), _p(cut, np.int32),
+                                       _p(sd, np.int64), _p(sp, np.int64))
+    _check(rc, "sjo_fit_pairs_limited")
+    return cut, sd, sp
+
+
+def cover(seg_off, pre_peak, C, grant_job, grant_cut, cap_set):
+    """Smallest capacity of cap_set (ascending) covering each grant's peak, and the slack
+    against the gap's own capacity: (cover int32 [G], slack int32 [G])."""
+    G = len(C)
+    cap_set = np.ascontiguousarray(cap_set, dtype=np.int32)
+    cov = np.empty(G, dtype=np.int32)
+    slack = np.empty(G, dtype=np.int32)
+    rc = _load().sjo_cover(ctypes.c_int32(G), _p(seg_off, np.int64), _p(pre_peak, np.int64),
+                           _p(C, np.int32), _p(grant_job, np.int32), _p(grant_cut, np.int32),
+                           ctypes.c_int32(len(cap_set)), _p(cap_set, np.int32), _p(cov, np.int32),
+                           _p(slack, np.int32))
+    _check(rc, "sjo_cover")
+    return cov, slack
+
+
 def fit(seg_off, dur, mem, safe, progress, W, C, want_bits: bool = True):
     """Returns (cut int32 [G, J], interest_bits uint32 [G, ceil(J/32)] or None)."""
     J = len(seg_off) - 1
