@@ -6,4 +6,4 @@ arithmetic (no prefix sums over profiles, no fit test, no scores), so both the
 CPU oracle's tests and the GPU path can be fed from it without sharing any
 computation.
 """
-from .workloads import CONFIGS, Workload, make_workload, make_gaps, config_names  # noqa: F401
+from .workloads import CONFIGS, Workload, make_workload, make_gaps, make_channels, config_names  # noqa: F401

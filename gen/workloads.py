@@ -233,3 +233,20 @@ def make_gaps(name: str, seed: int, tick: int, n_gaps: Optional[int] = None):
     c_set = np.asarray(cfg.c_set, dtype=np.int32)
     C = c_set[rng.integers(0, len(c_set), size=G)]
     return np.ascontiguousarray(W), np.ascontiguousarray(C)
+
+
+def make_channels(wl: Workload, seed: int):
+    """A second profile channel and per-job deadlines for a workload (inputs only):
+    power [n_segments] int32 in watts, a floor plus a share that follows the segment's memory
+    with multiplicative noise (100..~1100 W); deadline [n_jobs] int32, log-uniform between
+    1 % and 400 % of the config's widest window, measured from time 0, so that for some jobs
+    the deadline is tighter than most windows and for others it never binds."""
+    cfg = CONFIGS[wl.name]
+    rng = np.random.Generator(np.random.PCG64([int(seed), 2000003]))
+    S, J = wl.n_segments, wl.n_jobs
+    share = wl.mem.astype(np.float64) / 147456.0
+    power = 100.0 + 900.0 * np.clip(share * rng.uniform(0.5, 1.5, size=S), 0.0, 1.1)
+    w_hi = float(cfg.w_range[1])
+    deadline = np.floor(0.01 * w_hi * (400.0 ** rng.random(J))).astype(np.int64)
+    return (np.ascontiguousarray(power.astype(np.int32)),
+            np.ascontiguousarray(np.clip(deadline, 0, 2**31 - 1).astype(np.int32)))

@@ -16,6 +16,8 @@
  *   sja_resolve           grants, with conflicts settled in rounds so that a job
  *                         holds at most one gap (Sec. 3.1 / 3.5: fragments of a
  *                         job are sequential from one progress point)
+ *   sja_cover             smallest capacity of a set that covers each grant
+ *                         (Sec. 3.9)
  *   sja_advance           end of the tick: granted jobs move to their cut and
  *                         only their tables are rebuilt (Sec. 3.1 / 3.5)
  *
@@ -122,6 +124,42 @@ int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes);
 /* Static string for a status code; last error text of a context (host). */
 const char *sja_status_string(int status);
 const char *sja_last_error(const sja_ctx *ctx);
+
+/*
+ * Admission limits on top of each gap's own window and capacity.  All are off
+ * in a new context.
+ *   - power trace with a cap (Sec. 4.4, energy-aware admission: the subjob's
+ *     peak power over its lifetime stays within the cap; the same test as the
+ *     memory fit, on a second channel).  The cap is the one in force for the
+ *     tick, shared by its gaps.
+ *   - deadline per job (Sec. 4.4, deadline-aware admission: only subjobs that
+ *     complete by the deadline; the gaps of a tick start at `now`, so the
+ *     subjob's duration must be <= deadline[j] - now).
+ *   - duration bounds (Sec. 4.3, granularity: minimum and maximum subjob
+ *     duration enforced by the framework): at most tau_max, and at least
+ *     tau_min unless the subjob runs to the job's end.
+ * With limits, cut[g][j] is the largest safe boundary whose subjob passes the
+ * gap's tests and all of these.
+ */
+typedef struct {
+    int32_t tau_min;   /* >= 0; 0 = no lower bound                         */
+    int32_t tau_max;   /* >= 0; INT32_MAX = no upper bound                 */
+    int32_t power_cap; /* used only with a power trace                     */
+    int32_t now;       /* used only with deadlines                         */
+} sja_limits;
+
+/*
+ * Sets (limits != NULL) or clears (limits == NULL) the admission limits.
+ * `limits` is a host pointer and is copied.  power [n_segments] int32 (power of
+ * each profile segment) and deadline [n_jobs] int32 are device arrays sized for
+ * the NEXT sja_prepare_profiles, or NULL to leave that test out; they must stay
+ * alive and unchanged while that prepare's tables are in use.  The limits take
+ * effect at the next sja_prepare_profiles; sja_advance keeps applying the ones
+ * its prepare used, `now` included (to move `now`, set the limits and prepare
+ * again).  SJA_ERR_SIZE for a negative tau_min or tau_max.  Touches no device.
+ */
+int sja_set_limits(sja_ctx *ctx, const sja_limits *limits, const int32_t *power,
+                   const int32_t *deadline);
 
 /*
  * Per-job segmented scans from the progress point (Sec. 3.9: segmentation is
@@ -238,6 +276,25 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
 int sja_advance(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
                 const int32_t *grant_job, const int32_t *grant_cut, const int32_t *job_gap,
                 int32_t *progress, int32_t *wait, int32_t wait_step, int64_t *metrics);
+
+/*
+ * Slack-minimising capacity mapping for the grants (Sec. 3.9: map the granted
+ * window to the smallest slice capacity of the set that covers the predicted
+ * demand in it).
+ *   C, grant_job, grant_cut [n_gaps]  the gaps and the grants of sja_resolve
+ *   cap_set [n_caps] int32            the capacity set, ascending (device)
+ *   cover [n_gaps] int32, out         smallest cap_set entry >= the memory peak
+ *                                     of the granted subjob; -1 if the gap is
+ *                                     ungranted or no entry covers the peak
+ *   slack [n_gaps] int32, out         C[g] - cover[g]; 0 where cover is -1
+ * Reads the running peaks of the last sja_prepare_profiles: call it before
+ * sja_advance moves the jobs.  An entry whose job id or cut is out of range
+ * counts as ungranted.  A cap_set that does not ascend gives unspecified (but
+ * in-range) answers.  Only enqueues work.
+ */
+int sja_cover(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *C, const int32_t *grant_job,
+              const int32_t *grant_cut, int32_t n_caps, const int32_t *cap_set, int32_t *cover,
+              int32_t *slack);
 
 /*
  * Measurement aid for benchmarks (callers that report the pair-evaluation

@@ -4,7 +4,7 @@
 methods carry the same names as the C entry points declared in include/sja.h.
 """
 from .binding import (  # noqa: F401
-    Engine, Params, SjaError, load_library,
+    Engine, Params, Limits, SjaError, load_library,
     POLICY_EFFICIENCY, POLICY_FAIRNESS, POLICY_SLA, POLICY_MIXED,
 )
 from .tick import DeviceTick  # noqa: F401

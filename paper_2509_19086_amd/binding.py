@@ -38,6 +38,17 @@ class Params(ctypes.Structure):
                    max_rounds)
 
 
+class Limits(ctypes.Structure):
+    """Mirror of sja_limits."""
+    _fields_ = [("tau_min", ctypes.c_int32), ("tau_max", ctypes.c_int32),
+                ("power_cap", ctypes.c_int32), ("now", ctypes.c_int32)]
+
+    @classmethod
+    def make(cls, tau_min: int = 0, tau_max: int = 2**31 - 1, power_cap: int = 2**31 - 1,
+             now: int = 0) -> "Limits":
+        return cls(tau_min, tau_max, power_cap, now)
+
+
 def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     """Loads the built library (builds it only if no library is there at all)."""
     global _lib
@@ -72,6 +83,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_fit_select.argtypes = [vp, vp, i32, vp, vp, ctypes.POINTER(Params)] + [vp] * 7
     lib.sja_fit_select.restype = ctypes.c_int
     lib.sja_resolve.restype = ctypes.c_int
+    lib.sja_set_limits.argtypes = [vp, ctypes.POINTER(Limits), vp, vp]
+    lib.sja_set_limits.restype = ctypes.c_int
+    lib.sja_cover.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp, vp]
+    lib.sja_cover.restype = ctypes.c_int
     lib.sja_advance.argtypes = [vp, vp, i32] + [vp] * 7 + [i32, vp]
     lib.sja_advance.restype = ctypes.c_int
     lib.sja_enable_timing.argtypes = [vp, ctypes.c_int]
@@ -206,6 +221,21 @@ class Engine:
                 _ptr(grant_score, torch.int64, G), _ptr(job_gap, torch.int32, J),
                 _ptr(rounds_used_and_stable, torch.int32, 2))
         rc = self.lib.sja_resolve(self.h, _stream(), ctypes.byref(params), *args)
+        self._check(rc, self.h)
+
+    def sja_set_limits(self, limits, power=None, deadline=None):
+        """limits: a Limits or None (clear).  power / deadline: device int32 tensors or None;
+        the engine keeps them alive until the limits are replaced."""
+        self._limit_arrays = (power, deadline)
+        rc = self.lib.sja_set_limits(self.h, ctypes.byref(limits) if limits is not None else None,
+                                     _ptr(power, torch.int32), _ptr(deadline, torch.int32))
+        self._check(rc, self.h)
+
+    def sja_cover(self, C, grant_job, grant_cut, cap_set, cover, slack):
+        G, K = C.numel(), cap_set.numel()
+        args = (_ptr(C, torch.int32, G), _ptr(grant_job, torch.int32, G), _ptr(grant_cut, torch.int32, G))
+        rc = self.lib.sja_cover(self.h, _stream(), G, *args, K, _ptr(cap_set, torch.int32, K),
+                                _ptr(cover, torch.int32, G), _ptr(slack, torch.int32, G))
         self._check(rc, self.h)
 
     def sja_advance(self, W, C, grant_job, grant_cut, job_gap, progress, wait, wait_step, metrics):

@@ -356,6 +356,18 @@ int enqueue_gap_plan(sja_ctx *ctx, hipStream_t st, const Layout &L, int32_t n_ga
     return SJA_OK;
 }
 
+JobLimits job_limits(const sja_limits &l, const int32_t *power, const int32_t *deadline)
+{
+    JobLimits out;
+    out.tau_min = l.tau_min;
+    out.tau_max = l.tau_max;
+    out.power_cap = l.power_cap;
+    out.now = l.now;
+    out.power = power;
+    out.deadline = deadline;
+    return out;
+}
+
 }  // namespace
 
 extern "C" {
@@ -420,47 +432,6 @@ int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes)
     return SJA_OK;
 }
 
-int sja_advance(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
-                const int32_t *grant_job, const int32_t *grant_cut, const int32_t *job_gap, int32_t *progress,
-                int32_t *wait, int32_t wait_step, int64_t *metrics)
-{
-    if (!ctx) return SJA_ERR_NULL;
-    if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_advance before sja_prepare_profiles");
-    if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
-    if (wait_step < 0) return fail(ctx, SJA_ERR_SIZE, "wait_step");
-    if (n_gaps > 0 && (!W || !C || !grant_job || !grant_cut)) return fail(ctx, SJA_ERR_NULL, "gap arrays");
-    const int J = ctx->n_jobs;
-    if (J > 0 && (!job_gap || !progress)) return fail(ctx, SJA_ERR_NULL, "job_gap / progress");
-    if (!metrics) return fail(ctx, SJA_ERR_NULL, "metrics");
-    const Layout L = make_layout(0, J, ctx->n_segments);
-    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small");
-
-    DeviceGuard guard(ctx->device);
-    SJA_HIP(guard.err, "hipSetDevice");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    // the profiles of the granted jobs change: whatever the last fit left no longer describes them
-    ctx->fitted = false;
-    ctx->planned = false;
-    unsigned long long *m = reinterpret_cast<unsigned long long *>(metrics);
-    hipLaunchKernelGGL(k_fill_i64, dim3(1), dim3(64), 0, st, 4, int64_t(0), metrics);
-    SJA_HIP(hipGetLastError(), "k_fill_i64 launch");
-    if (n_gaps > 0) {
-        hipLaunchKernelGGL(k_advance_gaps, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, J, ctx->seg_off,
-                           ctx->pre_dur, ctx->pre_peak, W, C, grant_job, grant_cut, job_gap, progress, m);
-        SJA_HIP(hipGetLastError(), "k_advance_gaps launch");
-    }
-    if (J > 0) {
-        const int jobs_per_block = 256 / kWave;
-        hipLaunchKernelGGL(k_advance_jobs, dim3((J + jobs_per_block - 1) / jobs_per_block), dim3(256), 0, st,
-                           n_gaps, J, ctx->seg_off, ctx->dur, ctx->mem, ctx->safe, grant_job, grant_cut, job_gap,
-                           progress, wait, wait_step, ctx->pre_dur, ctx->pre_peak, ctx->prev_safe,
-                           ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),
-                           ws_ptr<int32_t>(ctx, L.n_atoms), ws_ptr<int2>(ctx, L.first_dp), m);
-        SJA_HIP(hipGetLastError(), "k_advance_jobs launch");
-    }
-    return SJA_OK;
-}
-
 int sja_enable_timing(sja_ctx *ctx, int on)
 {
     if (!ctx) return SJA_ERR_NULL;
@@ -488,6 +459,23 @@ int sja_last_fit_kernel_ms(sja_ctx *ctx, float *ms_host)
     return SJA_OK;
 }
 
+int sja_set_limits(sja_ctx *ctx, const sja_limits *limits, const int32_t *power, const int32_t *deadline)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!limits) {
+        ctx->limits_on = false;
+        ctx->lim_power = nullptr;
+        ctx->lim_deadline = nullptr;
+        return SJA_OK;
+    }
+    if (limits->tau_min < 0 || limits->tau_max < 0) return fail(ctx, SJA_ERR_SIZE, "tau_min / tau_max");
+    ctx->limits = *limits;
+    ctx->lim_power = power;
+    ctx->lim_deadline = deadline;
+    ctx->limits_on = true;
+    return SJA_OK;
+}
+
 int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
                          const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
                          const uint8_t *safe, const int32_t *progress, int32_t *pre_dur,
@@ -510,12 +498,25 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (n_jobs > 0) {
         const int jobs_per_block = 256 / kWave;
-        hipLaunchKernelGGL(k_prepare, dim3((n_jobs + jobs_per_block - 1) / jobs_per_block), dim3(256), 0, st,
-                           n_jobs, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe,
-                           ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),
-                           ws_ptr<int32_t>(ctx, L.n_atoms), ws_ptr<int2>(ctx, L.first_dp));
+        const dim3 grid((n_jobs + jobs_per_block - 1) / jobs_per_block), block(256);
+        if (ctx->limits_on) {
+            const JobLimits lim = job_limits(ctx->limits, ctx->lim_power, ctx->lim_deadline);
+            hipLaunchKernelGGL(k_prepare<true>, grid, block, 0, st, lim, n_jobs, seg_off, dur, mem, safe, progress,
+                               pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
+                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int2>(ctx, L.first_dp));
+        } else {
+            hipLaunchKernelGGL(k_prepare<false>, grid, block, 0, st, JobLimits{}, n_jobs, seg_off, dur, mem, safe,
+                               progress, pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
+                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int2>(ctx, L.first_dp));
+        }
         SJA_HIP(hipGetLastError(), "k_prepare launch");
     }
+    ctx->limits_used = ctx->limits_on;
+    ctx->limits_applied = ctx->limits;
+    ctx->used_power = ctx->lim_power;
+    ctx->used_deadline = ctx->lim_deadline;
     ctx->n_jobs = n_jobs;
     ctx->n_segments = n_segments;
     ctx->seg_off = seg_off;
@@ -750,6 +751,77 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
     SJA_HIP(hipMemcpyAsync(rounds_used_and_stable, result, sizeof(result), hipMemcpyHostToDevice, st),
             "rounds writeback");
     SJA_HIP(hipStreamSynchronize(st), "final synchronise");
+    return SJA_OK;
+}
+
+int sja_advance(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
+                const int32_t *grant_job, const int32_t *grant_cut, const int32_t *job_gap, int32_t *progress,
+                int32_t *wait, int32_t wait_step, int64_t *metrics)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_advance before sja_prepare_profiles");
+    if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
+    if (wait_step < 0) return fail(ctx, SJA_ERR_SIZE, "wait_step");
+    if (n_gaps > 0 && (!W || !C || !grant_job || !grant_cut)) return fail(ctx, SJA_ERR_NULL, "gap arrays");
+    const int J = ctx->n_jobs;
+    if (J > 0 && (!job_gap || !progress)) return fail(ctx, SJA_ERR_NULL, "job_gap / progress");
+    if (!metrics) return fail(ctx, SJA_ERR_NULL, "metrics");
+    const Layout L = make_layout(0, J, ctx->n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small");
+
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the profiles of the granted jobs change: whatever the last fit left no longer describes them
+    ctx->fitted = false;
+    ctx->planned = false;
+    unsigned long long *m = reinterpret_cast<unsigned long long *>(metrics);
+    hipLaunchKernelGGL(k_fill_i64, dim3(1), dim3(64), 0, st, 4, int64_t(0), metrics);
+    SJA_HIP(hipGetLastError(), "k_fill_i64 launch");
+    if (n_gaps > 0) {
+        hipLaunchKernelGGL(k_advance_gaps, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, J, ctx->seg_off,
+                           ctx->pre_dur, ctx->pre_peak, W, C, grant_job, grant_cut, job_gap, progress, m);
+        SJA_HIP(hipGetLastError(), "k_advance_gaps launch");
+    }
+    if (J > 0) {
+        const int jobs_per_block = 256 / kWave;
+        const dim3 grid((J + jobs_per_block - 1) / jobs_per_block), block(256);
+        if (ctx->limits_used) {
+            const JobLimits lim = job_limits(ctx->limits_applied, ctx->used_power, ctx->used_deadline);
+            hipLaunchKernelGGL(k_advance_jobs<true>, grid, block, 0, st, lim, n_gaps, J, ctx->seg_off, ctx->dur,
+                               ctx->mem, ctx->safe, grant_job, grant_cut, job_gap, progress, wait, wait_step,
+                               ctx->pre_dur, ctx->pre_peak, ctx->prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
+                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int2>(ctx, L.first_dp), m);
+        } else {
+            hipLaunchKernelGGL(k_advance_jobs<false>, grid, block, 0, st, JobLimits{}, n_gaps, J, ctx->seg_off,
+                               ctx->dur, ctx->mem, ctx->safe, grant_job, grant_cut, job_gap, progress, wait,
+                               wait_step, ctx->pre_dur, ctx->pre_peak, ctx->prev_safe,
+                               ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),
+                               ws_ptr<int32_t>(ctx, L.n_atoms), ws_ptr<int2>(ctx, L.first_dp), m);
+        }
+        SJA_HIP(hipGetLastError(), "k_advance_jobs launch");
+    }
+    return SJA_OK;
+}
+
+int sja_cover(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *C, const int32_t *grant_job,
+              const int32_t *grant_cut, int32_t n_caps, const int32_t *cap_set, int32_t *cover, int32_t *slack)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!ctx->prepared) return fail(ctx, SJA_ERR_STATE, "sja_cover before sja_prepare_profiles");
+    if (n_gaps < 0 || n_gaps > SJA_MAX_GAPS) return fail(ctx, SJA_ERR_SIZE, "n_gaps");
+    if (n_caps < 0) return fail(ctx, SJA_ERR_SIZE, "n_caps");
+    if (n_gaps > 0 && (!C || !grant_job || !grant_cut || !cover || !slack)) return fail(ctx, SJA_ERR_NULL, "gap arrays");
+    if (n_caps > 0 && !cap_set) return fail(ctx, SJA_ERR_NULL, "cap_set");
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_gaps > 0) {
+        hipLaunchKernelGGL(k_cover, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, ctx->n_jobs, ctx->seg_off,
+                           ctx->pre_peak, C, grant_job, grant_cut, n_caps, cap_set, cover, slack);
+        SJA_HIP(hipGetLastError(), "k_cover launch");
+    }
     return SJA_OK;
 }
 

@@ -198,6 +198,12 @@ struct sja_ctx {
     int32_t *pre_peak;
     int32_t *prev_safe;
 
+    // admission limits: as set by sja_set_limits, and as the last prepare applied them
+    bool limits_on, limits_used;
+    sja_limits limits, limits_applied;
+    const int32_t *lim_power, *lim_deadline;
+    const int32_t *used_power, *used_deadline;
+
     // optional timing of the pair-evaluation kernel
     bool timing;
     bool timed;

@@ -41,8 +41,33 @@ __device__ __forceinline__ void wave_scan_add_max_max(int &s, int &m, int &l, in
 // cut after the progress point) into the workspace at the job's segment base,
 // as (duration, peak) and (duration, boundary) pairs.
 // --------------------------------------------------------------------------
+// Admission limits applied while the atoms are compacted (Sec. 4.3: bounds on
+// a subjob's duration; Sec. 4.4: peak power under a cap, completion by a
+// deadline).  Each test is monotone along a job's boundaries, or can only turn
+// the answer of a pair into a decline, so an atom that fails one is of no use
+// to any gap and is left out; the kernels downstream never see the limits.
+struct JobLimits {
+    int tau_min;                 // shortest subjob that may be offered, the job's end excepted
+    int tau_max;                 // longest subjob that may be offered
+    int power_cap;               // bound on the running power peak (with a power trace)
+    int now;                     // deadline[j] - now bounds the duration (with deadlines)
+    const int32_t *power;        // per segment, or null
+    const int32_t *deadline;     // per job, or null
+};
+
+__device__ __forceinline__ void wave_scan_max(int &q, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int q2 = __shfl_up(q, d, kWave);
+        if (lane >= d) q = max(q, q2);
+    }
+}
+
 // One wave walks job j's segments from boundary p to the job's end.
+template <bool LIMITED>
 __device__ __forceinline__ void prepare_job(
+    const JobLimits &lim,
     int j, int lane, int64_t base, int L, int p, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
@@ -51,6 +76,14 @@ __device__ __forceinline__ void prepare_job(
 {
     int carry_sum = 0, carry_peak = INT32_MIN, carry_last = -1, count = 0;
     int first_d = INT32_MAX, first_p = INT32_MAX;     // the first atom, if there is one
+    int d_hi = INT32_MAX, carry_pow = INT32_MIN;
+    if (LIMITED) {
+        d_hi = lim.tau_max;
+        if (lim.deadline) {
+            const int64_t room = int64_t(lim.deadline[j]) - lim.now;
+            if (room < d_hi) d_hi = room < 0 ? -1 : int(room);
+        }
+    }
     for (int k0 = p; k0 < L; k0 += kWave) {
         const int k = k0 + lane;
         const bool valid = k < L;
@@ -70,6 +103,17 @@ __device__ __forceinline__ void prepare_job(
             pre_dur[base + k] = s;
             pre_peak[base + k] = m;
             prev_safe[base + k] = l;
+        }
+        if (LIMITED) {
+            bool keep = flag && s <= d_hi && (s >= lim.tau_min || k + 1 == L);
+            if (lim.power) {
+                int q = valid ? lim.power[base + k] : INT32_MIN;
+                wave_scan_max(q, lane);
+                q = max(q, carry_pow);
+                keep = keep && q <= lim.power_cap;
+                carry_pow = __shfl(q, kWave - 1, kWave);
+            }
+            flag = keep;
         }
         const unsigned long long mask = __ballot(flag);
         if (count == 0 && mask) {
@@ -93,8 +137,9 @@ __device__ __forceinline__ void prepare_job(
     }
 }
 
+template <bool LIMITED>
 __global__ __launch_bounds__(256) void k_prepare(
-    int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    JobLimits lim, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
@@ -108,8 +153,8 @@ __global__ __launch_bounds__(256) void k_prepare(
     const int L = int(seg_off[j + 1] - base);
     int p = progress[j];
     p = p < 0 ? 0 : (p > L ? L : p);
-    prepare_job(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db, n_atoms,
-                first_dp);
+    prepare_job<LIMITED>(lim, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db,
+                         n_atoms, first_dp);
 }
 
 // --------------------------------------------------------------------------
@@ -183,11 +228,44 @@ __global__ __launch_bounds__(256) void k_advance_gaps(
     }
 }
 
+// Slack-minimising capacity mapping (Sec. 3.9): per granted gap the smallest
+// capacity of an ascending set that covers the granted subjob's memory peak.
+__global__ __launch_bounds__(256) void k_cover(
+    int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ pre_peak,
+    const int32_t *__restrict__ C, const int32_t *__restrict__ grant_job,
+    const int32_t *__restrict__ grant_cut, int n_caps, const int32_t *__restrict__ cap_set,
+    int32_t *__restrict__ cover, int32_t *__restrict__ slack)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_gaps) return;
+    int cov = -1, sl = 0;
+    const int j = grant_job[g];
+    if (j >= 0 && j < n_jobs) {
+        const int64_t base = seg_off[j];
+        const int cut = grant_cut[g];
+        if (cut >= 1 && cut <= int(seg_off[j + 1] - base)) {
+            const int peak = pre_peak[base + cut - 1];
+            int lo = 0, hi = n_caps;                  // first capacity >= peak
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (cap_set[mid] < peak) lo = mid + 1; else hi = mid;
+            }
+            if (lo < n_caps) {
+                cov = cap_set[lo];
+                sl = C[g] - cov;
+            }
+        }
+    }
+    cover[g] = cov;
+    slack[g] = sl;
+}
+
 // One wave per job: a granted job moves to its cut, stops waiting and has its
 // running tables and atoms rebuilt from there; any other unfinished job waits
 // wait_step longer.  metrics[3] counts the jobs with nothing left afterwards.
+template <bool LIMITED>
 __global__ __launch_bounds__(256) void k_advance_jobs(
-    int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    JobLimits lim, int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ grant_job, const int32_t *__restrict__ grant_cut,
     const int32_t *__restrict__ job_gap, int32_t *__restrict__ progress, int32_t *__restrict__ wait,
@@ -208,8 +286,8 @@ __global__ __launch_bounds__(256) void k_advance_jobs(
         // every lane evaluates the same scalars, so the branch is uniform over the wave
         if (grant_holds(job_gap[j], j, n_gaps, n_jobs, seg_off, grant_job, grant_cut, job_gap, progress, cut)) {
             p = cut;
-            prepare_job(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db,
-                        n_atoms, first_dp);
+            prepare_job<LIMITED>(lim, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp,
+                                 atom_db, n_atoms, first_dp);
             if (lane == 0) {
                 progress[j] = p;
                 if (wait) wait[j] = 0;
