@@ -220,6 +220,46 @@ def main():
         chain["grants"].append(m[2])
         chain["rounds"].append(tick.rounds.cpu().tolist()[0])
         chain["utilisation"].append(m[0] / m[1] if m[1] else None)
+    # outside the timed steps: the tick's front half under admission limits, and the covering-capacity map
+    from gen import make_channels
+    import numpy as np
+    power, deadline = make_channels(wl, args.seed)
+    lim_kw = dict(tau_min=int(wl.W.max()) // 14, tau_max=(2 * int(wl.W.max())) // 3,
+                  power_cap=int(np.percentile(power, 85)), now=7)
+    d_power, d_deadline = torch.from_numpy(power).cuda(), torch.from_numpy(deadline).cuda()
+    cap_set = torch.from_numpy(np.unique(wl.C)).cuda()
+    cover = torch.empty(wl.n_gaps, dtype=torch.int32, device="cuda:0")
+    slack = torch.empty_like(cover)
+    tick.W, tick.C = chain_gaps[0]
+    tick.progress.copy_(torch.from_numpy(wl.progress))
+    limited = {"prepare_ms": [], "fit_select_ms": [], "cover_ms": []}
+    eng.sja_set_limits(P.Limits.make(**lim_kw), d_power, d_deadline)
+    try:
+        for i in range(args.steps + 1):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(); tick.prepare()
+            e[1].record(); tick.fit_select(par)
+            e[2].record(); e[2].synchronize()
+            if i:
+                limited["prepare_ms"].append(e[0].elapsed_time(e[1]))
+                limited["fit_select_ms"].append(e[1].elapsed_time(e[2]))
+        tick.resolve(par)
+        for i in range(args.steps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); eng.sja_cover(tick.C, tick.grant_job, tick.grant_cut, cap_set, cover, slack)
+            e1.record(); e1.synchronize()
+            if i:
+                limited["cover_ms"].append(e0.elapsed_time(e1))
+        limited = {k: sum(v) / len(v) for k, v in limited.items()}
+        limited.update({"limits": lim_kw, "interested_candidates": int((tick.cand_job >= 0).sum().item()),
+                        "grants": int((tick.grant_job >= 0).sum().item()),
+                        "rounds": tick.rounds.cpu().tolist()[0],
+                        "mean_slack_of_grants": float(slack[tick.grant_job >= 0].float().mean().item()),
+                        "note": "power trace under a cap, per-job deadlines, min / max subjob duration "
+                                "(sja_set_limits) and sja_cover over the gaps' own capacity set; "
+                                "not part of the timed step"})
+    finally:
+        eng.sja_set_limits(None)
     chain["note"] = ("sja_fit_select + sja_resolve + sja_advance per tick, new gaps every tick, no prepare "
                      "after the first; not part of the timed step")
 
@@ -249,6 +289,7 @@ def main():
                              "note": "sja_fit_select: the candidates of fit + select without the pair matrix; "
                                      "not part of the timed step"},
         "tick_chain": chain,
+        "admission_limits": limited,
         "resolve": {"rounds": rounds, "stable": stable, "grants": grants},
         "interest_density": interest_density,
         "roofline": {"kernel": "k_fit_main", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,

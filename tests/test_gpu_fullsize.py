@@ -189,3 +189,67 @@ def test_stress_chain_of_ticks(oracle):
         np.testing.assert_array_equal(t.pre_dur.cpu().numpy().astype(np.int64)[live], pd2[live])
         np.testing.assert_array_equal(t.pre_peak.cpu().numpy().astype(np.int64)[live], pp2[live])
         np.testing.assert_array_equal(t.prev_safe.cpu().numpy()[live], ps2[live])
+
+
+def test_stress_limits_full_size(oracle):
+    """The full Stress tick under all admission limits at once: sampled pairs and whole sampled
+    rows of the cut matrix, the fused candidates for every gap, and the grants with the oracle
+    evaluating each granted pair under the same limits."""
+    import torch
+    import paper_2509_19086_amd as P
+    from gen import make_channels
+    wl = make_workload("stress", 0)
+    G, J = wl.n_gaps, wl.n_jobs
+    power, deadline = make_channels(wl, 0)
+    kw = dict(tau_min=int(wl.W.max()) // 14, tau_max=(2 * int(wl.W.max())) // 3,
+              power_cap=int(np.percentile(power, 85)), now=7)
+    eng = P.Engine(0)
+    t = P.DeviceTick(eng, wl, want_bits=True)
+    d_power, d_deadline = torch.from_numpy(power).cuda(), torch.from_numpy(deadline).cuda()
+    eng.sja_set_limits(P.Limits.make(**kw), d_power, d_deadline)
+    olim = oracle.Limits.make(**kw)
+    par = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    opar = oracle.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    t.prepare(); t.fit(); t.select(par)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(43)
+    gi = rng.integers(0, G, size=300_000).astype(np.int32)
+    ji = rng.integers(0, J, size=300_000).astype(np.int32)
+    want, _, _ = oracle.fit_pairs_limited(gi, ji, wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C,
+                                          olim, power, deadline)
+    plain, _, _ = oracle.fit_pairs(gi, ji, wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C)
+    assert (want != plain).mean() > 0.05                       # the limits bind
+    flat = torch.from_numpy(gi.astype(np.int64) * J + ji.astype(np.int64)).cuda()
+    np.testing.assert_array_equal(t.cut.view(-1)[flat].cpu().numpy(), want)
+
+    rows = np.unique(np.concatenate([[0, G - 1, int(np.argmax(wl.W))], rng.integers(0, G, size=8)])).astype(np.int64)
+    cut_r, bits_r = oracle.fit_limited(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress,
+                                       np.ascontiguousarray(wl.W[rows]), np.ascontiguousarray(wl.C[rows]),
+                                       olim, power, deadline, True)
+    rows_t = torch.from_numpy(rows).cuda()
+    np.testing.assert_array_equal(t.cut[rows_t].cpu().numpy(), cut_r)
+    np.testing.assert_array_equal(t.bits[rows_t].cpu().numpy().view(np.uint32), bits_r)
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cj, cc, cs = oracle.select(cut_r, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+    np.testing.assert_array_equal(t.cand_job[rows_t].cpu().numpy(), cj)
+    np.testing.assert_array_equal(t.cand_score[rows_t].cpu().numpy(), cs)
+
+    sel = (t.cand_job.clone(), t.cand_cut.clone(), t.cand_score.clone())
+    t.fit_select(par)
+    torch.cuda.synchronize()
+    for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
+        assert torch.equal(a, b)
+
+    t.resolve(par)
+    gj = t.grant_job.cpu().numpy(); gc = t.grant_cut.cpu().numpy(); jg = t.job_gap.cpu().numpy()
+    granted = np.nonzero(gj >= 0)[0]
+    assert len(granted) > 1000 and len(np.unique(gj[granted])) == len(granted)
+    np.testing.assert_array_equal(jg[gj[granted]], granted)
+    ocut, sd, sp = oracle.fit_pairs_limited(granted.astype(np.int32), gj[granted], wl.seg_off, wl.dur, wl.mem,
+                                            wl.safe, wl.progress, wl.W, wl.C, olim, power, deadline)
+    np.testing.assert_array_equal(gc[granted], ocut)
+    lens = np.diff(wl.seg_off)
+    assert (sd <= kw["tau_max"]).all() and (sd <= deadline[gj[granted]].astype(np.int64) - kw["now"]).all()
+    assert ((sd >= kw["tau_min"]) | (ocut == lens[gj[granted]])).all()
+    assert gj[0] == cj[0] and gc[0] == cc[0]
