@@ -5,6 +5,9 @@
  * One tick of the paper's three-phase protocol (Sec. 3.5), evaluated for every
  * advertised gap and every waiting job at once:
  *
+ *   sja_set_limits        optional admission limits applied by the next prepare:
+ *                         power trace under a cap, per-job deadline (Sec. 4.4),
+ *                         minimum / maximum subjob duration (Sec. 4.3)
  *   sja_prepare_profiles  per-job running duration / running peak / last safe
  *                         boundary from the job's progress point (the on-demand
  *                         evaluation of the envelope U(t), Sec. 3.9)
