@@ -104,6 +104,94 @@ def cpu_baseline(wl, sample_gaps):
     }
 
 
+def measure_extras(args, wl, eng, tick, par):
+    """Measured after the timed steps, never part of them: the fused fit-select call, a chain of
+    ticks with sja_advance, and the tick's front half under admission limits with sja_cover."""
+    import numpy as np
+    import torch
+    import paper_2509_19086_amd as P
+    from gen import make_channels, make_gaps
+    pairs = wl.n_gaps * wl.n_jobs
+
+    # the fused fit -> select call (same candidates, no pair matrix)
+    fused_ms, fused_kernel_ms = [], []
+    for i in range(args.steps + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); tick.fit_select(par); e1.record(); e1.synchronize()
+        if i:
+            fused_ms.append(e0.elapsed_time(e1))
+            fused_kernel_ms.append(eng.sja_last_fit_kernel_ms())
+
+    # a chain of ticks with fresh gaps each tick (fused fit-select,
+    # grants, advance), the job tables carried over instead of prepared again
+    chain_gaps = [(tick.W, tick.C)] + [tuple(torch.from_numpy(a).cuda() for a in
+                                             make_gaps(args.workload, args.seed, k)) for k in range(1, args.chain_ticks)]
+    chain = {"tick_ms": [], "advance_ms": [], "grants": [], "rounds": [], "utilisation": []}
+    tick.prepare()
+    for W_k, C_k in chain_gaps:
+        tick.W, tick.C = W_k, C_k
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record(); tick.fit_select(par); tick.resolve(par)
+        e[1].record(); tick.advance(1000)
+        e[2].record(); e[2].synchronize()
+        m = tick.metrics.cpu().tolist()
+        chain["tick_ms"].append(e[0].elapsed_time(e[2]))
+        chain["advance_ms"].append(e[1].elapsed_time(e[2]))
+        chain["grants"].append(m[2])
+        chain["rounds"].append(tick.rounds.cpu().tolist()[0])
+        chain["utilisation"].append(m[0] / m[1] if m[1] else None)
+    # the tick's front half under admission limits, and the covering-capacity map
+    power, deadline = make_channels(wl, args.seed)
+    lim_kw = dict(tau_min=int(wl.W.max()) // 14, tau_max=(2 * int(wl.W.max())) // 3,
+                  power_cap=int(np.percentile(power, 85)), now=7)
+    d_power, d_deadline = torch.from_numpy(power).cuda(), torch.from_numpy(deadline).cuda()
+    cap_set = torch.from_numpy(np.unique(wl.C)).cuda()
+    cover = torch.empty(wl.n_gaps, dtype=torch.int32, device="cuda:0")
+    slack = torch.empty_like(cover)
+    tick.W, tick.C = chain_gaps[0]
+    tick.progress.copy_(torch.from_numpy(wl.progress))
+    limited = {"prepare_ms": [], "fit_select_ms": [], "cover_ms": []}
+    eng.sja_set_limits(P.Limits.make(**lim_kw), d_power, d_deadline)
+    try:
+        for i in range(args.steps + 1):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(); tick.prepare()
+            e[1].record(); tick.fit_select(par)
+            e[2].record(); e[2].synchronize()
+            if i:
+                limited["prepare_ms"].append(e[0].elapsed_time(e[1]))
+                limited["fit_select_ms"].append(e[1].elapsed_time(e[2]))
+        tick.resolve(par)
+        for i in range(args.steps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); eng.sja_cover(tick.C, tick.grant_job, tick.grant_cut, cap_set, cover, slack)
+            e1.record(); e1.synchronize()
+            if i:
+                limited["cover_ms"].append(e0.elapsed_time(e1))
+        limited = {k: sum(v) / len(v) for k, v in limited.items()}
+        limited.update({"limits": lim_kw, "interested_candidates": int((tick.cand_job >= 0).sum().item()),
+                        "grants": int((tick.grant_job >= 0).sum().item()),
+                        "rounds": tick.rounds.cpu().tolist()[0],
+                        "mean_slack_of_grants": float(slack[tick.grant_job >= 0].float().mean().item()),
+                        "note": "power trace under a cap, per-job deadlines, min / max subjob duration "
+                                "(sja_set_limits) and sja_cover over the gaps' own capacity set; "
+                                "not part of the timed step"})
+    finally:
+        eng.sja_set_limits(None)
+    chain["note"] = ("sja_fit_select + sja_resolve + sja_advance per tick, new gaps every tick, no prepare "
+                     "after the first; not part of the timed step")
+
+    return {
+        "fused_fit_select": {"call_ms": sum(fused_ms) / len(fused_ms),
+                             "kernel_ms": sum(fused_kernel_ms) / len(fused_kernel_ms),
+                             "evals_per_s": pairs / (sum(fused_ms) / len(fused_ms) * 1e-3),
+                             "note": "sja_fit_select: the candidates of fit + select without the pair matrix; "
+                                     "not part of the timed step"},
+        "tick_chain": chain,
+        "admission_limits": limited,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +207,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (reference reading for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE) and exit")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip what is measured after the timed steps (fused call, chain of ticks, limits)")
     ap.add_argument("--chain-ticks", type=int, default=4,
                     help="ticks in the carried-over chain measured after the timed steps")
     args = ap.parse_args()
@@ -182,15 +272,6 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    # outside the timed steps: the fused fit -> select call (same candidates, no pair matrix)
-    fused_ms, fused_kernel_ms = [], []
-    for i in range(args.steps + 1):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(); tick.fit_select(par); e1.record(); e1.synchronize()
-        if i:
-            fused_ms.append(e0.elapsed_time(e1))
-            fused_kernel_ms.append(eng.sja_last_fit_kernel_ms())
-
     pairs = wl.n_gaps * wl.n_jobs
     ms_per_step = 1e3 * elapsed / args.steps
     mean = lambda xs: sum(xs) / len(xs)
@@ -201,67 +282,7 @@ def main():
     grants = int((tick.grant_job >= 0).sum().item())
     interest_density = float((tick.cut >= 0).float().mean().item()) if pairs <= 2**29 else None
 
-    # outside the timed steps: a chain of ticks with fresh gaps each tick (fused fit-select,
-    # grants, advance), the job tables carried over instead of prepared again
-    from gen import make_gaps
-    chain_gaps = [(tick.W, tick.C)] + [tuple(torch.from_numpy(a).cuda() for a in
-                                             make_gaps(args.workload, args.seed, k)) for k in range(1, args.chain_ticks)]
-    chain = {"tick_ms": [], "advance_ms": [], "grants": [], "rounds": [], "utilisation": []}
-    tick.prepare()
-    for W_k, C_k in chain_gaps:
-        tick.W, tick.C = W_k, C_k
-        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        e[0].record(); tick.fit_select(par); tick.resolve(par)
-        e[1].record(); tick.advance(1000)
-        e[2].record(); e[2].synchronize()
-        m = tick.metrics.cpu().tolist()
-        chain["tick_ms"].append(e[0].elapsed_time(e[2]))
-        chain["advance_ms"].append(e[1].elapsed_time(e[2]))
-        chain["grants"].append(m[2])
-        chain["rounds"].append(tick.rounds.cpu().tolist()[0])
-        chain["utilisation"].append(m[0] / m[1] if m[1] else None)
-    # outside the timed steps: the tick's front half under admission limits, and the covering-capacity map
-    from gen import make_channels
-    import numpy as np
-    power, deadline = make_channels(wl, args.seed)
-    lim_kw = dict(tau_min=int(wl.W.max()) // 14, tau_max=(2 * int(wl.W.max())) // 3,
-                  power_cap=int(np.percentile(power, 85)), now=7)
-    d_power, d_deadline = torch.from_numpy(power).cuda(), torch.from_numpy(deadline).cuda()
-    cap_set = torch.from_numpy(np.unique(wl.C)).cuda()
-    cover = torch.empty(wl.n_gaps, dtype=torch.int32, device="cuda:0")
-    slack = torch.empty_like(cover)
-    tick.W, tick.C = chain_gaps[0]
-    tick.progress.copy_(torch.from_numpy(wl.progress))
-    limited = {"prepare_ms": [], "fit_select_ms": [], "cover_ms": []}
-    eng.sja_set_limits(P.Limits.make(**lim_kw), d_power, d_deadline)
-    try:
-        for i in range(args.steps + 1):
-            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-            e[0].record(); tick.prepare()
-            e[1].record(); tick.fit_select(par)
-            e[2].record(); e[2].synchronize()
-            if i:
-                limited["prepare_ms"].append(e[0].elapsed_time(e[1]))
-                limited["fit_select_ms"].append(e[1].elapsed_time(e[2]))
-        tick.resolve(par)
-        for i in range(args.steps + 1):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); eng.sja_cover(tick.C, tick.grant_job, tick.grant_cut, cap_set, cover, slack)
-            e1.record(); e1.synchronize()
-            if i:
-                limited["cover_ms"].append(e0.elapsed_time(e1))
-        limited = {k: sum(v) / len(v) for k, v in limited.items()}
-        limited.update({"limits": lim_kw, "interested_candidates": int((tick.cand_job >= 0).sum().item()),
-                        "grants": int((tick.grant_job >= 0).sum().item()),
-                        "rounds": tick.rounds.cpu().tolist()[0],
-                        "mean_slack_of_grants": float(slack[tick.grant_job >= 0].float().mean().item()),
-                        "note": "power trace under a cap, per-job deadlines, min / max subjob duration "
-                                "(sja_set_limits) and sja_cover over the gaps' own capacity set; "
-                                "not part of the timed step"})
-    finally:
-        eng.sja_set_limits(None)
-    chain["note"] = ("sja_fit_select + sja_resolve + sja_advance per tick, new gaps every tick, no prepare "
-                     "after the first; not part of the timed step")
+    extras = {} if args.no_extras else measure_extras(args, wl, eng, tick, par)
 
     out = {
         "metric": "gap-job fit evaluations/sec (whole tick: prepare+fit+select+resolve), 1 GPU",
@@ -283,13 +304,7 @@ def main():
         "call_ms": {k: mean(v) for k, v in rec.items()},
         "fit_evals_per_s": pairs / (mean(rec["fit"]) * 1e-3),
         "fit_kernel_evals_per_s": pairs / (fit_kernel_ms * 1e-3),
-        "fused_fit_select": {"call_ms": sum(fused_ms) / len(fused_ms),
-                             "kernel_ms": sum(fused_kernel_ms) / len(fused_kernel_ms),
-                             "evals_per_s": pairs / (sum(fused_ms) / len(fused_ms) * 1e-3),
-                             "note": "sja_fit_select: the candidates of fit + select without the pair matrix; "
-                                     "not part of the timed step"},
-        "tick_chain": chain,
-        "admission_limits": limited,
+        **extras,
         "resolve": {"rounds": rounds, "stable": stable, "grants": grants},
         "interest_density": interest_density,
         "roofline": {"kernel": "k_fit_main", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
