@@ -98,6 +98,30 @@ def test_resolve_mode_validation(lib):
         lib.sja_destroy(h)
 
 
+def test_tick_end_calls_validate_on_the_host(lib):
+    import paper_2509_19086_amd as P
+    vp = ctypes.c_void_p
+    h = vp()
+    assert lib.sja_create(ctypes.byref(h), 0) == 0
+    junk = vp(256)                                     # never dereferenced on these paths
+    try:
+        # nothing prepared yet
+        assert lib.sja_advance(h, None, 4, junk, junk, junk, junk, junk, junk, None, 1, junk) == -4
+        assert b"sja_advance" in lib.sja_last_error(h)
+        assert lib.sja_cover(h, None, 4, junk, junk, junk, 2, junk, junk, junk) == -4
+        assert lib.sja_advance(None, None, 0, None, None, None, None, None, None, None, 0, None) == -1
+        assert lib.sja_cover(None, None, 0, None, None, None, 0, None, None, None) == -1
+        # limits: host-side copy, range checks, clearing
+        lim = P.Limits.make(tau_min=3, tau_max=9)
+        assert lib.sja_set_limits(h, ctypes.byref(lim), None, None) == 0
+        assert lib.sja_set_limits(h, ctypes.byref(P.Limits.make(tau_min=-1)), None, None) == -2
+        assert lib.sja_set_limits(h, ctypes.byref(P.Limits.make(tau_max=-1)), None, None) == -2
+        assert lib.sja_set_limits(h, None, None, None) == 0
+        assert lib.sja_set_limits(None, None, None, None) == -1
+    finally:
+        lib.sja_destroy(h)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     import paper_2509_19086_amd as P
