@@ -104,6 +104,83 @@ def cpu_baseline(wl, sample_gaps):
     }
 
 
+def run_statistics(wl, tick):
+    """What one tick produced, for comparing runs: interest density, mean walk length (cut - progress
+    over the interested pairs) and plain int64 sums of the outputs.  Computed after the timed steps,
+    a slab of gap rows at a time so that the temporaries stay small."""
+    import torch
+    G, J = wl.n_gaps, wl.n_jobs
+    interested = 0
+    cut_sum = 0
+    walk_sum = 0
+    prog = tick.progress.to(torch.int64)
+    rows = max(1, (1 << 28) // max(J, 1))
+    for g0 in range(0, G, rows):
+        slab = tick.cut[g0:g0 + rows]
+        m = slab >= 0
+        per_job = m.sum(dim=0, dtype=torch.int64)
+        interested += int(per_job.sum().item())
+        cut_sum += int(slab.sum(dtype=torch.int64).item())
+        walk_sum += int((torch.where(m, slab, torch.zeros_like(slab)).sum(dtype=torch.int64)
+                         - (per_job * prog).sum()).item())
+    i64 = lambda t: int(t.sum(dtype=torch.int64).item())
+    return {"interest_density": interested / (G * J) if G * J else None,
+            "mean_walk_segments": walk_sum / interested if interested else None,
+            "checksums": {"cut": cut_sum, "interest_bits": i64(tick.bits.view(torch.uint8)) if tick.bits is not None else None,
+                          "pre_dur": i64(tick.pre_dur), "cand_job": i64(tick.cand_job), "cand_score": i64(tick.cand_score),
+                          "grant_job": i64(tick.grant_job), "grant_cut": i64(tick.grant_cut),
+                          "grant_score": i64(tick.grant_score), "job_gap": i64(tick.job_gap)}}
+
+
+def bandwidth_reference(tick):
+    """What this GPU does on plain kernels, measured in the same process: a fill of the cut matrix
+    (store-only, the shape of the pair-evaluation kernel's traffic) and a 1 GiB device copy
+    (read + write counted)."""
+    import torch
+    def timed(fn, reps=5):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+    out = {}
+    if tick.cut is not None and tick.cut.numel():
+        ms = timed(lambda: tick.cut.fill_(-1))
+        out["fill_cut_matrix_GBs"] = tick.cut.numel() * 4 / (ms * 1e-3) / 1e9
+    src = torch.empty(2**28, dtype=torch.int32, device="cuda:0")
+    dst = torch.empty_like(src)
+    ms = timed(lambda: dst.copy_(src))
+    out["copy_1GiB_GBs"] = 2 * src.numel() * 4 / (ms * 1e-3) / 1e9
+    return out
+
+
+def large_fit(args):
+    """The pair-evaluation kernel on the Large config as well (the second-largest; 2^28 pairs)."""
+    import torch
+    import paper_2509_19086_amd as P
+    from gen import make_workload
+    wl = make_workload("large", args.seed)
+    eng = P.Engine(0)
+    eng.sja_enable_timing(True)
+    t = P.DeviceTick(eng, wl)
+    t.prepare()
+    ms, call = [], []
+    for i in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); t.fit(); e1.record(); e1.synchronize()
+        if i:
+            ms.append(eng.sja_last_fit_kernel_ms())
+            call.append(e0.elapsed_time(e1))
+    alg = algorithmic_fit_bytes(wl, count_atoms(wl))
+    k = sum(ms) / len(ms)
+    return {"workload": f"large seed {wl.seed}: {wl.n_gaps} gaps x {wl.n_jobs} jobs", "kernel_ms": k,
+            "call_ms": sum(call) / len(call), "algorithmic_bytes": alg,
+            "achieved_GBs": alg / (k * 1e-3) / 1e9, "frac": alg / (k * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "evals_per_s": wl.n_gaps * wl.n_jobs / (k * 1e-3)}
+
+
 def measure_extras(args, wl, eng, tick, par):
     """Measured after the timed steps, never part of them: the fused fit-select call, a chain of
     ticks with sja_advance, and the tick's front half under admission limits with sja_cover."""
@@ -115,7 +192,8 @@ def measure_extras(args, wl, eng, tick, par):
 
     # the fused fit -> select call (same candidates, no pair matrix)
     fused_ms, fused_kernel_ms = [], []
-    for i in range(args.steps + 1):
+    reps = 3
+    for i in range(reps + 1):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(); tick.fit_select(par); e1.record(); e1.synchronize()
         if i:
@@ -153,7 +231,7 @@ def measure_extras(args, wl, eng, tick, par):
     limited = {"prepare_ms": [], "fit_select_ms": [], "cover_ms": []}
     eng.sja_set_limits(P.Limits.make(**lim_kw), d_power, d_deadline)
     try:
-        for i in range(args.steps + 1):
+        for i in range(reps + 1):
             e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             e[0].record(); tick.prepare()
             e[1].record(); tick.fit_select(par)
@@ -162,7 +240,7 @@ def measure_extras(args, wl, eng, tick, par):
                 limited["prepare_ms"].append(e[0].elapsed_time(e[1]))
                 limited["fit_select_ms"].append(e[1].elapsed_time(e[2]))
         tick.resolve(par)
-        for i in range(args.steps + 1):
+        for i in range(reps + 1):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(); eng.sja_cover(tick.C, tick.grant_job, tick.grant_cut, cap_set, cover, slack)
             e1.record(); e1.synchronize()
@@ -189,14 +267,15 @@ def measure_extras(args, wl, eng, tick, par):
                                      "not part of the timed step"},
         "tick_chain": chain,
         "admission_limits": limited,
+        "large_fit": large_fit(args) if wl.name != "large" else None,
     }
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="stress",
                     help="named config (default: stress, the largest single-GPU config)")
     ap.add_argument("--seed", type=int, default=0)
@@ -280,7 +359,8 @@ def main():
     achieved = alg_bytes / (fit_kernel_ms * 1e-3) / 1e9
     rounds, stable = tick.rounds.cpu().tolist()
     grants = int((tick.grant_job >= 0).sum().item())
-    interest_density = float((tick.cut >= 0).float().mean().item()) if pairs <= 2**29 else None
+    stats = run_statistics(wl, tick)
+    reference = bandwidth_reference(tick)
 
     extras = {} if args.no_extras else measure_extras(args, wl, eng, tick, par)
 
@@ -302,13 +382,18 @@ def main():
                                f"max_rounds {wl.max_rounds}",
                    "pairs": pairs, "atoms": n_atoms},
         "call_ms": {k: mean(v) for k, v in rec.items()},
+        "call_ms_median": {k: sorted(v)[len(v) // 2] for k, v in rec.items()},
+        "call_ms_min": {k: min(v) for k, v in rec.items()},
         "fit_evals_per_s": pairs / (mean(rec["fit"]) * 1e-3),
         "fit_kernel_evals_per_s": pairs / (fit_kernel_ms * 1e-3),
         **extras,
         "resolve": {"rounds": rounds, "stable": stable, "grants": grants},
-        "interest_density": interest_density,
+        "run": stats,
+        "bandwidth_reference": reference,
         "roofline": {"kernel": "k_fit_main", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "frac_of_fill": (achieved / reference["fill_cut_matrix_GBs"]
+                                      if "fill_cut_matrix_GBs" in reference else None),
                      "traffic": measured_fit_traffic(args.workload, args.seed),
                      "algorithmic_bytes": alg_bytes, "kernel_ms": fit_kernel_ms},
         "gen_seconds": t_gen,
