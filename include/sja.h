@@ -300,6 +300,31 @@ int sja_cover(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *C, cons
               int32_t *slack);
 
 /*
+ * Input check, no step of the method: the data-dependent preconditions that
+ * the calls above assume and do not test themselves.  *problems (device,
+ * one uint32) receives the OR of the sja_problem bits found, 0 if none.
+ *   seg_off [n_jobs+1], dur, mem [n_segments], progress [n_jobs]: as for
+ *   sja_prepare_profiles.  params (host; may be NULL), wait, sla_class: as for
+ *   sja_select; with params the policy's per-job inputs are checked too, and
+ *   the score bound is tested per job against (whole duration) x (largest
+ *   memory) x the job's policy factor, which no subjob's score exceeds.
+ * Reads nothing outside the arrays whatever their contents.  Only enqueues work.
+ */
+typedef enum {
+    SJA_BAD_OFFSETS = 1,       /* seg_off does not start at 0, decreases, or does not end at n_segments */
+    SJA_BAD_DURATION = 2,      /* a segment lasts less than 1 tick                                      */
+    SJA_BAD_MEMORY = 4,        /* a negative memory value                                               */
+    SJA_BAD_PROGRESS = 8,      /* a progress point outside [0, L_j]                                     */
+    SJA_BAD_DURATION_SUM = 16, /* a job's durations sum to more than 2^31-1                             */
+    SJA_BAD_CLASS = 32,        /* an SLA class above 2 under a policy that reads it                     */
+    SJA_BAD_WAIT = 64,         /* a negative waiting time under a policy that reads it                  */
+    SJA_BAD_SCORE_RANGE = 128  /* a policy score could reach 2^62                                       */
+} sja_problem;
+int sja_validate(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments, const int64_t *seg_off,
+                 const int32_t *dur, const int32_t *mem, const int32_t *progress, const sja_params *params,
+                 const int32_t *wait, const uint8_t *sla_class, uint32_t *problems);
+
+/*
  * Measurement aid for benchmarks (callers that report the pair-evaluation
  * kernel's own duration rather than the whole call's).  With timing enabled,
  * sja_fit brackets its pair-evaluation kernel with HIP events on `stream`;

@@ -87,6 +87,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_set_limits.restype = ctypes.c_int
     lib.sja_cover.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp, vp]
     lib.sja_cover.restype = ctypes.c_int
+    lib.sja_validate.argtypes = [vp, vp, i32, i64, vp, vp, vp, vp, ctypes.POINTER(Params), vp, vp, vp]
+    lib.sja_validate.restype = ctypes.c_int
     lib.sja_advance.argtypes = [vp, vp, i32] + [vp] * 7 + [i32, vp]
     lib.sja_advance.restype = ctypes.c_int
     lib.sja_enable_timing.argtypes = [vp, ctypes.c_int]
@@ -221,6 +223,16 @@ class Engine:
                 _ptr(grant_score, torch.int64, G), _ptr(job_gap, torch.int32, J),
                 _ptr(rounds_used_and_stable, torch.int32, 2))
         rc = self.lib.sja_resolve(self.h, _stream(), ctypes.byref(params), *args)
+        self._check(rc, self.h)
+
+    def sja_validate(self, seg_off, dur, mem, progress, params, wait, sla_class, problems):
+        J, S = seg_off.numel() - 1, dur.numel()
+        rc = self.lib.sja_validate(self.h, _stream(), J, S, _ptr(seg_off, torch.int64, J + 1),
+                                   _ptr(dur, torch.int32, S), _ptr(mem, torch.int32, S),
+                                   _ptr(progress, torch.int32, J),
+                                   ctypes.byref(params) if params is not None else None,
+                                   _ptr(wait, torch.int32, J), _ptr(sla_class, torch.uint8, J),
+                                   _ptr(problems, torch.int32, 1))
         self._check(rc, self.h)
 
     def sja_set_limits(self, limits, power=None, deadline=None):

@@ -432,6 +432,36 @@ int sja_set_workspace(sja_ctx *ctx, void *dev_ptr, size_t bytes)
     return SJA_OK;
 }
 
+int sja_validate(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments, const int64_t *seg_off,
+                 const int32_t *dur, const int32_t *mem, const int32_t *progress, const sja_params *params,
+                 const int32_t *wait, const uint8_t *sla_class, uint32_t *problems)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (n_jobs < 0 || n_jobs > SJA_MAX_JOBS) return fail(ctx, SJA_ERR_SIZE, "n_jobs");
+    if (n_segments < 0 || n_segments > SJA_MAX_SEGMENTS) return fail(ctx, SJA_ERR_SIZE, "n_segments");
+    if (!seg_off || !problems) return fail(ctx, SJA_ERR_NULL, "seg_off / problems");
+    if (n_jobs > 0 && !progress) return fail(ctx, SJA_ERR_NULL, "progress");
+    if (n_segments > 0 && (!dur || !mem)) return fail(ctx, SJA_ERR_NULL, "dur / mem");
+    PolicyDev pol{};
+    if (params) {
+        const int rc = check_params(ctx, params, wait, sla_class);
+        if (rc != SJA_OK) return rc;
+        pol = to_dev(params);
+    }
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, st, reinterpret_cast<int32_t *>(problems), int64_t(1), 0);
+    SJA_HIP(hipGetLastError(), "k_fill_i32 launch");
+    if (n_jobs > 0) {
+        const int jobs_per_block = 256 / kWave;
+        hipLaunchKernelGGL(k_validate, dim3((n_jobs + jobs_per_block - 1) / jobs_per_block), dim3(256), 0, st, n_jobs,
+                           n_segments, seg_off, dur, mem, progress, params != nullptr, pol, wait, sla_class, problems);
+        SJA_HIP(hipGetLastError(), "k_validate launch");
+    }
+    return SJA_OK;
+}
+
 int sja_enable_timing(sja_ctx *ctx, int on)
 {
     if (!ctx) return SJA_ERR_NULL;

@@ -316,6 +316,64 @@ __global__ __launch_bounds__(256) void k_advance_jobs(
 namespace sja {
 
 // --------------------------------------------------------------------------
+// Input check (no step of the method): the data-dependent assumptions the
+// other kernels make and do not test.  One wave per job; reads stay inside
+// [0, n_segments) whatever the offsets say.  Bits as in the header.
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_validate(
+    int n_jobs, int64_t n_segments, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    const int32_t *__restrict__ mem, const int32_t *__restrict__ progress, bool with_policy, PolicyDev pol,
+    const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class, uint32_t *__restrict__ problems)
+{
+    const int lane = lane_id();
+    const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (j >= n_jobs) return;
+    uint32_t bad = 0;
+    const int64_t b = seg_off[j], e = seg_off[j + 1];
+    if (b < 0 || e < b || e > n_segments || (j == 0 && b != 0) || (j == n_jobs - 1 && e != n_segments) ||
+        e - b > INT32_MAX) {
+        bad |= SJA_BAD_OFFSETS;
+    } else {
+        const int L = int(e - b);
+        const int p = progress[j];
+        if (p < 0 || p > L) bad |= SJA_BAD_PROGRESS;
+        long long sum = 0;
+        int peak = 0;
+        for (int k = lane; k < L; k += kWave) {
+            const int d = dur[b + k], m = mem[b + k];
+            if (d < 1) bad |= SJA_BAD_DURATION;
+            if (m < 0) bad |= SJA_BAD_MEMORY;
+            sum += d > 0 ? d : 0;
+            peak = max(peak, m);
+        }
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            sum += __shfl_xor(sum, d, kWave);
+            peak = max(peak, __shfl_xor(peak, d, kWave));
+        }
+        if (sum > INT32_MAX) bad |= SJA_BAD_DURATION_SUM;
+        if (with_policy) {
+            const int cls = sla_class ? sla_class[j] : 0;
+            const bool uses_class = pol.policy == SJA_POLICY_SLA || pol.policy == SJA_POLICY_MIXED;
+            const bool uses_wait = pol.policy == SJA_POLICY_FAIRNESS || pol.policy == SJA_POLICY_MIXED;
+            if (uses_class && cls > 2) bad |= SJA_BAD_CLASS;
+            if (uses_wait && wait[j] < 0) bad |= SJA_BAD_WAIT;
+            if (!(bad & (SJA_BAD_CLASS | SJA_BAD_WAIT | SJA_BAD_DURATION_SUM))) {
+                // no subjob of the job fills more than (whole duration) x (largest memory)
+                unsigned long long mult, tier;
+                job_policy(pol, wait, sla_class, j, mult, tier);
+                const unsigned long long F = (unsigned long long)sum * (unsigned long long)peak;   // < 2^62
+                const unsigned long long limit = 1ull << 62;
+                if (mult != 0 && F >= (limit + mult - 1) / mult) bad |= SJA_BAD_SCORE_RANGE;
+            }
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) bad |= __shfl_xor(int(bad), d, kWave);
+    if (lane == 0 && bad) atomicOr(problems, bad);
+}
+
+// --------------------------------------------------------------------------
 // K3  policy arg-max per gap (Sec. 3.5 phase 3).  Lanes run along jobs and
 // walk a chunk of gap positions in the sorted order of the last fit, so a
 // job's cut -- and with it F = duration * peak -- rarely changes from one

@@ -118,6 +118,12 @@ def test_tick_end_calls_validate_on_the_host(lib):
         assert lib.sja_set_limits(h, ctypes.byref(P.Limits.make(tau_max=-1)), None, None) == -2
         assert lib.sja_set_limits(h, None, None, None) == 0
         assert lib.sja_set_limits(None, None, None, None) == -1
+        # validate: sizes and required pointers
+        assert lib.sja_validate(h, None, -1, 0, junk, None, None, junk, None, None, None, junk) == -2
+        assert lib.sja_validate(h, None, 4, 8, None, junk, junk, junk, None, None, None, junk) == -1
+        assert lib.sja_validate(h, None, 4, 8, junk, junk, junk, junk, None, None, None, None) == -1
+        assert lib.sja_validate(h, None, 4, 8, junk, junk, junk, junk, ctypes.byref(P.Params.make(7)), junk, junk,
+                                junk) == -3
     finally:
         lib.sja_destroy(h)
 
