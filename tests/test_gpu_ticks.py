@@ -195,3 +195,28 @@ def test_advance_state_and_argument_checks(engine):
         t.resolve(par)
     t.fit_select(par); t.resolve(par)                          # a new fit needs no new prepare
     torch.cuda.synchronize()
+
+
+def test_advance_and_cover_with_no_gaps(engine, oracle):
+    """A tick that offered nothing: every unfinished job waits, the totals are zero."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("tiny", 0, n_gaps=0, n_jobs=6)
+    wl.progress[2] = int(wl.seg_off[3] - wl.seg_off[2])                    # one finished job
+    t = P.DeviceTick(engine, wl, want_bits=False, want_cut=False)
+    par = P.Params.make(1, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    t.prepare(); t.fit_select(par); t.resolve(par)
+    t.metrics.fill_(-3)
+    t.advance(11)
+    cover = torch.empty(0, dtype=torch.int32, device="cuda:0")
+    engine.sja_cover(t.C, t.grant_job, t.grant_cut, torch.tensor([5, 9], dtype=torch.int32, device="cuda:0"),
+                     cover, cover.clone())
+    torch.cuda.synchronize()
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    none = np.zeros(0, dtype=np.int32)
+    p2, w2, m = oracle.advance(wl.seg_off, pd, pp, none, none, none, none, np.full(6, -1, np.int32), wl.progress,
+                               wl.wait, 11)
+    np.testing.assert_array_equal(t.progress.cpu().numpy(), p2)
+    np.testing.assert_array_equal(t.wait.cpu().numpy(), w2)
+    assert t.metrics.cpu().tolist() == m.tolist() == [0, 0, 0, 1]
+    assert w2[2] == wl.wait[2] and (np.delete(w2, 2) == np.delete(wl.wait, 2) + 11).all()
