@@ -1,7 +1,7 @@
 // Fused fit -> select: the per-gap policy arg-max straight from the atom
-// tables, without a (gap, job) matrix in between (Sec. 3.5: no subjob state is
-// created before a grant is issued; what a gap needs from the jobs' replies is
-// only the best one).
+// tables, without a (gap, job) matrix in between (Sec. 3.5: a subjob only
+// comes into being at its grant, so all a gap needs from the jobs' replies is
+// the best one).
 //
 // The stepping is that of the pair-evaluation kernel: lanes run along jobs,
 // waves step through sorted gap positions of one capacity class, each lane
