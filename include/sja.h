@@ -90,7 +90,7 @@ typedef enum {
 } sja_policy;
 
 /*
- * Policy parameters (Sec. 3.5: the scheduler "applies its allocation policy";
+ * Policy parameters (Sec. 3.5: the scheduler picks by its allocation policy;
  * Sec. 4.2: a lightweight selection among interested jobs).  F is the
  * capacity-time rectangle a subjob fills: its duration times its peak memory.
  * Keys compare lexicographically, larger wins, equal keys go to the lower job
