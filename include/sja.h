@@ -28,10 +28,10 @@
  *   - Every array argument is a DEVICE pointer owned by the caller, unless the
  *     comment says "host".  The library never frees or reallocates them.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     sja_prepare_profiles, sja_fit and sja_select only enqueue work and
- *     return; outputs are valid once the stream has been synchronised.
- *     sja_resolve runs a data-dependent number of rounds and synchronises the
- *     stream before it returns.
+ *     Every call except sja_resolve only enqueues work and returns; outputs
+ *     are valid once the stream has been synchronised.  sja_resolve runs a
+ *     data-dependent number of rounds and synchronises the stream before it
+ *     returns.
  *   - The context remembers the pointers and sizes handed to the previous
  *     call of the sequence prepare -> fit -> select / resolve: the arrays of
  *     sja_prepare_profiles must stay alive and unchanged until the last
@@ -52,7 +52,8 @@
  * subjob boundary (Sec. 3.7); the end counts as one whatever its flag.
  * progress[j] in [0, L] is the boundary the job has completed up to.
  *
- * Data-dependent preconditions (not checked): seg_off non-decreasing with
+ * Data-dependent preconditions (not checked by these calls; sja_validate
+ * checks them on the device and reports problem bits): seg_off non-decreasing with
  * seg_off[0] == 0 and seg_off[n_jobs] == n_segments; 0 <= progress[j] <= L_j;
  * dur >= 1; mem >= 0; per job, the sum of durations fits int32; every policy
  * score term (see sja_params: F, or F times its weight) is below 2^62 (the

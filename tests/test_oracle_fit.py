@@ -266,3 +266,28 @@ def test_illustrative_scenario_from_the_paper(oracle):
     mono = np.zeros_like(safe)
     cut_m, _ = oracle.fit(seg_off, dur, mem, mono, progress, W, C)
     assert cut_m[0, 0] == -1
+
+
+@pytest.mark.parametrize("name", ["large", "stress"])
+def test_fullsize_digest_files_come_from_this_oracle(oracle, name):
+    """The stored full-size digests (tests/golden/make_fullsize_digest.py) are what the oracle
+    gives today: two of their blocks recomputed here."""
+    import importlib.util
+    path = os.path.join(GOLDEN, f"fullsize_digest_{name}.json")
+    with open(path) as f:
+        gold = json.load(f)
+    spec = importlib.util.spec_from_file_location("make_fullsize_digest",
+                                                  os.path.join(GOLDEN, "make_fullsize_digest.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    wl = make_workload(name, gold["seed"])
+    assert len(gold["blocks"]) == (wl.n_gaps + gold["block"] - 1) // gold["block"]
+    par = oracle.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    for b in (0, len(gold["blocks"]) - 1):
+        g0 = b * gold["block"]
+        W = np.ascontiguousarray(wl.W[g0:g0 + gold["block"]])
+        C = np.ascontiguousarray(wl.C[g0:g0 + gold["block"]])
+        cut, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, W, C, False)
+        cj, cc, cs = oracle.select(cut, wl.seg_off, pd, pp, par, wl.wait, wl.sla_class)
+        assert mod.block_digest(cut, g0, cj, cc, cs) == gold["blocks"][b]
