@@ -4,6 +4,8 @@ gap order).  Calls only gen/ and oracle/.  The GPU tests recompute the same dige
 library's outputs, which compares whole outputs at sizes where the oracle takes minutes.
 
     python tests/golden/make_fullsize_digest.py large stress
+    python tests/golden/make_fullsize_digest.py --resolve large stress   (adds the grants; keeps the whole
+                                                                         cut matrix in host memory, hours at Stress)
 
 Per block b (gaps g = 256 b .. 256 b + 255, jobs j), all sums in wrapping int64:
     interested   number of pairs with cut >= 0
@@ -12,6 +14,9 @@ Per block b (gaps g = 256 b .. 256 b + 255, jobs j), all sums in wrapping int64:
     cand_job     sum of cand_job * (g + 1)
     cand_cut     sum of cand_cut * (g + 1)
     cand_score   sum of cand_score
+With --resolve, "resolve" holds, for the round cap of the config and for 0 (until stable): rounds, stable,
+the number of grants and sum grant_job * (g + 1), sum grant_cut * (g + 1), sum grant_score,
+sum job_gap * (j + 1), all in wrapping int64.
 """
 import json
 import os
@@ -39,14 +44,28 @@ def block_digest(cut, g0, cand_job, cand_cut, cand_score):
                 "cand_score": int(cand_score.sum(dtype=np.int64))}
 
 
+def grant_digest(gj, gc, gs, jg, rounds, stable):
+    gw = np.arange(1, len(gj) + 1, dtype=np.int64)
+    jw = np.arange(1, len(jg) + 1, dtype=np.int64)
+    with np.errstate(over="ignore"):
+        return {"rounds": int(rounds), "stable": int(stable), "grants": int((gj >= 0).sum()),
+                "grant_job": int((gj.astype(np.int64) * gw).sum(dtype=np.int64)),
+                "grant_cut": int((gc.astype(np.int64) * gw).sum(dtype=np.int64)),
+                "grant_score": int(gs.sum(dtype=np.int64)),
+                "job_gap": int((jg.astype(np.int64) * jw).sum(dtype=np.int64))}
+
+
 def main(names):
     import oracle as O
     from gen import make_workload
+    with_resolve = "--resolve" in names
+    names = [n for n in names if not n.startswith("--")] or ["large", "stress"]
     for name in names:
         wl = make_workload(name, 0)
         par = O.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
         pd, pp, _ = O.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
         blocks = []
+        whole = np.empty((wl.n_gaps, wl.n_jobs), dtype=np.int32) if with_resolve else None
         t0 = time.time()
         for g0 in range(0, wl.n_gaps, BLOCK):
             W = np.ascontiguousarray(wl.W[g0:g0 + BLOCK])
@@ -54,11 +73,20 @@ def main(names):
             cut, _ = O.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, W, C, False)
             cj, cc, cs = O.select(cut, wl.seg_off, pd, pp, par, wl.wait, wl.sla_class)
             blocks.append(block_digest(cut, g0, cj, cc, cs))
+            if whole is not None:
+                whole[g0:g0 + BLOCK] = cut
             if (g0 // BLOCK) % 16 == 0:
                 print(f"{name}: gap {g0} of {wl.n_gaps}, {time.time() - t0:.0f} s", flush=True)
         out = {"config": name, "seed": 0, "n_gaps": wl.n_gaps, "n_jobs": wl.n_jobs, "policy": int(wl.policy),
                "block": BLOCK, "source": "oracle/ (sjo_fit, sjo_select), written by tests/golden/make_fullsize_digest.py",
                "blocks": blocks}
+        if whole is not None:
+            out["resolve"] = {}
+            for cap in sorted({int(wl.max_rounds), 0}, reverse=True):
+                p2 = O.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, cap)
+                res = O.resolve(whole, wl.seg_off, pd, pp, p2, wl.wait, wl.sla_class)
+                out["resolve"][str(cap)] = grant_digest(*res)
+                print(f"{name}: resolve cap {cap}: {res[4]} rounds, {time.time() - t0:.0f} s", flush=True)
         path = os.path.join(ROOT, "tests", "golden", f"fullsize_digest_{name}.json")
         with open(path, "w") as f:
             json.dump(out, f, indent=0)
@@ -66,4 +94,4 @@ def main(names):
 
 
 if __name__ == "__main__":
-    main(sys.argv[1:] or ["large", "stress"])
+    main(sys.argv[1:])

@@ -301,6 +301,18 @@ def test_whole_outputs_match_the_oracle_digests(name):
     torch.cuda.synchronize()
     for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
         assert torch.equal(a, b)
+    # the grants of every gap, with the config's round cap and until stable
+    gw = torch.arange(1, wl.n_gaps + 1, dtype=torch.int64, device="cuda:0")
+    jw = torch.arange(1, wl.n_jobs + 1, dtype=torch.int64, device="cuda:0")
+    for cap, want in gold.get("resolve", {}).items():
+        t.resolve(P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, int(cap)))
+        rounds, stable = t.rounds.cpu().tolist()
+        got_r = {"rounds": rounds, "stable": stable, "grants": int((t.grant_job >= 0).sum().item()),
+                 "grant_job": int((t.grant_job.to(torch.int64) * gw).sum().item()),
+                 "grant_cut": int((t.grant_cut.to(torch.int64) * gw).sum().item()),
+                 "grant_score": int(t.grant_score.sum().item()),
+                 "job_gap": int((t.job_gap.to(torch.int64) * jw).sum().item())}
+        assert got_r == want, f"round cap {cap}"
 
 
 def test_beyond_stress_64bit_indexing(oracle):
