@@ -287,3 +287,25 @@ def test_fused_then_matrix_rounds_is_refused(engine):
     finally:
         engine.sja_set_resolve_mode(0)
     torch.cuda.synchronize()
+
+
+def test_random_small_shapes(engine, oracle):
+    """Sixty random shapes from one gap x one job to 130 x 400, every generator, every policy:
+    the whole tick in both resolve modes, and the fused call with resolve on top of it."""
+    rng = np.random.default_rng(20240)
+    names = ["tiny", "small", "medium", "large", "stress"]
+    for case in range(60):
+        name = names[case % len(names)]
+        G = int(rng.integers(1, 131))
+        J = int(rng.integers(1, 401))
+        if case % 7 == 0:
+            G, J = (1, J) if case % 14 == 0 else (G, 1)
+        wl = make_workload(name, 100 + case, n_gaps=G, n_jobs=J)
+        if case % 5 == 0:                                   # windows and capacities from zero up: many declines
+            wl.W = np.ascontiguousarray((wl.W * rng.random(G)).astype(np.int32))
+            wl.C = np.ascontiguousarray((wl.C * rng.random(G)).astype(np.int32))
+        policy = int(rng.integers(0, 4))
+        wl.max_rounds = int(rng.integers(0, 4)) if case % 3 == 0 else 0
+        full_tick_check(engine, oracle, wl, policies=[policy])
+        # with more than 64 distinct capacities the rounds scan the matrix, which the fused call never writes
+        fused_check(engine, oracle, wl, [policy], resolve=len(np.unique(wl.C)) <= 64)
