@@ -204,7 +204,9 @@ def measure_extras(args, wl, eng, tick, par):
     # grants, advance), the job tables carried over instead of prepared again
     chain_gaps = [(tick.W, tick.C)] + [tuple(torch.from_numpy(a).cuda() for a in
                                              make_gaps(args.workload, args.seed, k)) for k in range(1, args.chain_ticks)]
-    chain = {"tick_ms": [], "advance_ms": [], "grants": [], "rounds": [], "utilisation": []}
+    chain = {"tick_ms": [], "advance_ms": [], "grants": [], "rejected_gaps": [], "finished_jobs": [], "rounds": [],
+             "utilisation": [], "mean_wait_of_unfinished_jobs": []}
+    lens = torch.from_numpy(np.diff(wl.seg_off).astype(np.int32)).cuda()
     tick.prepare()
     for W_k, C_k in chain_gaps:
         tick.W, tick.C = W_k, C_k
@@ -216,6 +218,11 @@ def measure_extras(args, wl, eng, tick, par):
         chain["tick_ms"].append(e[0].elapsed_time(e[2]))
         chain["advance_ms"].append(e[1].elapsed_time(e[2]))
         chain["grants"].append(m[2])
+        chain["rejected_gaps"].append(wl.n_gaps - m[2])
+        chain["finished_jobs"].append(m[3])
+        open_jobs = tick.progress < lens
+        chain["mean_wait_of_unfinished_jobs"].append(
+            float(tick.wait[open_jobs].double().mean().item()) if bool(open_jobs.any()) else None)
         chain["rounds"].append(tick.rounds.cpu().tolist()[0])
         chain["utilisation"].append(m[0] / m[1] if m[1] else None)
     # the tick's front half under admission limits, and the covering-capacity map
@@ -228,6 +235,7 @@ def measure_extras(args, wl, eng, tick, par):
     slack = torch.empty_like(cover)
     tick.W, tick.C = chain_gaps[0]
     tick.progress.copy_(torch.from_numpy(wl.progress))
+    tick.wait.copy_(torch.from_numpy(wl.wait))
     limited = {"prepare_ms": [], "fit_select_ms": [], "cover_ms": []}
     eng.sja_set_limits(P.Limits.make(**lim_kw), d_power, d_deadline)
     try:
