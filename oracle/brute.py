@@ -46,8 +46,10 @@ def fit_all(seg_off, dur, mem, safe, progress, W, C) -> List[List[int]]:
 
 
 def key_of(policy: int, sub_dur: int, sub_peak: int, wait: int, cls: int, wait_scale: int,
-           sla_weight: Sequence[int], class0_override: int) -> Tuple[int, int, int]:
-    F = sub_dur * sub_peak
+           sla_weight: Sequence[int], class0_override: int, F: Optional[int] = None) -> Tuple[int, int, int]:
+    """F defaults to the rectangle duration x peak; the area variant passes its own F."""
+    if F is None:
+        F = sub_dur * sub_peak
     if policy == EFFICIENCY:
         return (0, F, 0)
     if policy == FAIRNESS:
@@ -61,8 +63,9 @@ def key_of(policy: int, sub_dur: int, sub_peak: int, wait: int, cls: int, wait_s
 
 def select_gap(cut_row, seg_off, dur, mem, progress, wait, sla_class, policy,
                wait_scale=1000, sla_weight=(4, 2, 1), class0_override=1,
-               held: Optional[set] = None):
-    """(job, cut, score) for one gap: sort every candidate, take the first."""
+               held: Optional[set] = None, by_area: bool = False):
+    """(job, cut, score) for one gap: sort every candidate, take the first.
+    by_area: F = sum of dur * mem over the subjob instead of its duration x peak."""
     cands = []
     for j, c in enumerate(cut_row):
         if c < 0 or (held is not None and j in held):
@@ -70,8 +73,9 @@ def select_gap(cut_row, seg_off, dur, mem, progress, wait, sla_class, policy,
         d = job_slices(seg_off, dur, j)
         m = job_slices(seg_off, mem, j)
         p = int(progress[j])
+        F = sum(x * y for x, y in zip(d[p:c], m[p:c])) if by_area else None
         key = key_of(policy, sum(d[p:c]), max(m[p:c]), int(wait[j]), int(sla_class[j]),
-                     wait_scale, sla_weight, class0_override)
+                     wait_scale, sla_weight, class0_override, F)
         cands.append((key, j, c))
     if not cands:
         return (-1, -1, 0)
@@ -81,7 +85,7 @@ def select_gap(cut_row, seg_off, dur, mem, progress, wait, sla_class, policy,
 
 
 def resolve(cut, seg_off, dur, mem, progress, wait, sla_class, policy, max_rounds=0,
-            wait_scale=1000, sla_weight=(4, 2, 1), class0_override=1):
+            wait_scale=1000, sla_weight=(4, 2, 1), class0_override=1, by_area: bool = False):
     """Literal simulation of the grant rounds with explicit sets."""
     G = len(cut)
     J = len(seg_off) - 1
@@ -96,7 +100,7 @@ def resolve(cut, seg_off, dur, mem, progress, wait, sla_class, policy, max_round
             if grant[g] is not None:
                 continue
             j, c, s = select_gap(cut[g], seg_off, dur, mem, progress, wait, sla_class, policy,
-                                 wait_scale, sla_weight, class0_override, held)
+                                 wait_scale, sla_weight, class0_override, held, by_area)
             if j >= 0:
                 choice[g] = (j, c, s)
         rounds += 1

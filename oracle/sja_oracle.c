@@ -106,6 +106,32 @@ int sjo_prepare(int32_t n_jobs, const int64_t *seg_off, const int32_t *dur,
 }
 
 /* ------------------------------------------------------------------------
+ * Area under the envelope from the progress point: pre_area[k] = sum over
+ * segments p..k of dur * mem, the memory-time a subjob ending after segment k
+ * really uses (the alternative reading of "filled capacity-time"; the default
+ * is the rectangle duration * peak).
+ * ---------------------------------------------------------------------- */
+int sjo_area(int32_t n_jobs, const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+             const int32_t *progress, int64_t *pre_area)
+{
+    if (n_jobs < 0) return SJO_ERR_ARG;
+    for (int32_t j = 0; j < n_jobs; ++j) {
+        int64_t base = seg_off[j];
+        int64_t L = seg_off[j + 1] - base;
+        int64_t p = progress[j];
+        if (L < 0 || p < 0 || p > L) return SJO_ERR_ARG;
+        int64_t area = 0;
+        for (int64_t k = base + p; k < base + L; ++k) {
+            int64_t term;
+            if (__builtin_mul_overflow((int64_t)dur[k], (int64_t)mem[k], &term) ||
+                __builtin_add_overflow(area, term, &area)) return SJO_ERR_OVERFLOW;
+            pre_area[k] = area;
+        }
+    }
+    return SJO_OK;
+}
+
+/* ------------------------------------------------------------------------
  * Optional admission limits on top of the gap's own window and capacity:
  *   - a power trace with a cap in force for the tick: the subjob's peak power
  *     must stay <= power_cap (Sec. 4.4, energy-aware admission: the same
@@ -278,11 +304,9 @@ static int key_greater(const sjo_key *a, const sjo_key *b)
     return a->k2 > b->k2;
 }
 
-static int make_key(const sjo_params *pp, int64_t sub_dur, int64_t sub_peak, int64_t wait,
-                    int32_t cls, sjo_key *key)
+static int make_key(const sjo_params *pp, int64_t F, int64_t wait, int32_t cls, sjo_key *key)
 {
-    int64_t F, s;
-    if (__builtin_mul_overflow(sub_dur, sub_peak, &F)) return SJO_ERR_OVERFLOW;
+    int64_t s;
     switch (pp->policy) {
     case SJO_EFFICIENCY:
         key->k0 = 0; key->k1 = F; key->k2 = 0;
@@ -310,7 +334,7 @@ static int make_key(const sjo_params *pp, int64_t sub_dur, int64_t sub_peak, int
  * only when its key is strictly greater (so the lowest id wins ties). */
 static int select_gap(const sjo_params *pp, int32_t n_jobs, const int32_t *cut_row,
                       const int64_t *seg_off, const int64_t *pre_dur, const int64_t *pre_peak,
-                      const int32_t *wait, const uint8_t *sla_class, const int32_t *job_held,
+                      const int64_t *pre_area, const int32_t *wait, const uint8_t *sla_class, const int32_t *job_held,
                       int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score)
 {
     sjo_key best = {0, 0, 0};
@@ -321,8 +345,10 @@ static int select_gap(const sjo_params *pp, int32_t n_jobs, const int32_t *cut_r
         if (job_held && job_held[j] >= 0) continue;
         int64_t k = seg_off[j] + c - 1;
         sjo_key key;
-        int rc = make_key(pp, pre_dur[k], pre_peak[k], wait ? wait[j] : 0,
-                          sla_class ? sla_class[j] : 0, &key);
+        int64_t F;
+        if (pre_area) F = pre_area[k];
+        else if (__builtin_mul_overflow(pre_dur[k], pre_peak[k], &F)) return SJO_ERR_OVERFLOW;
+        int rc = make_key(pp, F, wait ? wait[j] : 0, sla_class ? sla_class[j] : 0, &key);
         if (rc != SJO_OK) return rc;
         if (bj < 0 || key_greater(&key, &best)) { best = key; bj = j; bc = c; }
     }
@@ -333,11 +359,13 @@ static int select_gap(const sjo_params *pp, int32_t n_jobs, const int32_t *cut_r
 }
 
 /* Per-gap policy arg-max over interested, un-held jobs.  pre_dur / pre_peak are
- * sjo_prepare's outputs (looked up at the cut).  job_held (may be NULL): a job
+ * sjo_prepare's outputs (looked up at the cut).  pre_area (may be NULL) switches
+ * the filled capacity-time F from the rectangle duration * peak to the area
+ * under the envelope, sjo_area's output.  job_held (may be NULL): a job
  * with job_held[j] >= 0 is skipped.  gap_active (may be NULL): a gap with
  * gap_active[g] == 0 gets cand_job = cand_cut = -1, cand_score = 0. */
 int sjo_select(int32_t n_gaps, int32_t n_jobs, const int32_t *cut, const int64_t *seg_off,
-               const int64_t *pre_dur, const int64_t *pre_peak, const sjo_params *pp,
+               const int64_t *pre_dur, const int64_t *pre_peak, const int64_t *pre_area, const sjo_params *pp,
                const int32_t *wait, const uint8_t *sla_class, const int32_t *job_held,
                const uint8_t *gap_active, int32_t *cand_job, int32_t *cand_cut,
                int64_t *cand_score)
@@ -351,7 +379,7 @@ int sjo_select(int32_t n_gaps, int32_t n_jobs, const int32_t *cut, const int64_t
             cand_job[g] = -1; cand_cut[g] = -1; cand_score[g] = 0;
             continue;
         }
-        int rc = select_gap(pp, n_jobs, cut + (int64_t)g * n_jobs, seg_off, pre_dur, pre_peak,
+        int rc = select_gap(pp, n_jobs, cut + (int64_t)g * n_jobs, seg_off, pre_dur, pre_peak, pre_area,
                             wait, sla_class, job_held, &cand_job[g], &cand_cut[g],
                             &cand_score[g]);
         if (rc != SJO_OK) {
@@ -371,7 +399,7 @@ int sjo_select(int32_t n_gaps, int32_t n_jobs, const int32_t *cut, const int64_t
  * if the process ended by itself, 0 if the round cap cut it short.
  * ---------------------------------------------------------------------- */
 int sjo_resolve(int32_t n_gaps, int32_t n_jobs, const int32_t *cut, const int64_t *seg_off,
-                const int64_t *pre_dur, const int64_t *pre_peak, const sjo_params *pp,
+                const int64_t *pre_dur, const int64_t *pre_peak, const int64_t *pre_area, const sjo_params *pp,
                 const int32_t *wait, const uint8_t *sla_class, int32_t *grant_job,
                 int32_t *grant_cut, int64_t *grant_score, int32_t *job_gap,
                 int32_t *rounds_stable)
@@ -392,7 +420,7 @@ int sjo_resolve(int32_t n_gaps, int32_t n_jobs, const int32_t *cut, const int64_
     int rc = SJO_OK;
     for (int64_t r = 1; r <= cap; ++r) {
         for (int32_t g = 0; g < n_gaps; ++g) active[g] = grant_job[g] < 0;
-        rc = sjo_select(n_gaps, n_jobs, cut, seg_off, pre_dur, pre_peak, pp, wait, sla_class,
+        rc = sjo_select(n_gaps, n_jobs, cut, seg_off, pre_dur, pre_peak, pre_area, pp, wait, sla_class,
                         job_gap, active, cj, cc, cs);
         if (rc != SJO_OK) break;
         ++rounds;

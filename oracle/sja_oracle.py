@@ -95,6 +95,16 @@ def prepare(seg_off, dur, mem, safe, progress, fill: int = -7):
     return pre_dur, pre_peak, prev_safe
 
 
+def area(seg_off, dur, mem, progress, fill: int = -7):
+    """pre_area int64 [S]: area under the envelope from each job's progress point; untouched = fill."""
+    J = len(seg_off) - 1
+    out = np.full(int(seg_off[-1]), fill, dtype=np.int64)
+    rc = _load().sjo_area(ctypes.c_int32(J), _p(seg_off, np.int64), _p(dur, np.int32), _p(mem, np.int32),
+                          _p(progress, np.int32), _p(out, np.int64))
+    _check(rc, "sjo_area")
+    return out
+
+
 class Limits(ctypes.Structure):
     """Mirror of sjo_limits (admission limits of Sec. 4.3 / 4.4)."""
     _fields_ = [("tau_min", ctypes.c_int32), ("tau_max", ctypes.c_int32),
@@ -186,14 +196,16 @@ def fit_pairs(gap_idx, job_idx, seg_off, dur, mem, safe, progress, W, C):
 
 
 def select(cut, seg_off, pre_dur, pre_peak, params: Params, wait, sla_class,
-           job_held=None, gap_active=None):
-    """Returns (cand_job int32 [G], cand_cut int32 [G], cand_score int64 [G])."""
+           job_held=None, gap_active=None, pre_area=None):
+    """Returns (cand_job int32 [G], cand_cut int32 [G], cand_score int64 [G]).
+    pre_area (from area()) scores by the area under the envelope instead of duration x peak."""
     G, J = cut.shape
     cj = np.empty(G, dtype=np.int32)
     cc = np.empty(G, dtype=np.int32)
     cs = np.empty(G, dtype=np.int64)
     rc = _load().sjo_select(ctypes.c_int32(G), ctypes.c_int32(J), _p(cut, np.int32),
                             _p(seg_off, np.int64), _p(pre_dur, np.int64), _p(pre_peak, np.int64),
+                            _p(pre_area, np.int64),
                             ctypes.byref(params), _p(wait, np.int32), _p(sla_class, np.uint8),
                             _p(job_held, np.int32), _p(gap_active, np.uint8),
                             _p(cj, np.int32), _p(cc, np.int32), _p(cs, np.int64))
@@ -201,7 +213,7 @@ def select(cut, seg_off, pre_dur, pre_peak, params: Params, wait, sla_class,
     return cj, cc, cs
 
 
-def resolve(cut, seg_off, pre_dur, pre_peak, params: Params, wait, sla_class):
+def resolve(cut, seg_off, pre_dur, pre_peak, params: Params, wait, sla_class, pre_area=None):
     """Returns (grant_job, grant_cut, grant_score, job_gap, rounds_used, stable)."""
     G, J = cut.shape
     gj = np.empty(G, dtype=np.int32)
@@ -211,7 +223,8 @@ def resolve(cut, seg_off, pre_dur, pre_peak, params: Params, wait, sla_class):
     rs = np.zeros(2, dtype=np.int32)
     rc = _load().sjo_resolve(ctypes.c_int32(G), ctypes.c_int32(J), _p(cut, np.int32),
                              _p(seg_off, np.int64), _p(pre_dur, np.int64),
-                             _p(pre_peak, np.int64), ctypes.byref(params), _p(wait, np.int32),
+                             _p(pre_peak, np.int64), _p(pre_area, np.int64), ctypes.byref(params),
+                             _p(wait, np.int32),
                              _p(sla_class, np.uint8), _p(gj, np.int32), _p(gc, np.int32),
                              _p(gs, np.int64), _p(jg, np.int32), _p(rs, np.int32))
     _check(rc, "sjo_resolve")
