@@ -267,7 +267,28 @@ def measure_extras(args, wl, eng, tick, par):
     chain["note"] = ("sja_fit_select + sja_resolve + sja_advance per tick, new gaps every tick, no prepare "
                      "after the first; not part of the timed step")
 
+    # the same front half with the area-under-the-envelope score
+    tick.progress.copy_(torch.from_numpy(wl.progress))
+    tick.wait.copy_(torch.from_numpy(wl.wait))
+    by_area = {"prepare_ms": [], "fit_select_ms": []}
+    eng.sja_set_score(1)
+    try:
+        for i in range(reps + 1):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(); tick.prepare()
+            e[1].record(); tick.fit_select(par)
+            e[2].record(); e[2].synchronize()
+            if i:
+                by_area["prepare_ms"].append(e[0].elapsed_time(e[1]))
+                by_area["fit_select_ms"].append(e[1].elapsed_time(e[2]))
+        tick.resolve(par)
+        by_area = {k: sum(v) / len(v) for k, v in by_area.items()}
+        by_area.update({"rounds": tick.rounds.cpu().tolist()[0], "grants": int((tick.grant_job >= 0).sum().item()),
+                        "note": "sja_set_score(SJA_SCORE_AREA): F = area under the envelope; not part of the timed step"})
+    finally:
+        eng.sja_set_score(0)
     return {
+        "area_score": by_area,
         "fused_fit_select": {"call_ms": sum(fused_ms) / len(fused_ms),
                              "kernel_ms": sum(fused_kernel_ms) / len(fused_kernel_ms),
                              "evals_per_s": pairs / (sum(fused_ms) / len(fused_ms) * 1e-3),

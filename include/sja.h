@@ -130,6 +130,24 @@ const char *sja_status_string(int status);
 const char *sja_last_error(const sja_ctx *ctx);
 
 /*
+ * Which quantity the policies score as the "filled capacity-time" F of a
+ * subjob (the paper names the notion and leaves its formula open):
+ *   SJA_SCORE_RECTANGLE  duration x peak memory: the rectangle the subjob's
+ *                        footprint occupies in the gap (the default)
+ *   SJA_SCORE_AREA       sum of dur x mem over the subjob's segments: the area
+ *                        under its memory envelope, never above the rectangle
+ * Takes effect at the next sja_prepare_profiles (which then also keeps running
+ * area tables in the workspace) and holds for the sja_select, sja_fit_select,
+ * sja_resolve and sja_advance calls on top of it.  Keys, tie rules and the
+ * score bound are unchanged.  SJA_ERR_SIZE for any other value.
+ */
+typedef enum {
+    SJA_SCORE_RECTANGLE = 0,
+    SJA_SCORE_AREA = 1
+} sja_score;
+int sja_set_score(sja_ctx *ctx, int score);
+
+/*
  * Admission limits on top of each gap's own window and capacity.  All are off
  * in a new context.
  *   - power trace with a cap (Sec. 4.4, energy-aware admission: the subjob's

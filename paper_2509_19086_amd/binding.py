@@ -83,6 +83,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_fit_select.argtypes = [vp, vp, i32, vp, vp, ctypes.POINTER(Params)] + [vp] * 7
     lib.sja_fit_select.restype = ctypes.c_int
     lib.sja_resolve.restype = ctypes.c_int
+    lib.sja_set_score.argtypes = [vp, ctypes.c_int]
+    lib.sja_set_score.restype = ctypes.c_int
     lib.sja_set_limits.argtypes = [vp, ctypes.POINTER(Limits), vp, vp]
     lib.sja_set_limits.restype = ctypes.c_int
     lib.sja_cover.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp, vp]
@@ -234,6 +236,9 @@ class Engine:
                                    _ptr(wait, torch.int32, J), _ptr(sla_class, torch.uint8, J),
                                    _ptr(problems, torch.int32, 1))
         self._check(rc, self.h)
+
+    def sja_set_score(self, score: int) -> None:
+        self._check(self.lib.sja_set_score(self.h, int(score)), self.h)
 
     def sja_set_limits(self, limits, power=None, deadline=None):
         """limits: a Limits or None (clear).  power / deadline: device int32 tensors or None;

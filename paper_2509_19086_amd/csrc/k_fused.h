@@ -42,10 +42,13 @@ __device__ __forceinline__ unsigned long long fused_readlane_u64(unsigned long l
 
 // Eight waves per SIMD (64 registers, a few spilled) beat the 94 registers the
 // compiler takes by itself: the stepping loop is bound by latency (1.5 against 2.1 ms).
-template <int BLOCK, int CAP, int PERIOD, bool MIXED>
+// AREA: the key's F is the atom's area under the envelope (a second window of
+// 64-bit values beside the (duration, peak) one) instead of duration x peak.
+template <int BLOCK, int CAP, int PERIOD, bool MIXED, bool AREA>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_fit_select(
     int n_jobs, int n_gaps, int chunk_bound, PolicyDev pol, const int64_t *__restrict__ seg_off,
-    const int2 *__restrict__ atom_dp, const int32_t *__restrict__ n_atoms,
+    const int2 *__restrict__ atom_dp, const long long *__restrict__ atom_area,
+    const int32_t *__restrict__ n_atoms,
     const int32_t *__restrict__ plan, const int32_t *__restrict__ chunk_begin,
     const int32_t *__restrict__ chunk_end, const int32_t *__restrict__ chunk_class,
     const int32_t *__restrict__ chunk_sub, const int32_t *__restrict__ start_tab,
@@ -59,6 +62,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
     static_assert((CAP & (CAP - 1)) == 0 && BLOCK % kWave == 0 && PERIOD <= 64, "tile shape");
     constexpr int WAVES = BLOCK / kWave;
     __shared__ int2 win[CAP][BLOCK];
+    __shared__ long long win_area[AREA ? CAP : 1][AREA ? BLOCK : 1];
     // per wave and period: the steps at which its running best changed, with the new best
     __shared__ unsigned long long e_hi[WAVES][PERIOD + 1];
     __shared__ unsigned long long e_lo[WAVES][PERIOD + 1];
@@ -82,6 +86,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
     const int64_t base = seg_off[j];
     const int n = usable ? n_atoms[j] : 0;
     const int2 *dp = atom_dp + base;
+    const long long *da = atom_area + base;        // read with AREA only
     unsigned long long mult = 1, tier = 0;
     job_policy(pol, wait, sla_class, j, mult, tier);
     const int s_begin = chunk_begin[chunk], s_end = chunk_end[chunk];
@@ -119,10 +124,15 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
         ++n_events;
     };
 
-    auto key_of = [&](int d, int p) {
-        const unsigned long long F = (unsigned long long)d * (unsigned long long)p;
+    auto key_from = [&](unsigned long long F) {
         key_hi = ((tier << 62) | (F * mult)) + 1ull;
         key_lo = MIXED ? F : 0ull;
+    };
+    // key of the atom just passed: a - 1, whose window slot is still intact (a top-up writes at most
+    // up to atom a + CAP - 1)
+    auto key_of = [&](int d, int p) {
+        if (AREA) key_from((unsigned long long)win_area[(a - 1) & (CAP - 1)][tid]);
+        else key_from((unsigned long long)d * (unsigned long long)p);
     };
     // a key changed in the lanes of `ch` (those that can matter): move the running best
     auto challenge = [&](bool in) {
@@ -174,7 +184,14 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
             a = upper_bound_dur(dp, n_cap, gap_w[s]);
         }
         key_hi = 0; key_lo = 0;
-        if (a > 0) { const int2 v = dp[a - 1]; key_of(v.x, v.y); }
+        if (a > 0) {
+            if (AREA) {
+                key_from((unsigned long long)da[a - 1]);
+            } else {
+                const int2 v = dp[a - 1];
+                key_from((unsigned long long)v.x * (unsigned long long)v.y);
+            }
+        }
         hi = a;
         best_hi = 0; best_lo = 0; best_lane = kWave; best_atoms = 0;
         note();
@@ -193,6 +210,9 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
 #pragma unroll
         for (int t = 0; t < CAP; ++t)
             if (hi + t < want) win[(hi + t) & (CAP - 1)][tid] = v[t];
+        if (AREA) {
+            for (int idx = hi; idx < want; ++idx) win_area[idx & (CAP - 1)][tid] = da[idx];
+        }
         hi = max(hi, want);
         reload();
     };
@@ -212,8 +232,12 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
                 if (__ballot(a == hi) & dry_mask) {
                     // a window ran dry inside a period: refill at once (rare)
                     if (a == hi && hi < n_cap) {
-                        const int want = min(a + CAP, n_cap);
-                        for (int idx = hi; idx < want; ++idx) win[idx & (CAP - 1)][tid] = dp[idx];
+                        // with AREA one slot stays back: atom a - 1 shares its slot with atom a + CAP - 1
+                        const int want = min(a + CAP - (AREA ? 1 : 0), n_cap);
+                        for (int idx = hi; idx < want; ++idx) {
+                            win[idx & (CAP - 1)][tid] = dp[idx];
+                            if (AREA) win_area[idx & (CAP - 1)][tid] = da[idx];
+                        }
                         hi = want;
                         reload();
                     }

@@ -76,7 +76,7 @@ __global__ void k_reach(int n_jobs, const int32_t *__restrict__ plan, const int3
 // of the inverted key = descending key) and the identity permutation.
 __global__ __launch_bounds__(256) void k_atom_keys(
     int n_jobs, PolicyDev pol, const int64_t *__restrict__ seg_off, const int2 *__restrict__ atom_dp,
-    const int32_t *__restrict__ abase, const int32_t *__restrict__ wait,
+    const long long *__restrict__ atom_area, const int32_t *__restrict__ abase, const int32_t *__restrict__ wait,
     const uint8_t *__restrict__ sla_class, unsigned long long *__restrict__ key_hi,
     unsigned long long *__restrict__ key_lo, uint32_t *__restrict__ perm, int2 *__restrict__ atom_ja)
 {
@@ -84,13 +84,15 @@ __global__ __launch_bounds__(256) void k_atom_keys(
     if (j >= n_jobs) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int a0 = abase[j], n = abase[j + 1] - a0;
-    const int2 *dp = atom_dp + seg_off[j];
+    const int64_t base = seg_off[j];
+    const int2 *dp = atom_dp + base;
     unsigned long long mult, tier;
     job_policy(pol, wait, sla_class, j, mult, tier);
     const bool mixed = pol.policy == SJA_POLICY_MIXED;
     for (int a = lane; a < n; a += kWave) {
         const int2 v = dp[a];
-        const unsigned long long F = (unsigned long long)v.x * (unsigned long long)v.y;
+        const unsigned long long F = atom_area ? (unsigned long long)atom_area[base + a]
+                                               : (unsigned long long)v.x * (unsigned long long)v.y;
         key_hi[a0 + a] = ~((tier << 62) | (F * mult));
         key_lo[a0 + a] = ~(mixed ? F : 0ull);
         perm[a0 + a] = uint32_t(a0 + a);
@@ -508,6 +510,7 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
 __global__ void k_grant_finish(int lb_cap, PolicyDev pol, const int32_t *__restrict__ plan,
                                const int4 *__restrict__ state, const int64_t *__restrict__ seg_off,
                                const int2 *__restrict__ atom_dp, const int2 *__restrict__ atom_db,
+                               const long long *__restrict__ atom_area,
                                const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
                                int32_t *grant_job, int32_t *grant_cut, int64_t *grant_score,
                                int32_t *job_gap)
@@ -523,7 +526,9 @@ __global__ void k_grant_finish(int lb_cap, PolicyDev pol, const int32_t *__restr
     job_policy(pol, wait, sla_class, j, mult, tier);
     grant_job[g] = j;
     grant_cut[g] = atom_db[base + st.z].y;
-    grant_score[g] = int64_t((unsigned long long)v.x * (unsigned long long)v.y * mult);
+    const unsigned long long F = atom_area ? (unsigned long long)atom_area[base + st.z]
+                                           : (unsigned long long)v.x * (unsigned long long)v.y;
+    grant_score[g] = int64_t(F * mult);
     job_gap[j] = g;
 }
 

@@ -48,6 +48,16 @@ int fail_hip(sja_ctx *ctx, hipError_t e, const char *what)
 template <typename T>
 T *ws_ptr(sja_ctx *ctx, size_t off) { return reinterpret_cast<T *>(ctx->ws + off); }
 
+// The area tables exist (and are read) only while the area score is in force.
+const long long *atom_area_of(const sja_ctx *ctx, const Layout &L)
+{
+    return ctx->score_used == SJA_SCORE_AREA ? reinterpret_cast<const long long *>(ctx->ws + L.atom_area) : nullptr;
+}
+const long long *pre_area_of(const sja_ctx *ctx, const Layout &L)
+{
+    return ctx->score_used == SJA_SCORE_AREA ? reinterpret_cast<const long long *>(ctx->ws + L.pre_area) : nullptr;
+}
+
 int check_params(sja_ctx *ctx, const sja_params *p, const int32_t *wait, const uint8_t *sla_class)
 {
     if (!p) return fail(ctx, SJA_ERR_NULL, "params");
@@ -89,9 +99,11 @@ int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const 
         const int n_chunks = (G + kSelGapChunk - 1) / kSelGapChunk;
         const int tiles8 = (job_tiles + 7) / 8 * 8;
         const unsigned grid = unsigned(tiles8) * unsigned(n_chunks);
-        auto kern = params->policy == SJA_POLICY_MIXED ? k_select_pass<true> : k_select_pass<false>;
+        const bool mixed = params->policy == SJA_POLICY_MIXED;
+        auto kern = pre_area_of(ctx, L) ? (mixed ? k_select_pass<true, true> : k_select_pass<false, true>)
+                                        : (mixed ? k_select_pass<true, false> : k_select_pass<false, false>);
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kSelBlock), 0, st, J, G, n_chunks,
-                           to_dev(params), ctx->seg_off, ctx->pre_dur, ctx->pre_peak, ctx->cut,
+                           to_dev(params), ctx->seg_off, ctx->pre_dur, ctx->pre_peak, pre_area_of(ctx, L), ctx->cut,
                            ws_ptr<int32_t>(ctx, L.gap_order), wait, sla_class, job_held, gap_active,
                            ws_ptr<SelPartial>(ctx, L.sel_part));
         SJA_HIP(hipGetLastError(), "k_select_pass launch");
@@ -190,7 +202,8 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(hipGetLastError(), "k_reach launch");
     SJA_HIP(enqueue_scan(st, abase, int64_t(J) + 1, tmp, counters + 2), "atom scan launch");
     // policy keys of the atoms and the bytes in which they differ (both only need the device-side counts)
-    hipLaunchKernelGGL(k_atom_keys, dim3((J + 3) / 4), dim3(256), 0, st, J, pol, ctx->seg_off, atom_dp, abase, wait,
+    hipLaunchKernelGGL(k_atom_keys, dim3((J + 3) / 4), dim3(256), 0, st, J, pol, ctx->seg_off, atom_dp,
+                       atom_area_of(ctx, L), abase, wait,
                        sla_class, key_hi, key_lo, perm[0], atom_ja);
     SJA_HIP(hipGetLastError(), "k_atom_keys launch");
     hipLaunchKernelGGL(k_key_bits, dim3(256), dim3(256), 0, st, counters + 2, key_hi, key_lo,
@@ -307,7 +320,8 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
         }
     }
     hipLaunchKernelGGL(k_grant_finish, dim3(unsigned((int64_t(n_subs) * kWave + 255) / 256)), dim3(256), 0, st, lb_bound, pol,
-                       plan, state, ctx->seg_off, atom_dp, atom_db, wait, sla_class, grant_job, grant_cut, grant_score,
+                       plan, state, ctx->seg_off, atom_dp, atom_db, atom_area_of(ctx, L), wait, sla_class, grant_job,
+                       grant_cut, grant_score,
                        job_gap);
     SJA_HIP(hipGetLastError(), "k_grant_finish launch");
     *done = true;
@@ -489,6 +503,14 @@ int sja_last_fit_kernel_ms(sja_ctx *ctx, float *ms_host)
     return SJA_OK;
 }
 
+int sja_set_score(sja_ctx *ctx, int score)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (score != SJA_SCORE_RECTANGLE && score != SJA_SCORE_AREA) return fail(ctx, SJA_ERR_SIZE, "unknown score");
+    ctx->score_mode = score;
+    return SJA_OK;
+}
+
 int sja_set_limits(sja_ctx *ctx, const sja_limits *limits, const int32_t *power, const int32_t *deadline)
 {
     if (!ctx) return SJA_ERR_NULL;
@@ -529,14 +551,17 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
     if (n_jobs > 0) {
         const int jobs_per_block = 256 / kWave;
         const dim3 grid((n_jobs + jobs_per_block - 1) / jobs_per_block), block(256);
+        const bool by_area = ctx->score_mode == SJA_SCORE_AREA;
+        long long *pre_area = by_area ? ws_ptr<long long>(ctx, L.pre_area) : nullptr;
+        long long *atom_area = by_area ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
         if (ctx->limits_on) {
             const JobLimits lim = job_limits(ctx->limits, ctx->lim_power, ctx->lim_deadline);
-            hipLaunchKernelGGL(k_prepare<true>, grid, block, 0, st, lim, n_jobs, seg_off, dur, mem, safe, progress,
+            hipLaunchKernelGGL(k_prepare<true>, grid, block, 0, st, lim, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe, progress,
                                pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
                                ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int2>(ctx, L.first_dp));
         } else {
-            hipLaunchKernelGGL(k_prepare<false>, grid, block, 0, st, JobLimits{}, n_jobs, seg_off, dur, mem, safe,
+            hipLaunchKernelGGL(k_prepare<false>, grid, block, 0, st, JobLimits{}, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe,
                                progress, pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
                                ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int2>(ctx, L.first_dp));
@@ -544,6 +569,7 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
         SJA_HIP(hipGetLastError(), "k_prepare launch");
     }
     ctx->limits_used = ctx->limits_on;
+    ctx->score_used = ctx->score_mode;
     ctx->limits_applied = ctx->limits;
     ctx->used_power = ctx->lim_power;
     ctx->used_deadline = ctx->lim_deadline;
@@ -660,9 +686,12 @@ int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W,
             const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
             const int tiles8 = (job_tiles + 7) / 8 * 8;
             const unsigned grid = unsigned(tiles8) * unsigned(chunk_bound);
-            auto kern = params->policy == SJA_POLICY_MIXED
-                            ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true>
-                            : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false>;
+            const bool mixed = params->policy == SJA_POLICY_MIXED;
+            const long long *atom_area = atom_area_of(ctx, L);
+            auto kern = atom_area ? (mixed ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true, true>
+                                           : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false, true>)
+                                  : (mixed ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true, false>
+                                           : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false, false>);
             if (ctx->timing) {
                 if (!ctx->ev_start) {
                     SJA_HIP(hipEventCreate(&ctx->ev_start), "hipEventCreate");
@@ -671,7 +700,7 @@ int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W,
                 SJA_HIP(hipEventRecord(ctx->ev_start, st), "hipEventRecord");
             }
             hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedBlock), 0, st, J, n_gaps, chunk_bound, to_dev(params),
-                               ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), atom_area, ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int32_t>(ctx, L.plan), ws_ptr<int32_t>(ctx, L.chunk_begin),
                                ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
                                ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.start_tab),
@@ -816,15 +845,18 @@ int sja_advance(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, co
     if (J > 0) {
         const int jobs_per_block = 256 / kWave;
         const dim3 grid((J + jobs_per_block - 1) / jobs_per_block), block(256);
+        const bool by_area = ctx->score_used == SJA_SCORE_AREA;
+        long long *pre_area = by_area ? ws_ptr<long long>(ctx, L.pre_area) : nullptr;
+        long long *atom_area = by_area ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
         if (ctx->limits_used) {
             const JobLimits lim = job_limits(ctx->limits_applied, ctx->used_power, ctx->used_deadline);
-            hipLaunchKernelGGL(k_advance_jobs<true>, grid, block, 0, st, lim, n_gaps, J, ctx->seg_off, ctx->dur,
+            hipLaunchKernelGGL(k_advance_jobs<true>, grid, block, 0, st, lim, pre_area, atom_area, n_gaps, J, ctx->seg_off, ctx->dur,
                                ctx->mem, ctx->safe, grant_job, grant_cut, job_gap, progress, wait, wait_step,
                                ctx->pre_dur, ctx->pre_peak, ctx->prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
                                ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int2>(ctx, L.first_dp), m);
         } else {
-            hipLaunchKernelGGL(k_advance_jobs<false>, grid, block, 0, st, JobLimits{}, n_gaps, J, ctx->seg_off,
+            hipLaunchKernelGGL(k_advance_jobs<false>, grid, block, 0, st, JobLimits{}, pre_area, atom_area, n_gaps, J, ctx->seg_off,
                                ctx->dur, ctx->mem, ctx->safe, grant_job, grant_cut, job_gap, progress, wait,
                                wait_step, ctx->pre_dur, ctx->pre_peak, ctx->prev_safe,
                                ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),

@@ -40,6 +40,7 @@ struct Layout {
     size_t atom_dp, atom_db;               // [S+8] int2 each: (dur, peak) and (dur, boundary)
     size_t n_atoms;                        // [J] int32
     size_t first_dp;                       // [J] int2: a job's first atom (duration, peak), INT32_MAX twice if none
+    size_t atom_area, pre_area;            // area score only: int64 area under the envelope per atom / per segment
     size_t gap_rank, gap_order;            // [G] int32
     size_t gap_w, gap_c, gap_run_end;      // [G+16] int32, in sorted order
     size_t gap_cls;                        // [G+16] int32: capacity class of a sorted position
@@ -116,6 +117,8 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.atom_db = take(size_t(S + 8) * 8);
     L.n_atoms = take(size_t(J) * 4);
     L.first_dp = take(size_t(J) * 8);
+    L.atom_area = take(size_t(S + 8) * 8);
+    L.pre_area = take(size_t(S + 8) * 8);
     L.gap_rank = take(size_t(G) * 4);
     L.gap_order = take(size_t(G) * 4);
     L.gap_w = take(size_t(G + 16) * 4);
@@ -203,6 +206,9 @@ struct sja_ctx {
     sja_limits limits, limits_applied;
     const int32_t *lim_power, *lim_deadline;
     const int32_t *used_power, *used_deadline;
+
+    // how F is read (sja_set_score), and how the last prepare built the tables
+    int score_mode, score_used;
 
     // optional timing of the pair-evaluation kernel
     bool timing;

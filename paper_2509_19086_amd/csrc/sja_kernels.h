@@ -64,10 +64,22 @@ __device__ __forceinline__ void wave_scan_max(int &q, int lane)
     }
 }
 
-// One wave walks job j's segments from boundary p to the job's end.
+// Inclusive wave scan of 64-bit sums.
+__device__ __forceinline__ void wave_scan_add64(long long &v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const long long o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+}
+
+// One wave walks job j's segments from boundary p to the job's end.  With
+// pre_area / atom_area (both or neither) it also keeps the running area under
+// the envelope, sum of dur * mem, per segment and per atom.
 template <bool LIMITED>
 __device__ __forceinline__ void prepare_job(
-    const JobLimits &lim,
+    const JobLimits &lim, long long *__restrict__ pre_area, long long *__restrict__ atom_area,
     int j, int lane, int64_t base, int L, int p, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
@@ -77,6 +89,7 @@ __device__ __forceinline__ void prepare_job(
     int carry_sum = 0, carry_peak = INT32_MIN, carry_last = -1, count = 0;
     int first_d = INT32_MAX, first_p = INT32_MAX;     // the first atom, if there is one
     int d_hi = INT32_MAX, carry_pow = INT32_MIN;
+    long long carry_area = 0;
     if (LIMITED) {
         d_hi = lim.tau_max;
         if (lim.deadline) {
@@ -94,6 +107,14 @@ __device__ __forceinline__ void prepare_job(
             m = mem[base + k];
             flag = (safe[base + k] != 0) || (k + 1 == L);
             l = flag ? k + 1 : -1;
+        }
+        long long ar = 0;
+        if (pre_area) {
+            ar = valid ? (long long)s * (long long)m : 0ll;
+            wave_scan_add64(ar, lane);
+            ar += carry_area;
+            if (valid) pre_area[base + k] = ar;
+            carry_area = __shfl(ar, kWave - 1, kWave);
         }
         wave_scan_add_max_max(s, m, l, lane);
         s += carry_sum;
@@ -125,6 +146,7 @@ __device__ __forceinline__ void prepare_job(
             const int idx = count + __popcll(mask & lanes_below(lane));
             atom_dp[base + idx] = make_int2(s, m);
             atom_db[base + idx] = make_int2(s, k + 1);
+            if (atom_area) atom_area[base + idx] = ar;
         }
         count += __popcll(mask);
         carry_sum = __shfl(s, kWave - 1, kWave);
@@ -139,7 +161,7 @@ __device__ __forceinline__ void prepare_job(
 
 template <bool LIMITED>
 __global__ __launch_bounds__(256) void k_prepare(
-    JobLimits lim, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    JobLimits lim, long long *__restrict__ pre_area, long long *__restrict__ atom_area, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
@@ -153,7 +175,7 @@ __global__ __launch_bounds__(256) void k_prepare(
     const int L = int(seg_off[j + 1] - base);
     int p = progress[j];
     p = p < 0 ? 0 : (p > L ? L : p);
-    prepare_job<LIMITED>(lim, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db,
+    prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db,
                          n_atoms, first_dp);
 }
 
@@ -265,7 +287,7 @@ __global__ __launch_bounds__(256) void k_cover(
 // wait_step longer.  metrics[3] counts the jobs with nothing left afterwards.
 template <bool LIMITED>
 __global__ __launch_bounds__(256) void k_advance_jobs(
-    JobLimits lim, int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    JobLimits lim, long long *__restrict__ pre_area, long long *__restrict__ atom_area, int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ grant_job, const int32_t *__restrict__ grant_cut,
     const int32_t *__restrict__ job_gap, int32_t *__restrict__ progress, int32_t *__restrict__ wait,
@@ -286,7 +308,7 @@ __global__ __launch_bounds__(256) void k_advance_jobs(
         // every lane evaluates the same scalars, so the branch is uniform over the wave
         if (grant_holds(job_gap[j], j, n_gaps, n_jobs, seg_off, grant_job, grant_cut, job_gap, progress, cut)) {
             p = cut;
-            prepare_job<LIMITED>(lim, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp,
+            prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp,
                                  atom_db, n_atoms, first_dp);
             if (lane == 0) {
                 progress[j] = p;
@@ -393,11 +415,11 @@ __device__ __forceinline__ bool key_better(unsigned long long hi_a, unsigned lon
 // Steps reduced together by one wave (see k_select_pass).
 constexpr int kSelBatch = 8;
 
-template <bool MIXED>
+template <bool MIXED, bool AREA>
 __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     int n_jobs, int n_gaps, int n_chunks, PolicyDev pol, const int64_t *__restrict__ seg_off,
     const int32_t *__restrict__ pre_dur, const int32_t *__restrict__ pre_peak,
-    const int32_t *__restrict__ cut, const int32_t *__restrict__ gap_order,
+    const long long *__restrict__ pre_area, const int32_t *__restrict__ cut, const int32_t *__restrict__ gap_order,
     const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
     const int32_t *__restrict__ job_held, const uint8_t *__restrict__ gap_active,
     SelPartial *__restrict__ part)
@@ -453,7 +475,7 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
         }
         // a job's cut rarely changes from one sorted position to the next: only the changes
         // gather (duration, peak), all of a batch's gathers in flight together
-        int dv[kSelBatch], pv[kSelBatch];
+        int dv[kSelBatch], pv[kSelBatch];    // AREA: the two halves of F itself, read instead of (duration, peak)
         bool fresh[kSelBatch];
         int prev = last_cut;
 #pragma unroll
@@ -461,8 +483,14 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
             const int c = cv[t];
             fresh[t] = c >= 0 && c != prev;
             if (fresh[t]) {
-                dv[t] = pre_dur[base + c - 1];
-                pv[t] = pre_peak[base + c - 1];
+                if (AREA) {
+                    const long long a = pre_area[base + c - 1];
+                    dv[t] = int(uint32_t(a));
+                    pv[t] = int(uint32_t((unsigned long long)a >> 32));
+                } else {
+                    dv[t] = pre_dur[base + c - 1];
+                    pv[t] = pre_peak[base + c - 1];
+                }
             }
             prev = c >= 0 ? c : prev;
         }
@@ -470,7 +498,8 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
 #pragma unroll
         for (int t = 0; t < kSelBatch; ++t) {
             if (fresh[t]) {
-                const unsigned long long F = (unsigned long long)dv[t] * (unsigned long long)pv[t];
+                const unsigned long long F = AREA ? (((unsigned long long)uint32_t(pv[t]) << 32) | uint32_t(dv[t]))
+                                                  : (unsigned long long)dv[t] * (unsigned long long)pv[t];
                 hi = ((tier << 62) | (F * mult)) + 1ull;
             }
             s_key[wave][t][lane] = cv[t] >= 0 ? hi : 0ull;

@@ -372,3 +372,47 @@ def test_beyond_stress_64bit_indexing(oracle):
     torch.cuda.synchronize()
     for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
         assert torch.equal(a, b)
+
+
+def test_stress_area_score_full_size(oracle):
+    """The area score at the full Stress size: candidates of sampled gap rows against the oracle,
+    the fused call against select for every gap, and every grant's score recomputed by the oracle."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("stress", 0)
+    G, J = wl.n_gaps, wl.n_jobs
+    eng = P.Engine(0)
+    eng.sja_set_score(1)
+    t = P.DeviceTick(eng, wl, want_bits=False)
+    par = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 8)
+    opar = oracle.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 8)
+    t.prepare(); t.fit(); t.select(par)
+    torch.cuda.synchronize()
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    pa = oracle.area(wl.seg_off, wl.dur, wl.mem, wl.progress)
+    rng = np.random.default_rng(45)
+    rows = np.unique(np.concatenate([[0, G - 1], rng.integers(0, G, size=10)])).astype(np.int64)
+    cut_r, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress,
+                          np.ascontiguousarray(wl.W[rows]), np.ascontiguousarray(wl.C[rows]), False)
+    cj, cc, cs = oracle.select(cut_r, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class, pre_area=pa)
+    rj, _, rs = oracle.select(cut_r, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+    assert (cs != rs).any()                                    # not the rectangle's scores
+    rows_t = torch.from_numpy(rows).cuda()
+    np.testing.assert_array_equal(t.cand_job[rows_t].cpu().numpy(), cj)
+    np.testing.assert_array_equal(t.cand_cut[rows_t].cpu().numpy(), cc)
+    np.testing.assert_array_equal(t.cand_score[rows_t].cpu().numpy(), cs)
+    sel = (t.cand_job.clone(), t.cand_cut.clone(), t.cand_score.clone())
+    t.resolve(par)
+    gj = t.grant_job.cpu().numpy(); gc = t.grant_cut.cpu().numpy(); gs = t.grant_score.cpu().numpy()
+    granted = np.nonzero(gj >= 0)[0]
+    assert len(granted) > 1000 and len(np.unique(gj[granted])) == len(granted)
+    ocut, _, _ = oracle.fit_pairs(granted.astype(np.int32), gj[granted], wl.seg_off, wl.dur, wl.mem, wl.safe,
+                                  wl.progress, wl.W, wl.C)
+    np.testing.assert_array_equal(gc[granted], ocut)
+    F = pa[wl.seg_off[:-1][gj[granted]] + ocut - 1]
+    np.testing.assert_array_equal(gs[granted], F * (wl.wait_scale + wl.wait[gj[granted]].astype(np.int64)))
+    assert gj[0] == cj[0] and gs[0] == cs[0]
+    t.fit_select(par)
+    torch.cuda.synchronize()
+    for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
+        assert torch.equal(a, b)
