@@ -119,3 +119,42 @@ def test_area_score_chain_of_ticks_and_back(engine, oracle):
         engine.sja_set_score(RECTANGLE)
     with pytest.raises(RuntimeError):
         engine.sja_set_score(2)
+
+
+def test_area_score_under_admission_limits(engine, oracle):
+    """Both options at once: atoms filtered by the limits carry their areas along."""
+    import torch
+    import paper_2509_19086_amd as P
+    from gen import make_channels
+    wl = make_workload("small", 5)
+    power, deadline = make_channels(wl, 5)
+    kw = dict(tau_min=120, tau_max=1300, power_cap=int(np.percentile(power, 85)), now=4)
+    par = P.Params.make(3, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    opar = oracle.Params.make(3, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    d_power, d_deadline = torch.from_numpy(power).cuda(), torch.from_numpy(deadline).cuda()
+    engine.sja_set_score(AREA)
+    engine.sja_set_limits(P.Limits.make(**kw), d_power, d_deadline)
+    try:
+        pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+        pa = oracle.area(wl.seg_off, wl.dur, wl.mem, wl.progress)
+        cut, _ = oracle.fit_limited(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C,
+                                    oracle.Limits.make(**kw), power, deadline)
+        want = oracle.resolve(cut, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class, pre_area=pa)
+        cj, cc, cs = oracle.select(cut, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class, pre_area=pa)
+        for fused in (False, True):
+            t = P.DeviceTick(engine, wl, want_bits=False, want_cut=not fused)
+            t.prepare()
+            if fused:
+                t.fit_select(par)
+            else:
+                t.fit(); t.select(par)
+                np.testing.assert_array_equal(t.cut.cpu().numpy(), cut)
+            np.testing.assert_array_equal(t.cand_job.cpu().numpy(), cj)
+            np.testing.assert_array_equal(t.cand_score.cpu().numpy(), cs)
+            t.resolve(par)
+            for x, y in zip((t.grant_job, t.grant_cut, t.grant_score, t.job_gap), want[:4]):
+                np.testing.assert_array_equal(x.cpu().numpy(), y)
+            assert t.rounds.cpu().tolist() == [want[4], want[5]]
+    finally:
+        engine.sja_set_limits(None)
+        engine.sja_set_score(RECTANGLE)
