@@ -28,6 +28,24 @@ def algorithmic_fit_bytes(wl, n_atoms_total):
     return 4 * G * J + 12 * n_atoms_total + 8 * G
 
 
+def secondary_rates(wl, n_atoms_total, call_ms, rounds):
+    """Algorithmic bytes and rates of the other calls (whole calls, HIP events): prepare moves 9 B in
+    and 12 B out per segment after the progress point plus 16 B per atom and 20 B per job; select
+    reads the 4-byte cut of every pair and writes 16 B per gap; the rounds of resolve are bound by
+    latency, so they are reported per round."""
+    import numpy as np
+    G, J = wl.n_gaps, wl.n_jobs
+    remaining = int((np.diff(wl.seg_off) - wl.progress).clip(min=0).sum())
+    out = {}
+    for name, nbytes in (("prepare", 21 * remaining + 16 * n_atoms_total + 20 * J), ("select", 4 * G * J + 16 * G)):
+        gbs = nbytes / (call_ms[name] * 1e-3) / 1e9
+        out[name] = {"algorithmic_bytes": nbytes, "achieved_GBs": gbs, "frac": gbs / HBM_PEAK_GBS,
+                     "evals_per_s": G * J / (call_ms[name] * 1e-3)}
+    out["resolve"] = {"us_per_round": 1e3 * call_ms["resolve"] / max(rounds, 1), "rounds": rounds,
+                      "evals_per_s": G * J / (call_ms["resolve"] * 1e-3)}
+    return out
+
+
 # HBM traffic of one k_fit_main launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, KiB
 # per dispatch), each scaled by what the same counter reads for a plain 1 GiB device copy
 # (profiles/fit_main_stress_pmc.md).  It belongs to one kernel source and one workload: the
@@ -413,6 +431,7 @@ def main():
         "call_ms": {k: mean(v) for k, v in rec.items()},
         "call_ms_median": {k: sorted(v)[len(v) // 2] for k, v in rec.items()},
         "call_ms_min": {k: min(v) for k, v in rec.items()},
+        "secondary": secondary_rates(wl, n_atoms, {k: mean(v) for k, v in rec.items()}, rounds),
         "fit_evals_per_s": pairs / (mean(rec["fit"]) * 1e-3),
         "fit_kernel_evals_per_s": pairs / (fit_kernel_ms * 1e-3),
         **extras,
