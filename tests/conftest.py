@@ -10,7 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    config.addinivalue_line("markers", "slow: full-size case, minutes on the GPU box")
+    config.addinivalue_line("markers", "slow: full-size case (seconds on the GPU, minutes of oracle work where it is not precomputed)")
 
 
 @pytest.fixture(scope="session")
