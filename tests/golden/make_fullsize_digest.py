@@ -6,6 +6,8 @@ library's outputs, which compares whole outputs at sizes where the oracle takes 
     python tests/golden/make_fullsize_digest.py large stress
     python tests/golden/make_fullsize_digest.py --resolve large stress   (adds the grants; keeps the whole
                                                                          cut matrix in host memory, hours at Stress)
+    python tests/golden/make_fullsize_digest.py --resolve --caps=8 stress   (only these round caps; entries for
+                                                                         other caps already in the file are kept)
 
 Per block b (gaps g = 256 b .. 256 b + 255, jobs j), all sums in wrapping int64:
     interested   number of pairs with cut >= 0
@@ -14,7 +16,7 @@ Per block b (gaps g = 256 b .. 256 b + 255, jobs j), all sums in wrapping int64:
     cand_job     sum of cand_job * (g + 1)
     cand_cut     sum of cand_cut * (g + 1)
     cand_score   sum of cand_score
-With --resolve, "resolve" holds, for the round cap of the config and for 0 (until stable): rounds, stable,
+With --resolve, "resolve" holds, for the round cap of the config, for 8 and for 0 (until stable): rounds, stable,
 the number of grants and sum grant_job * (g + 1), sum grant_cut * (g + 1), sum grant_score,
 sum job_gap * (j + 1), all in wrapping int64.
 """
@@ -59,6 +61,7 @@ def main(names):
     import oracle as O
     from gen import make_workload
     with_resolve = "--resolve" in names
+    caps_arg = [n.split("=", 1)[1] for n in names if n.startswith("--caps=")]
     names = [n for n in names if not n.startswith("--")] or ["large", "stress"]
     for name in names:
         wl = make_workload(name, 0)
@@ -78,16 +81,22 @@ def main(names):
             if (g0 // BLOCK) % 16 == 0:
                 print(f"{name}: gap {g0} of {wl.n_gaps}, {time.time() - t0:.0f} s", flush=True)
         out = {"config": name, "seed": 0, "n_gaps": wl.n_gaps, "n_jobs": wl.n_jobs, "policy": int(wl.policy),
-               "block": BLOCK, "source": "oracle/ (sjo_fit, sjo_select), written by tests/golden/make_fullsize_digest.py",
+               "block": BLOCK, "source": "oracle/ (sjo_fit, sjo_select, sjo_resolve where present), written by tests/golden/make_fullsize_digest.py",
                "blocks": blocks}
+        path = os.path.join(ROOT, "tests", "golden", f"fullsize_digest_{name}.json")
         if whole is not None:
             out["resolve"] = {}
-            for cap in sorted({int(wl.max_rounds), 0}, reverse=True):
+            if os.path.exists(path):
+                with open(path) as f:
+                    old = json.load(f)
+                if old.get("blocks") == blocks:
+                    out["resolve"] = old.get("resolve", {})
+            caps = {int(c) for c in caps_arg[0].split(",")} if caps_arg else {int(wl.max_rounds), 8, 0}
+            for cap in sorted(caps, reverse=True):
                 p2 = O.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, cap)
                 res = O.resolve(whole, wl.seg_off, pd, pp, p2, wl.wait, wl.sla_class)
                 out["resolve"][str(cap)] = grant_digest(*res)
                 print(f"{name}: resolve cap {cap}: {res[4]} rounds, {time.time() - t0:.0f} s", flush=True)
-        path = os.path.join(ROOT, "tests", "golden", f"fullsize_digest_{name}.json")
         with open(path, "w") as f:
             json.dump(out, f, indent=0)
         print("wrote", path, flush=True)
