@@ -220,3 +220,37 @@ def test_advance_and_cover_with_no_gaps(engine, oracle):
     np.testing.assert_array_equal(t.wait.cpu().numpy(), w2)
     assert t.metrics.cpu().tolist() == m.tolist() == [0, 0, 0, 1]
     assert w2[2] == wl.wait[2] and (np.delete(w2, 2) == np.delete(wl.wait, 2) + 11).all()
+
+
+def test_whole_chain_on_a_side_stream(engine, oracle):
+    """Every call takes the caller's stream: two ticks enqueued on a non-default stream (default
+    priority), the device only synchronised where sja_resolve does it itself and at the end."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("small", 12)
+    par = P.Params.make(3, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    opar = oracle.Params.make(3, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
+    t = P.DeviceTick(engine, wl, want_bits=True)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    W1, C1 = make_gaps("small", 12, 1)
+    with torch.cuda.stream(side):
+        t.prepare(); t.fit(); t.select(par); t.resolve(par)
+        first = [x.clone() for x in (t.cut, t.bits, t.cand_job, t.cand_score, t.grant_job, t.grant_cut, t.job_gap)]
+        t.advance(500)
+        t.set_gaps(W1, C1)
+        t.fit_select(par); t.resolve(par)
+    side.synchronize()
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cut, bits = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C)
+    cj, cc, cs = oracle.select(cut, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+    gj, gc, gs, jg, _, _ = oracle.resolve(cut, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+    for got, want in zip(first, (cut, bits.view(np.int32), cj, cs, gj, gc, jg)):
+        np.testing.assert_array_equal(got.cpu().numpy(), want)
+    p2, w2, _ = oracle.advance(wl.seg_off, pd, pp, wl.W, wl.C, gj, gc, jg, wl.progress, wl.wait, 500)
+    np.testing.assert_array_equal(t.progress.cpu().numpy(), p2)
+    pd2, pp2, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, p2)
+    cut2, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, p2, W1, C1, False)
+    gj2, gc2, gs2, jg2, _, _ = oracle.resolve(cut2, wl.seg_off, pd2, pp2, opar, w2, wl.sla_class)
+    np.testing.assert_array_equal(t.grant_job.cpu().numpy(), gj2)
+    np.testing.assert_array_equal(t.grant_score.cpu().numpy(), gs2)
