@@ -305,7 +305,7 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // 1 = granted, 2 = no candidate left (in memory the flag shares its word with
 // the gap index).  r[] holds the records at st.x on entry.
 constexpr int kWalk = 2;         // records a lane reads per trip on its own (8: 2.7 ms slower per Stress resolve)
-constexpr int kSweep = 4;        // chunks of 64 records the wave reads per trip when it walks together
+constexpr int kSweep = 3;        // chunks of 64 records the wave reads per trip when it walks together
 constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
 constexpr int kRoundBlock = 256; // threads per block of the round kernel
 constexpr int kBlockClaims = 256; // claims a block merges in LDS per round
