@@ -304,7 +304,7 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // st = (pointer, candidate job, candidate atom, flag) with flag 0 = active,
 // 1 = granted, 2 = no candidate left (in memory the flag shares its word with
 // the gap index).  r[] holds the records at st.x on entry.
-constexpr int kWalk = 2;         // records a lane reads per trip on its own (8: 2.7 ms slower per Stress resolve)
+constexpr int kWalk = 1;         // records a lane reads per trip on its own (8: 2.7 ms slower per Stress resolve)
 constexpr int kSweep = 3;        // chunks of 64 records the wave reads per trip when it walks together
 constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
 constexpr int kRoundBlock = 256; // threads per block of the round kernel
