@@ -306,25 +306,51 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // the gap index).  r[] holds the records at st.x on entry.
 constexpr int kWalk = 1;         // records a lane reads per trip on its own (8: 2.7 ms slower per Stress resolve)
 constexpr int kSweep = 3;        // chunks of 64 records the wave reads per trip when it walks together
+constexpr int kSweepHeld = 8;    // the same with the held bitmap: no claim words to fetch, so a wider trip costs little
 constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
 constexpr int kRoundBlock = 256; // threads per block of the round kernel
 constexpr int kBlockClaims = 256; // claims a block merges in LDS per round
 
+constexpr int kHeldMaxWords = 4096;   // words of the held-job bitmap a block keeps in LDS (jobs / 32)
+constexpr int kHeldRounds = 512;      // rounds that keep and read the bitmap; later rounds hardly ever walk together
+
+__device__ __forceinline__ bool held_bit(const uint32_t *s_held, uint32_t job)
+{
+    return (s_held[job >> 5] >> (job & 31u)) & 1u;
+}
+
+// HELD (the early rounds, where lanes pass hundreds of records of jobs that were
+// just taken): when the wave walks together it asks a bitmap in LDS which jobs
+// were held before this round, instead of fetching a claim word per record, so a
+// joint trip is one memory trip, not two; only the record a lane settles on has
+// its claim word fetched.  Two bitmaps alternate: a round reads one and writes
+// only the other (held_next), so nothing it reads changes under it.  A job named
+// in round k is held from round k+1 on, whoever wins it: the gaps naming it set
+// its bit in the bitmap round k+1 reads, and its winner, when it learns in round
+// k+1 that it won, sets it in the other one, after which both carry it.
+template <bool HELD>
 __device__ __forceinline__ void grant_step(int round, bool propose, int lane, int g, int list_begin, int list_end,
                                            const uint4 *__restrict__ rec, unsigned long long *claim, int4 &st,
                                            uint4 (&r)[kWalk], bool &lost, bool &cand, int *s_n, int *s_job,
-                                           unsigned long long *s_word)
+                                           unsigned long long *s_word, const uint32_t *s_held,
+                                           uint32_t *held_next)
 {
     lost = false;
     cand = false;
     if (st.w == 0 && st.y >= 0) {
-        if (claim[st.y] == claim_of(round - 1, g)) st.w = 1;      // won: final
-        else lost = true;
+        if (claim[st.y] == claim_of(round - 1, g)) {               // won: final
+            st.w = 1;
+            if (HELD) atomicOr(&held_next[uint32_t(st.y) >> 5], 1u << (uint32_t(st.y) & 31u));
+        } else {
+            lost = true;
+        }
     }
     int cand_job = -1;
     unsigned long long cand_word = 0;      // the candidate job's claim word as the walk saw it
     const bool walking = st.w == 0 && propose;
     int e = st.x, found = -1, found_j = -1, found_a = -1;
+    bool by_bitmap = false;                // found while walking together with HELD: the claim word is still to fetch
+    constexpr int SW = HELD ? kSweepHeld : kSweep;
     if (walking) {
         // own walk: every lane from its own pointer
         for (int trip = 0; e < list_end; ++trip) {
@@ -361,17 +387,20 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
             for (int d = 1; d < kWave; d <<= 1) e0 = min(e0, __shfl_xor(e0, d, kWave));
             e0 = __builtin_amdgcn_readfirstlane(e0);
             const int c0 = list_begin + ((e0 - list_begin) & ~(kWave - 1));
-            uint4 rr[kSweep];
-            unsigned long long cw[kSweep];
+            uint4 rr[SW];
+            unsigned long long cw[SW];
 #pragma unroll
-            for (int k = 0; k < kSweep; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
+            for (int k = 0; k < SW; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
 #pragma unroll
-            for (int k = 0; k < kSweep; ++k) cw[k] = claim[rr[k].x];
-            const bool here = looking && e < c0 + kSweep * kWave;
+            for (int k = 0; k < SW; ++k) {
+                if (HELD) cw[k] = held_bit(s_held, rr[k].x) ? ~0ull : 0ull;
+                else cw[k] = claim[rr[k].x];
+            }
+            const bool here = looking && e < c0 + SW * kWave;
             int hit = -1, hj = 0, ha = 0;
             unsigned int hw_lo = 0, hw_hi = 0;
 #pragma unroll
-            for (int k = 0; k < kSweep; ++k) {
+            for (int k = 0; k < SW; ++k) {
                 // records worth a look: free, and covering some lane that still needs one
                 const unsigned long long need = __ballot(here && hit < 0);
                 const int need_lo = need ? __ffsll((long long)need) - 1 : 0;
@@ -401,14 +430,16 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
                 if (hit >= 0) {
                     found = c0 + hit; found_j = hj; found_a = ha;
                     cand_word = (static_cast<unsigned long long>(hw_hi) << 32) | hw_lo;
+                    by_bitmap = HELD;
                     looking = false;
                 } else {
-                    e = c0 + kSweep * kWave;
+                    e = c0 + SW * kWave;
                     looking = e < list_end;
                 }
             }
         }
     }
+    if (HELD && by_bitmap) cand_word = claim[found_j];      // what this round's earlier claims left there
     if (walking) {
         if (found >= 0) {
             st = make_int4(found + 1, found_j, found_a, 0);
@@ -436,8 +467,13 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
             const unsigned long long word = (static_cast<unsigned long long>(round) << 32) | best;
             if (cand_word < word) {
                 const int slot = atomicAdd(s_n, 1);
-                if (slot < kBlockClaims) { s_job[slot] = job; s_word[slot] = word; }
-                else atomicMax(&claim[job], word);
+                if (slot < kBlockClaims) {
+                    s_job[slot] = job;
+                    s_word[slot] = word;
+                } else {
+                    atomicMax(&claim[job], word);
+                    if (HELD) atomicOr(&held_next[uint32_t(job) >> 5], 1u << (uint32_t(job) & 31u));
+                }
             }
         }
         todo &= ~__ballot(mine);
@@ -450,17 +486,19 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
 // and the block sends one atomicMax per job.  A round leaves two flags: somebody
 // lost (round k-1), somebody selected (round k); the host only asks those two
 // questions.
+template <bool HELD>
 __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     int round, int propose, int lb_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
     const int32_t *__restrict__ lb_end, const int32_t *__restrict__ list_off,
     const int32_t *__restrict__ gap_order, const uint4 *__restrict__ rec, unsigned long long *claim,
-    int4 *state, int32_t *cnt_lost, int32_t *cnt_cand)
+    int4 *state, int32_t *cnt_lost, int32_t *cnt_cand, int held_words, uint32_t *held)
 {
     __shared__ int s_n;
     __shared__ int s_job[kBlockClaims];
     __shared__ unsigned long long s_word[kBlockClaims];
-    if (threadIdx.x == 0) s_n = 0;
-    __syncthreads();
+    __shared__ uint4 s_held4[HELD ? kHeldMaxWords / 4 : 1];
+    const uint32_t *s_held = reinterpret_cast<const uint32_t *>(s_held4);
+    uint32_t *held_next = nullptr;
     const int u = blockIdx.x * (kRoundBlock / kWave) + (threadIdx.x / kWave);
     const int lane = threadIdx.x & (kWave - 1);
     // The state of a gap lives at (list block, lane) and carries the gap's index, so
@@ -468,6 +506,15 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     const int slot = u * kWave + lane;
     int4 raw = make_int4(0, -1, -1, 2);
     if (round > 1 && u < lb_cap) raw = state[slot];
+    if (HELD) {
+        // the bitmap travels together with the state; held_words is a multiple of 4 and at most
+        // kHeldMaxWords, and the two bitmaps lie back to back
+        const uint4 *src = reinterpret_cast<const uint4 *>(held + size_t(round & 1) * held_words);
+        for (int i = threadIdx.x; i < held_words / 4; i += kRoundBlock) s_held4[i] = src[i];
+        held_next = held + size_t((round + 1) & 1) * held_words;
+    }
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
     if (u < plan[kPlanListBlocks]) {
         const int list_begin = list_off[u], list_end = list_off[u + 1];
         if (round == 1) {
@@ -484,7 +531,8 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
         }
         const int4 before = st;
         bool lost, cand;
-        grant_step(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, r, lost, cand, &s_n, s_job, s_word);
+        grant_step<HELD>(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, r, lost, cand, &s_n, s_job,
+                         s_word, s_held, held_next);
         if (st.x != before.x || st.w != before.w || round == 1) state[slot] = make_int4(st.x, st.y, st.z, st.w | (g << 2));
         if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;
         if (__ballot(cand) && lane == 0) cnt_cand[round] = 1;
@@ -501,7 +549,10 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
                 first = first && k >= i;
             }
         }
-        if (first) atomicMax(&claim[job], word);
+        if (first) {
+            atomicMax(&claim[job], word);
+            if (HELD) atomicOr(&held_next[uint32_t(job) >> 5], 1u << (uint32_t(job) & 31u));
+        }
     }
 }
 

@@ -289,9 +289,24 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     const int round_grid = (n_subs + kRoundBlock / kWave - 1) / (kRoundBlock / kWave);
 
     // one launch per round, in batches between looks at the flags
+    // the first kHeldRounds rounds keep the held jobs as a bitmap too (two alternating copies), if it fits LDS
+    const int held_words = held_bitmap_words(J);
+    const bool use_held = held_words <= kHeldMaxWords;
+    uint32_t *held = ws_ptr<uint32_t>(ctx, L.g_held);
+    if (use_held) {
+        hipLaunchKernelGGL(k_fill_i32, dim3((2 * held_words + 255) / 256), dim3(256), 0, st,
+                           reinterpret_cast<int32_t *>(held), int64_t(2) * held_words, 0);
+        SJA_HIP(hipGetLastError(), "k_fill_i32 launch");
+    }
     auto launch_round = [&](int64_t k, int propose) {
-        hipLaunchKernelGGL(k_grant_round, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, lb_bound, plan, lb_begin, lb_end,
-                           list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand);
+        if (use_held && k <= kHeldRounds)
+            hipLaunchKernelGGL(k_grant_round<true>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, lb_bound,
+                               plan, lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
+                               held_words, held);
+        else
+            hipLaunchKernelGGL(k_grant_round<false>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, lb_bound,
+                               plan, lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
+                               0, static_cast<uint32_t *>(nullptr));
         return hipGetLastError();
     };
     std::vector<int32_t> h_lost, h_cand;

@@ -70,6 +70,7 @@ struct Layout {
     size_t lb_begin, lb_end, lb_sub;       // [list_bound] int32: grant-list blocks (pieces of sub-blocks)
     size_t lb_off;                         // [sub_bound+2] int32: first list block of a sub-block
     size_t g_list_off;                     // [list_bound+2] int32
+    size_t g_held;                         // 2 x held_bitmap_words(J) uint32: jobs held before a round, two alternating copies
     size_t g_state;                        // [list_bound * 64] int4: pointer, candidate job, candidate atom, flag | gap << 2
     size_t g_cnt_lost, g_cnt_cand;         // [min(G,J)+4] int32
     int64_t atom_cap, entry_cap;
@@ -107,6 +108,9 @@ inline int64_t fit_sub_bound(int64_t G, int64_t J)
 // Grant-list blocks: the sub-blocks, those that span a wide range of small
 // windows cut into pieces (at most kListSplits per capacity class).
 inline int64_t list_block_bound(int64_t G, int64_t J) { return fit_sub_bound(G, J) + int64_t(kMaxClasses) * kListSplits; }
+
+// Words of one held-job bitmap: one bit per job, padded to whole 16-byte loads.
+inline int held_bitmap_words(int64_t n_jobs) { return int(((n_jobs + 31) / 32 + 3) / 4 * 4); }
 
 inline Layout make_layout(int64_t G, int64_t J, int64_t S)
 {
@@ -174,6 +178,7 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.lb_off = take((ub + 2) * 4);
     L.g_list_off = take((lb + 2) * 4);
     L.g_state = take(lb * size_t(kWave) * 16);
+    L.g_held = take(2 * size_t(held_bitmap_words(J)) * 4);
     const size_t rounds_cap = size_t(G < J ? G : J) + 4;
     L.g_cnt_lost = take(rounds_cap * 4);
     L.g_cnt_cand = take(rounds_cap * 4);
