@@ -19,7 +19,9 @@
 //      atomicMax of (round, ~gap index), the claims of a thread block merged
 //      first; the next round's kernel first checks who won.  Claims carry the
 //      round number, so nothing is ever reset and a claim made in the current
-//      round is not mistaken for a hold.
+//      round is not mistaken for a hold.  In the early rounds, where lanes
+//      pass hundreds of records of jobs that were just taken, the waves
+//      also keep the held jobs as a bitmap (see grant_step).
 #pragma once
 
 #include "k_sort.h"
@@ -374,7 +376,8 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
         }
     }
     // Lanes that are still looking walk on together: per round trip the wave
-    // reads kSweep chunks of 64 records (and their jobs' claim words), starting
+    // reads SW chunks of 64 records (and their jobs' claim words, or with HELD
+    // the bitmap's answer), starting
     // at the chunk of its lowest pointer still looking, so a record is read once
     // per round; every lane whose pointer lies in that span takes the first free
     // record at or after its pointer that covers the lane, or moves on past the span.
