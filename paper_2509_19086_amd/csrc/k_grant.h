@@ -360,7 +360,8 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
 #pragma unroll
             for (int t = 0; t < kWalk; ++t) {
                 const bool covers = e + t < list_end && lane >= int(r[t].z & 255u) && lane < int(r[t].z >> 8);
-                c[t] = covers ? claim[r[t].x] : ~0ull;   // a huge stamp of an earlier round: "held"
+                // a huge stamp of an earlier round: "held"; with HELD the bitmap spares the fetch for a held job
+                c[t] = (covers && !(HELD && held_bit(s_held, r[t].x))) ? claim[r[t].x] : ~0ull;
                 if (!covers) r[t].z = 0;
             }
 #pragma unroll
