@@ -309,3 +309,10 @@ def test_random_small_shapes(engine, oracle):
         full_tick_check(engine, oracle, wl, policies=[policy])
         # with more than 64 distinct capacities the rounds scan the matrix, which the fused call never writes
         fused_check(engine, oracle, wl, [policy], resolve=len(np.unique(wl.C)) <= 64)
+
+
+def test_more_jobs_than_the_held_bitmap_holds(engine, oracle):
+    """With more than 131072 jobs the early rounds cannot keep the held jobs as a bitmap in LDS and
+    walk by claim words from the first round on: same grants."""
+    wl = make_workload("tiny", 5, n_gaps=96, n_jobs=140000)
+    full_tick_check(engine, oracle, wl, policies=[wl.policy, 3], resolve_modes=(0,))
