@@ -560,6 +560,27 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     }
 }
 
+// Gap positions that are neither granted nor out of candidates.  Every round that
+// does not end the process grants at least one of them, so this bounds the rounds
+// that can still follow; the host sizes its next batch of launches with it.
+__global__ __launch_bounds__(1024) void k_count_open(int lb_cap, const int32_t *__restrict__ plan,
+                                                     const int4 *__restrict__ state, int32_t *out)
+{
+    __shared__ int s_sum[1024 / kWave];
+    const int n = min(plan[kPlanListBlocks], lb_cap) * kWave;
+    int c = 0;
+    for (int i = threadIdx.x; i < n; i += 1024) c += (state[i].w & 3) == 0;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) c += __shfl_xor(c, d, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_sum[threadIdx.x / kWave] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+        for (int i = 0; i < 1024 / kWave; ++i) t += s_sum[i];
+        out[0] = t;
+    }
+}
+
 // After the last round: the grants themselves.  A granted position still holds
 // its winning (job, atom) in its state.
 __global__ void k_grant_finish(int lb_cap, PolicyDev pol, const int32_t *__restrict__ plan,

@@ -320,12 +320,18 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
         for (int64_t k = launched + 1; k <= upto; ++k) SJA_HIP(launch_round(k, 1), "k_grant_round launch");
         if (upto == cap) SJA_HIP(launch_round(cap + 1, 0), "k_grant_round launch");
         launched = upto;
+        hipLaunchKernelGGL(k_count_open, dim3(1), dim3(1024), 0, st, lb_bound, plan, state, counters + 12);
+        SJA_HIP(hipGetLastError(), "k_count_open launch");
         const int64_t known = (upto == cap) ? cap + 1 : upto;        // kernels that have run
         h_lost.resize(size_t(known + 1));
         h_cand.resize(size_t(known + 1));
         SJA_HIP(hipMemcpyAsync(h_lost.data(), cnt_lost, size_t(known + 1) * 4, hipMemcpyDeviceToHost, st), "round counters");
         SJA_HIP(hipMemcpyAsync(h_cand.data(), cnt_cand, size_t(known + 1) * 4, hipMemcpyDeviceToHost, st), "round counters");
+        int32_t h_open = 0;
+        SJA_HIP(hipMemcpyAsync(&h_open, counters + 12, 4, hipMemcpyDeviceToHost, st), "open count");
         SJA_HIP(hipStreamSynchronize(st), "round synchronise");
+        // every further round grants at least one open position: no point in enqueueing more than that
+        if (int64_t(h_open) + 1 < batch) batch = int64_t(h_open) + 1;
         for (int64_t r = next_check; r <= upto; ++r) {
             if (h_cand[size_t(r)] == 0) { result[0] = int32_t(r); result[1] = 1; finished = true; break; }
             if (r + 1 > known) { next_check = r; break; }              // losers of r not counted yet
