@@ -9,9 +9,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsja.so")
 SOURCES = [os.path.join(CSRC, "sja.hip")]
-HEADERS = [os.path.join(CSRC, "sja_internal.h"), os.path.join(CSRC, "sja_kernels.h"),
-           os.path.join(CSRC, "k_fit.h"), os.path.join(CSRC, "k_grant.h"), os.path.join(CSRC, "k_sort.h"),
-           os.path.join(os.path.dirname(_HERE), "include", "sja.h")]
+
+
+def headers() -> list:
+    """Every header the library is built from: all of csrc/ plus the public one."""
+    return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")) + \
+        [os.path.join(os.path.dirname(_HERE), "include", "sja.h")]
 
 
 def hipcc() -> str:
@@ -32,7 +35,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+    return any(os.path.getmtime(p) > t for p in SOURCES + headers())
 
 
 def build(force: bool = True, verbose: bool = False) -> str:

@@ -1,8 +1,10 @@
-"""GPU parity at the full sizes of the two largest configs, in the launch
-configuration bench.py times.  The oracle cannot produce 2^28..2^31 pairs in a
-test's time, so outputs are compared on sampled pairs and on whole sampled gap
-rows that the oracle computes one by one, and the grant invariants (which hold
-at any size) are checked with the oracle evaluating every granted pair."""
+"""GPU checks at the full sizes of the two largest configs, in the launch
+configuration bench.py times, that go beyond the element-by-element comparison
+of fit and select in tests/test_gpu_fullsize_elementwise.py: the grants (their
+invariants, which hold at any size, with the oracle evaluating every granted
+pair; digests of the oracle's own grants), both implementations of the rounds
+against each other, chains of ticks, admission limits, the area score, and a
+batch whose element offsets pass 2^32."""
 import numpy as np
 import pytest
 
@@ -255,28 +257,13 @@ def test_stress_limits_full_size(oracle):
     assert gj[0] == cj[0] and gc[0] == cc[0]
 
 
-def _gpu_digests(t, wl, block):
-    """The digests of tests/golden/make_fullsize_digest.py, recomputed from the library's outputs."""
-    import torch
-    G, J = wl.n_gaps, wl.n_jobs
-    jw = torch.arange(1, J + 1, dtype=torch.int64, device="cuda:0")[None, :]
-    out = []
-    for g0 in range(0, G, block):
-        c = t.cut[g0:g0 + block].to(torch.int64)
-        gw = torch.arange(g0 + 1, g0 + c.shape[0] + 1, dtype=torch.int64, device="cuda:0")
-        sl = slice(g0, g0 + block)
-        out.append({"interested": int((c >= 0).sum().item()), "cut_sum": int(c.sum().item()),
-                    "cut_mix": int(((c + 2) * jw * gw[:, None]).sum().item()),
-                    "cand_job": int((t.cand_job[sl].to(torch.int64) * gw).sum().item()),
-                    "cand_cut": int((t.cand_cut[sl].to(torch.int64) * gw).sum().item()),
-                    "cand_score": int(t.cand_score[sl].sum().item())})
-    return out
-
-
 @pytest.mark.parametrize("name", ["large", "stress"])
-def test_whole_outputs_match_the_oracle_digests(name):
-    """Every gap row of the cut matrix and every gap's candidate, at full size, against digests the
-    oracle wrote ahead of time (tests/golden/make_fullsize_digest.py; minutes of CPU work)."""
+def test_grants_match_the_oracle_digests(name):
+    """The grants of every gap at full size, with the round cap 8 and until stable, against
+    digests of the oracle's grants written ahead of time (tests/golden/make_fullsize_digest.py:
+    2007 rounds at Large, 9567 at Stress, hours of oracle time).  Fit and select are compared
+    element by element in tests/test_gpu_fullsize_elementwise.py; only the grants, which the
+    oracle cannot recompute inside a test, go through digests."""
     import json
     import os
     import torch
@@ -291,20 +278,10 @@ def test_whole_outputs_match_the_oracle_digests(name):
     par = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 0)
     t.prepare(); t.fit(); t.select(par)
     torch.cuda.synchronize()
-    got = _gpu_digests(t, wl, gold["block"])
-    assert len(got) == len(gold["blocks"])
-    for b, (x, y) in enumerate(zip(got, gold["blocks"])):
-        assert x == y, f"block {b} (gaps {b * gold['block']}..)"
-    # the fused call reports the same candidates
-    sel = (t.cand_job.clone(), t.cand_cut.clone(), t.cand_score.clone())
-    t.fit_select(par)
-    torch.cuda.synchronize()
-    for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
-        assert torch.equal(a, b)
-    # the grants of every gap, with the config's round cap and until stable
     gw = torch.arange(1, wl.n_gaps + 1, dtype=torch.int64, device="cuda:0")
     jw = torch.arange(1, wl.n_jobs + 1, dtype=torch.int64, device="cuda:0")
-    for cap, want in gold.get("resolve", {}).items():
+    assert gold.get("resolve")
+    for cap, want in gold["resolve"].items():
         t.resolve(P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, int(cap)))
         rounds, stable = t.rounds.cpu().tolist()
         got_r = {"rounds": rounds, "stable": stable, "grants": int((t.grant_job >= 0).sum().item()),

@@ -82,13 +82,14 @@ def test_tiny_all_policies(engine, oracle, seed):
     full_tick_check(engine, oracle, make_workload("tiny", seed), policies=[0, 1, 2, 3])
 
 
-@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4])
 def test_small_all_policies(engine, oracle, seed):
     full_tick_check(engine, oracle, make_workload("small", seed), policies=[1, 0, 2, 3])
 
 
-def test_medium(engine, oracle):
-    full_tick_check(engine, oracle, make_workload("medium", 0))
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4])
+def test_medium(engine, oracle, seed):
+    full_tick_check(engine, oracle, make_workload("medium", seed))
 
 
 @pytest.mark.parametrize("name,G,J", [("large", 300, 1000), ("stress", 777, 2500),

@@ -288,3 +288,25 @@ def test_mixed_breaks_fairness_ties_by_efficiency(oracle):
     fair = oracle.select(cut, seg_off, pd, pp, oracle.Params.make(1, wait_scale=2), wait, cls)
     assert (int(mixed[0][0]), int(mixed[2][0])) == (1, 12)
     assert (int(fair[0][0]), int(fair[2][0])) == (0, 12)
+
+
+@pytest.mark.slow
+def test_large_grant_digest_comes_from_this_oracle(oracle):
+    """The stored digest of the Large config's grants under its round cap of 8
+    (tests/golden/fullsize_digest_large.json, which the GPU test compares with) is what the
+    oracle gives today: the whole Large tick recomputed here, about half a minute."""
+    import importlib.util
+    import json
+    import os
+    golden = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    with open(os.path.join(golden, "fullsize_digest_large.json")) as f:
+        gold = json.load(f)
+    spec = importlib.util.spec_from_file_location("make_fullsize_digest", os.path.join(golden, "make_fullsize_digest.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    wl = make_workload("large", gold["seed"])
+    par = oracle.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 8)
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cut, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C, False)
+    res = oracle.resolve(cut, wl.seg_off, pd, pp, par, wl.wait, wl.sla_class)
+    assert mod.grant_digest(*res) == gold["resolve"]["8"]
