@@ -202,6 +202,32 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
                          int32_t *pre_peak, int32_t *prev_safe);
 
 /*
+ * sja_prepare_profiles for callers that cannot allocate device memory, not even
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same outputs, same errors; the library's
+ * private tables go into a scratch array built into the library (file-scope
+ * device memory of SJA_STATIC_SCRATCH_BYTES per GPU, held by every GPU the
+ * library runs on until the process ends) instead of the caller's workspace,
+ * and that array then IS the context's workspace for the rest of the tick:
+ * sja_fit, sja_fit_select, sja_select, sja_resolve, sja_cover and sja_advance
+ * work on it as usual and return SJA_ERR_WORKSPACE when their own tables for
+ * that many gaps do not fit into it.  The context stays on the built-in scratch
+ * until sja_set_workspace hands it another buffer.
+ *   - Limit: SJA_ERR_SIZE, before any device work, unless
+ *     sja_workspace_bytes(0, n_jobs, n_segments) <= SJA_STATIC_SCRATCH_BYTES.
+ *   - Calls no hipMalloc / hipFree and no allocating library routine.
+ *   - One array per GPU, shared by every context and every call on that GPU and
+ *     never cleared: nothing in it has to start at zero (each call rewrites all
+ *     that it later reads), but two ticks that overlap on one GPU, from two
+ *     contexts or two streams, race on it.  Run them one after the other.
+ */
+#define SJA_STATIC_SCRATCH_BYTES (64u << 20) /* 64 MiB */
+int sja_prepare_profiles_static(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
+                                const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                                const uint8_t *safe, const int32_t *progress, int32_t *pre_dur,
+                                int32_t *pre_peak, int32_t *prev_safe);
+
+/*
  * Fit evaluation for every (gap, job) pair (Sec. 3.5 phase 2; Sec. 3.8: a
  * subjob is admissible on capacity C over its lifetime if its demand stays
  * <= C; Sec. 3.9: max of U over the window <= c, longer fragments preferred).

@@ -50,13 +50,17 @@ class Limits(ctypes.Structure):
 
 
 def load_library(path: Optional[str] = None) -> ctypes.CDLL:
-    """Loads the built library (builds it only if no library is there at all)."""
+    """Loads the built library.  Builds it only when none is there at all; a library that is
+    older than its sources is loaded as it is, with a warning (build again before testing)."""
     global _lib
     if _lib is not None and path is None:
         return _lib
     p = path or _build.LIB
     if not os.path.exists(p):
         _build.build(force=True)
+    elif path is None and _build.is_stale():
+        import warnings
+        warnings.warn(f"{p} is older than its sources: run `python -m paper_2509_19086_amd.build`")
     if not os.path.exists(p):
         raise FileNotFoundError(f"{p} is missing: run `python -m paper_2509_19086_amd.build`")
     lib = ctypes.CDLL(p)
@@ -75,6 +79,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_last_error.restype = ctypes.c_char_p
     lib.sja_prepare_profiles.argtypes = [vp, vp, i32, i64] + [vp] * 8
     lib.sja_prepare_profiles.restype = ctypes.c_int
+    lib.sja_prepare_profiles_static.argtypes = [vp, vp, i32, i64] + [vp] * 8
+    lib.sja_prepare_profiles_static.restype = ctypes.c_int
     lib.sja_fit.argtypes = [vp, vp, i32] + [vp] * 4
     lib.sja_fit.restype = ctypes.c_int
     lib.sja_select.argtypes = [vp, vp, ctypes.POINTER(Params)] + [vp] * 7
@@ -175,16 +181,22 @@ class Engine:
         return float(ms.value)
 
     # -- the four calls --------------------------------------------------
-    def sja_prepare_profiles(self, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe):
+    def sja_prepare_profiles(self, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe,
+                             _entry="sja_prepare_profiles"):
         J = seg_off.numel() - 1
         S = dur.numel()
         args = (_ptr(seg_off, torch.int64, J + 1), _ptr(dur, torch.int32, S),
                 _ptr(mem, torch.int32, S), _ptr(safe, torch.uint8, S), _ptr(progress, torch.int32, J),
                 _ptr(pre_dur, torch.int32, S), _ptr(pre_peak, torch.int32, S),
                 _ptr(prev_safe, torch.int32, S))
-        rc = self.lib.sja_prepare_profiles(self.h, _stream(), J, S, *args)
+        rc = getattr(self.lib, _entry)(self.h, _stream(), J, S, *args)
         self._check(rc, self.h)
         self.n_jobs = J
+
+    def sja_prepare_profiles_static(self, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe):
+        """The same call on the library's built-in scratch: no workspace tensor is involved."""
+        self.sja_prepare_profiles(seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe,
+                                  _entry="sja_prepare_profiles_static")
 
     def sja_fit(self, W, C, cut, interest_bits=None):
         G = W.numel()

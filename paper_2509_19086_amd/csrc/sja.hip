@@ -2,12 +2,40 @@
 // bookkeeping and kernel launches.  See include/sja.h for the contract.
 #include "sja_kernels.h"
 
+#include <mutex>
 #include <new>
 #include <vector>
 
 using namespace sja;
 
+// Built-in scratch for callers that cannot allocate a workspace (see
+// sja_prepare_profiles_static).  Every GPU the library runs on holds its own
+// copy of this array, at its own address, until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress: kernels are given
+// the address that call returns, never the name.
+static __device__ __align__(256) unsigned char scratch[SJA_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, once known
+std::mutex g_scratch_mutex;
+
+// Address of the built-in scratch on `device`, which must be the current device.
+hipError_t static_scratch(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 struct DeviceGuard {
     int prev = -1;
@@ -403,6 +431,77 @@ JobLimits job_limits(const sja_limits &l, const int32_t *power, const int32_t *d
     return out;
 }
 
+// sja_prepare_profiles and its variant on the built-in scratch: the same checks and the same
+// kernel; only where the private tables live differs.
+int prepare_into(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
+                 const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                 const uint8_t *safe, const int32_t *progress, int32_t *pre_dur,
+                 int32_t *pre_peak, int32_t *prev_safe, bool on_static_scratch)
+{
+    ctx->prepared = false;
+    ctx->fitted = false;
+    ctx->planned = false;
+    if (n_jobs < 0 || n_jobs > SJA_MAX_JOBS) return fail(ctx, SJA_ERR_SIZE, "n_jobs");
+    if (n_segments < 0 || n_segments > SJA_MAX_SEGMENTS) return fail(ctx, SJA_ERR_SIZE, "n_segments");
+    if (!seg_off || !progress) return fail(ctx, SJA_ERR_NULL, "seg_off / progress");
+    if (n_segments > 0 && (!dur || !mem || !safe || !pre_dur || !pre_peak || !prev_safe))
+        return fail(ctx, SJA_ERR_NULL, "profile or output array");
+    const Layout L = make_layout(0, n_jobs, n_segments);
+    if (on_static_scratch) {
+        if (L.total > size_t(SJA_STATIC_SCRATCH_BYTES))
+            return fail(ctx, SJA_ERR_SIZE, "n_jobs / n_segments beyond what the built-in scratch holds "
+                                           "(sja_workspace_bytes(0, n_jobs, n_segments) > SJA_STATIC_SCRATCH_BYTES)");
+    } else if (!ctx->ws || ctx->ws_bytes < L.total) {
+        return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small for prepare");
+    }
+
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    if (on_static_scratch) {
+        void *p = nullptr;
+        SJA_HIP(static_scratch(ctx->device, &p), "hipGetSymbolAddress(scratch)");
+        ctx->ws = static_cast<char *>(p);
+        ctx->ws_bytes = size_t(SJA_STATIC_SCRATCH_BYTES);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_jobs > 0) {
+        const int jobs_per_block = 256 / kWave;
+        const dim3 grid((n_jobs + jobs_per_block - 1) / jobs_per_block), block(256);
+        const bool by_area = ctx->score_mode == SJA_SCORE_AREA;
+        long long *pre_area = by_area ? ws_ptr<long long>(ctx, L.pre_area) : nullptr;
+        long long *atom_area = by_area ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
+        if (ctx->limits_on) {
+            const JobLimits lim = job_limits(ctx->limits, ctx->lim_power, ctx->lim_deadline);
+            hipLaunchKernelGGL(k_prepare<true>, grid, block, 0, st, lim, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe, progress,
+                               pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
+                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int2>(ctx, L.first_dp));
+        } else {
+            hipLaunchKernelGGL(k_prepare<false>, grid, block, 0, st, JobLimits{}, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe,
+                               progress, pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
+                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
+                               ws_ptr<int2>(ctx, L.first_dp));
+        }
+        SJA_HIP(hipGetLastError(), "k_prepare launch");
+    }
+    ctx->limits_used = ctx->limits_on;
+    ctx->score_used = ctx->score_mode;
+    ctx->limits_applied = ctx->limits;
+    ctx->used_power = ctx->lim_power;
+    ctx->used_deadline = ctx->lim_deadline;
+    ctx->n_jobs = n_jobs;
+    ctx->n_segments = n_segments;
+    ctx->seg_off = seg_off;
+    ctx->dur = dur;
+    ctx->mem = mem;
+    ctx->safe = safe;
+    ctx->pre_dur = pre_dur;
+    ctx->pre_peak = pre_peak;
+    ctx->prev_safe = prev_safe;
+    ctx->prepared = true;
+    return SJA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -555,56 +654,18 @@ int sja_prepare_profiles(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_s
                          int32_t *pre_peak, int32_t *prev_safe)
 {
     if (!ctx) return SJA_ERR_NULL;
-    ctx->prepared = false;
-    ctx->fitted = false;
-    ctx->planned = false;
-    if (n_jobs < 0 || n_jobs > SJA_MAX_JOBS) return fail(ctx, SJA_ERR_SIZE, "n_jobs");
-    if (n_segments < 0 || n_segments > SJA_MAX_SEGMENTS) return fail(ctx, SJA_ERR_SIZE, "n_segments");
-    if (!seg_off || !progress) return fail(ctx, SJA_ERR_NULL, "seg_off / progress");
-    if (n_segments > 0 && (!dur || !mem || !safe || !pre_dur || !pre_peak || !prev_safe))
-        return fail(ctx, SJA_ERR_NULL, "profile or output array");
-    const Layout L = make_layout(0, n_jobs, n_segments);
-    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small for prepare");
+    return prepare_into(ctx, stream, n_jobs, n_segments, seg_off, dur, mem, safe, progress, pre_dur, pre_peak,
+                        prev_safe, false);
+}
 
-    DeviceGuard guard(ctx->device);
-    SJA_HIP(guard.err, "hipSetDevice");
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (n_jobs > 0) {
-        const int jobs_per_block = 256 / kWave;
-        const dim3 grid((n_jobs + jobs_per_block - 1) / jobs_per_block), block(256);
-        const bool by_area = ctx->score_mode == SJA_SCORE_AREA;
-        long long *pre_area = by_area ? ws_ptr<long long>(ctx, L.pre_area) : nullptr;
-        long long *atom_area = by_area ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
-        if (ctx->limits_on) {
-            const JobLimits lim = job_limits(ctx->limits, ctx->lim_power, ctx->lim_deadline);
-            hipLaunchKernelGGL(k_prepare<true>, grid, block, 0, st, lim, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe, progress,
-                               pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
-                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
-                               ws_ptr<int2>(ctx, L.first_dp));
-        } else {
-            hipLaunchKernelGGL(k_prepare<false>, grid, block, 0, st, JobLimits{}, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe,
-                               progress, pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
-                               ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
-                               ws_ptr<int2>(ctx, L.first_dp));
-        }
-        SJA_HIP(hipGetLastError(), "k_prepare launch");
-    }
-    ctx->limits_used = ctx->limits_on;
-    ctx->score_used = ctx->score_mode;
-    ctx->limits_applied = ctx->limits;
-    ctx->used_power = ctx->lim_power;
-    ctx->used_deadline = ctx->lim_deadline;
-    ctx->n_jobs = n_jobs;
-    ctx->n_segments = n_segments;
-    ctx->seg_off = seg_off;
-    ctx->dur = dur;
-    ctx->mem = mem;
-    ctx->safe = safe;
-    ctx->pre_dur = pre_dur;
-    ctx->pre_peak = pre_peak;
-    ctx->prev_safe = prev_safe;
-    ctx->prepared = true;
-    return SJA_OK;
+int sja_prepare_profiles_static(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
+                                const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                                const uint8_t *safe, const int32_t *progress, int32_t *pre_dur,
+                                int32_t *pre_peak, int32_t *prev_safe)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    return prepare_into(ctx, stream, n_jobs, n_segments, seg_off, dur, mem, safe, progress, pre_dur, pre_peak,
+                        prev_safe, true);
 }
 
 int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,

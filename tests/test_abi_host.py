@@ -137,3 +137,23 @@ def test_binding_refuses_cpu_tensors():
         e.sja_fit(x, x, x, None)
     with pytest.raises(TypeError):
         e.sja_fit(x.float(), x, x, None)
+
+
+def test_static_scratch_entry_point_checks_its_limit_on_the_host(lib):
+    """sja_prepare_profiles_static refuses what its built-in scratch cannot hold before it
+    touches a device, and applies the checks of sja_prepare_profiles first."""
+    vp = ctypes.c_void_p
+    h = vp()
+    assert lib.sja_create(ctypes.byref(h), 0) == 0
+    junk = vp(256)
+    text = open(os.path.join(ROOT, "include", "sja.h")).read()
+    limit = int(re.search(r"#define SJA_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text).group(1)) << \
+        int(re.search(r"#define SJA_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text).group(2))
+    assert lib.sja_workspace_bytes(0, 1024, 262144) <= limit < lib.sja_workspace_bytes(0, 32768, 1 << 25)
+    args = [junk] * 8
+    assert lib.sja_prepare_profiles_static(None, None, 4, 64, *args) == -1
+    assert lib.sja_prepare_profiles_static(h, None, -1, 64, *args) == -2
+    assert lib.sja_prepare_profiles_static(h, None, 4, 64, None, *args[1:]) == -1
+    assert lib.sja_prepare_profiles_static(h, None, 32768, 1 << 25, *args) == -2
+    assert b"built-in scratch" in lib.sja_last_error(h)
+    assert lib.sja_destroy(h) == 0
