@@ -38,140 +38,217 @@ __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
     if (i < n) p[i] = v;
 }
 
-constexpr int kRankSpan = 2048;  // gaps compared against per block in k_gap_rank
+// Rank of every gap in the order (C, W, index), in two steps: tiles of
+// kGapTile gaps are sorted in LDS (bitonic network over (key, index) pairs, which
+// are all distinct, so the order is total and the result exact), then every gap
+// adds up, over all tiles, how many pairs of the tile precede its own (a binary
+// search in the tile, staged in LDS; its position, inside its own tile).
+constexpr int kGapSortThreads = 1024;
+constexpr int kGapRankBlock = 256;
 
-__global__ __launch_bounds__(256) void k_gap_rank(int n_gaps, const int32_t *__restrict__ W,
-                                                  const int32_t *__restrict__ C,
-                                                  int32_t *__restrict__ rank)
+__device__ __forceinline__ bool gap_pair_less(unsigned long long ka, int ia, unsigned long long kb, int ib)
 {
-    __shared__ unsigned long long tile[256];
-    const int g = blockIdx.x * 256 + threadIdx.x;
-    const unsigned long long mine = g < n_gaps ? gap_key(W[g], C[g]) : 0ull;
-    const int h_begin = blockIdx.y * kRankSpan;
-    const int h_end = min(n_gaps, h_begin + kRankSpan);
-    int r = 0;
-    for (int h0 = h_begin; h0 < h_end; h0 += 256) {
-        const int h = h0 + threadIdx.x;
-        __syncthreads();
-        tile[threadIdx.x] = h < h_end ? gap_key(W[h], C[h]) : ~0ull;
-        __syncthreads();
-        const int n = min(256, h_end - h0);
-        for (int t = 0; t < n; ++t) {
-            const unsigned long long other = tile[t];
-            r += (other < mine) || (other == mine && (h0 + t) < g);
+    return ka < kb || (ka == kb && ia < ib);
+}
+
+__global__ __launch_bounds__(kGapSortThreads) void k_gap_tile_sort(int n_gaps, const int32_t *__restrict__ W,
+                                                                   const int32_t *__restrict__ C,
+                                                                   unsigned long long *__restrict__ tile_key,
+                                                                   int32_t *__restrict__ tile_idx, int32_t *plan,
+                                                                   int32_t *class_dmax)
+{
+    __shared__ unsigned long long s_key[kGapTile];
+    __shared__ int s_idx[kGapTile];
+    if (blockIdx.x == 0) {     // counters that later kernels of the sequence add to
+        if (threadIdx.x == 0) plan[kPlanMarks] = 0;
+        if (threadIdx.x < kMaxClasses) class_dmax[threadIdx.x] = INT32_MIN;
+    }
+    const int base = blockIdx.x * kGapTile;
+    for (int i = threadIdx.x; i < kGapTile; i += kGapSortThreads) {
+        const int g = base + i;
+        s_key[i] = g < n_gaps ? gap_key(W[g], C[g]) : ~0ull;      // padding sorts last (index beyond every gap)
+        s_idx[i] = g < n_gaps ? g : INT32_MAX;
+    }
+    __syncthreads();
+    for (int k = 2; k <= kGapTile; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < kGapTile / 2; t += kGapSortThreads) {
+                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1));     // the t-th index with bit j clear
+                const int hi = lo | j;
+                const bool up = (lo & k) == 0;
+                const unsigned long long ka = s_key[lo], kb = s_key[hi];
+                const int ia = s_idx[lo], ib = s_idx[hi];
+                if (gap_pair_less(kb, ib, ka, ia) == up) {
+                    s_key[lo] = kb; s_idx[lo] = ib;
+                    s_key[hi] = ka; s_idx[hi] = ia;
+                }
+            }
+            __syncthreads();
         }
     }
-    if (g < n_gaps && r) atomicAdd(&rank[g], r);
+    for (int i = threadIdx.x; i < kGapTile; i += kGapSortThreads) {
+        tile_key[base + i] = s_key[i];
+        tile_idx[base + i] = s_idx[i];
+    }
 }
 
-// Sorted copies of the gaps plus, per sorted position, the element offset of
-// the gap's cut row.
-__global__ void k_gap_scatter(int n_gaps, int n_jobs, const int32_t *__restrict__ W,
-                              const int32_t *__restrict__ C, const int32_t *__restrict__ rank,
-                              int32_t *__restrict__ order, int32_t *__restrict__ ws,
-                              int32_t *__restrict__ cs, int64_t *__restrict__ row)
+// One thread per entry of the sorted tiles.  rank[g] = number of gaps that precede g; the
+// gap's window, capacity, index and the element offset of its cut row go to that position of
+// the sorted copies.
+__global__ __launch_bounds__(kGapRankBlock) void k_gap_rank(int n_gaps, int n_jobs, int n_tiles,
+                                                            const unsigned long long *__restrict__ tile_key,
+                                                            const int32_t *__restrict__ tile_idx,
+                                                            const int32_t *__restrict__ W,
+                                                            const int32_t *__restrict__ C,
+                                                            int32_t *__restrict__ rank, int32_t *__restrict__ order,
+                                                            int32_t *__restrict__ ws, int32_t *__restrict__ cs,
+                                                            int64_t *__restrict__ row)
 {
-    const int g = blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= n_gaps) return;
-    const int r = rank[g];
-    order[r] = g;
-    ws[r] = W[g];
-    cs[r] = C[g];
-    row[r] = int64_t(g) * n_jobs;
+    __shared__ unsigned long long s_key[kGapTile];
+    __shared__ int s_idx[kGapTile];
+    const int e = blockIdx.x * kGapRankBlock + threadIdx.x;       // entry of the sorted tiles
+    const int own = e / kGapTile;
+    const unsigned long long key = tile_key[e];
+    const int idx = tile_idx[e];
+    int r = e - own * kGapTile;                                    // pairs of its own tile before it
+    for (int t = 0; t < n_tiles; ++t) {
+        if (t == own) continue;                                    // uniform over the block: kGapTile % kGapRankBlock == 0
+        __syncthreads();
+        for (int i = threadIdx.x; i < kGapTile; i += kGapRankBlock) {
+            s_key[i] = tile_key[t * kGapTile + i];
+            s_idx[i] = tile_idx[t * kGapTile + i];
+        }
+        __syncthreads();
+        int lo = 0, hi = kGapTile;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (gap_pair_less(s_key[mid], s_idx[mid], key, idx)) lo = mid + 1; else hi = mid;
+        }
+        r += lo;
+    }
+    if (idx < n_gaps) {
+        rank[idx] = r;
+        order[r] = idx;
+        ws[r] = W[idx];
+        cs[r] = C[idx];
+        row[r] = int64_t(idx) * n_jobs;
+    }
 }
 
-// run_end[s] = first sorted position after s whose capacity differs.
-__global__ void k_gap_run_end(int n_gaps, const int32_t *__restrict__ cs, int32_t *__restrict__ run_end)
+// Capacity classes = runs of equal C in the sorted order.  k_gap_marks appends the
+// first position of every run to a short list (a count beyond kMaxClasses only
+// says "too many": then the plan is not table-driven); k_gap_plan, every block
+// for itself, puts the list in order and derives the classes from it, then the
+// blocks share the per-position and per-chunk work.  The counters these kernels
+// add to are cleared by k_gap_tile_sort, the first kernel of the sequence.
+__global__ __launch_bounds__(256) void k_gap_marks(int n_gaps, const int32_t *__restrict__ cs, int32_t *plan,
+                                                   int32_t *__restrict__ marks)
 {
     const int s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= n_gaps) return;
-    const int c = cs[s];
-    int lo = s + 1, hi = n_gaps;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (cs[mid] <= c) lo = mid + 1; else hi = mid;
+    if (s == 0 || cs[s] != cs[s - 1]) {
+        const int i = atomicAdd(&plan[kPlanMarks], 1);
+        if (i <= kMaxClasses) marks[i] = s;
     }
-    run_end[s] = lo;
 }
 
-// One block.  Finds the capacity classes (runs of equal C) and cuts the sorted
-// positions into chunks of at most gc.  With at most kMaxClasses classes the
-// chunks never straddle a class and the table-driven path is used; otherwise
-// chunks are plain slices and the fit kernel searches for itself.
-__global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int sb, int chunk_bound,
-                                                   int sub_bound, const int32_t *__restrict__ cs,
-                                                   int32_t *plan, int32_t *class_begin,
-                                                   int32_t *class_chunk0, int32_t *class_sub0,
-                                                   int32_t *chunk_begin, int32_t *chunk_end,
-                                                   int32_t *chunk_class, int32_t *chunk_sub,
-                                                   int32_t *sub_begin, int32_t *sub_end,
-                                                   int32_t *sub_class, int32_t *gap_cls)
+// Chunks: at most gc sorted positions; sub-blocks: at most sb.  With at most
+// kMaxClasses classes neither straddles a class and the table-driven path is
+// used; otherwise chunks are plain slices and the stepping kernels search for
+// themselves.  Also: the class of every sorted position and run_end[s] = the
+// first position after s whose capacity differs.
+__global__ __launch_bounds__(256) void k_gap_plan(int n_gaps, int gc, int sb, int chunk_bound, int sub_bound,
+                                                  const int32_t *__restrict__ cs, const int32_t *__restrict__ marks,
+                                                  int32_t *plan, int32_t *class_begin,
+                                                  int32_t *class_chunk0, int32_t *class_sub0,
+                                                  int32_t *chunk_begin, int32_t *chunk_end,
+                                                  int32_t *chunk_class, int32_t *chunk_sub,
+                                                  int32_t *sub_begin, int32_t *sub_end,
+                                                  int32_t *sub_class, int32_t *__restrict__ gap_cls,
+                                                  int32_t *__restrict__ run_end)
 {
-    __shared__ int s_cnt[1024];
-    __shared__ int s_classes, s_chunks, s_tabled, s_subs;
+    static_assert(kMaxClasses <= kWave, "one wave scans the classes");
+    __shared__ int s_begin[kMaxClasses + 1], s_chunk0[kMaxClasses + 1], s_sub0[kMaxClasses + 1];
     const int t = threadIdx.x;
-    const int span = (n_gaps + 1023) / 1024;
-    const int lo = min(n_gaps, t * span), hi = min(n_gaps, lo + span);
-    int cnt = 0;
-    for (int s = lo; s < hi; ++s) cnt += (s == 0) || (cs[s] != cs[s - 1]);
-    s_cnt[t] = cnt;
-    __syncthreads();
-    if (t == 0) {
-        int acc = 0;
-        for (int i = 0; i < 1024; ++i) { const int c = s_cnt[i]; s_cnt[i] = acc; acc += c; }
-        s_classes = acc;
-        s_tabled = acc <= kMaxClasses;
-    }
-    __syncthreads();
-    const int n_classes = s_classes;
-    const bool tabled = s_tabled != 0;
-    {   // capacity class of every sorted position
-        int k = s_cnt[t];
-        for (int s = lo; s < hi; ++s) {
-            k += (s == 0) || (cs[s] != cs[s - 1]);
-            gap_cls[s] = k - 1;
-        }
-    }
+    const int n_marks = plan[kPlanMarks];
+    const bool tabled = n_marks <= kMaxClasses;
+    const int n_classes = n_marks;
+    int n_chunks = 0, n_subs = 0;
     if (tabled) {
-        int k = s_cnt[t];
-        for (int s = lo; s < hi; ++s)
-            if ((s == 0) || (cs[s] != cs[s - 1])) class_begin[k++] = s;
-        if (t == 0) class_begin[n_classes] = n_gaps;
-    }
-    __syncthreads();
-    if (t == 0) {
-        int q = 0, u = 0;
-        if (tabled) {
-            for (int c = 0; c < n_classes; ++c) {
-                class_chunk0[c] = q;
-                class_sub0[c] = u;
-                const int len = class_begin[c + 1] - class_begin[c];
-                q += (len + gc - 1) / gc;
-                u += (len + sb - 1) / sb;
+        if (t < kWave) {
+            // the marks in ascending order (each lane counts the marks below its own), then the
+            // first chunk and the first sub-block of every class by a scan over the class lengths
+            const int mine = t < n_classes ? marks[t] : INT32_MAX;
+            int r = 0;
+#pragma unroll 8
+            for (int i = 0; i < kWave; ++i) r += __builtin_amdgcn_readlane(mine, i) < mine;
+            if (t < n_classes) s_begin[r] = mine;
+            if (t == 0) s_begin[n_classes] = n_gaps;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int len = t < n_classes ? s_begin[t + 1] - s_begin[t] : 0;
+            const int nq = (len + gc - 1) / gc, nu = (len + sb - 1) / sb;
+            int iq = nq, iu = nu;
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const int oq = __shfl_up(iq, d, kWave), ou = __shfl_up(iu, d, kWave);
+                if (t >= d) { iq += oq; iu += ou; }
             }
-            class_chunk0[n_classes] = q;
-            class_sub0[n_classes] = u;
-        } else {
-            q = (n_gaps + gc - 1) / gc;
+            if (t < n_classes) { s_chunk0[t] = iq - nq; s_sub0[t] = iu - nu; }
+            if (t == kWave - 1) { s_chunk0[n_classes] = iq; s_sub0[n_classes] = iu; }
         }
-        s_chunks = min(q, chunk_bound);
-        s_subs = min(u, sub_bound);
-        plan[kPlanClasses] = n_classes;
-        plan[kPlanChunks] = s_chunks;
-        plan[kPlanTabled] = tabled ? 1 : 0;
-        plan[kPlanSubBlocks] = s_subs;
+        __syncthreads();
+        n_chunks = min(s_chunk0[n_classes], chunk_bound);
+        n_subs = min(s_sub0[n_classes], sub_bound);
+    } else {
+        n_chunks = min((n_gaps + gc - 1) / gc, chunk_bound);
     }
-    __syncthreads();
-    const int n_chunks = s_chunks;
-    for (int q = t; q < n_chunks; q += 1024) {
+    if (blockIdx.x == 0) {
+        if (tabled && t <= n_classes) {
+            class_begin[t] = s_begin[t];
+            class_chunk0[t] = s_chunk0[t];
+            class_sub0[t] = s_sub0[t];
+        }
+        if (t == 0) {
+            plan[kPlanClasses] = n_classes;
+            plan[kPlanChunks] = n_chunks;
+            plan[kPlanTabled] = tabled ? 1 : 0;
+            plan[kPlanSubBlocks] = n_subs;
+        }
+    }
+    const int gid = blockIdx.x * blockDim.x + t, stride = gridDim.x * blockDim.x;
+    auto class_of = [&](const int *first, int v) {      // last class whose first item is <= v
+        int lo = 0, hi = n_classes;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (first[mid] <= v) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    for (int s = gid; s < n_gaps; s += stride) {
         if (tabled) {
-            int c = 0;
-            while (c + 1 < n_classes && class_chunk0[c + 1] <= q) ++c;
-            const int b = class_begin[c] + (q - class_chunk0[c]) * gc;
+            const int c = class_of(s_begin, s);
+            gap_cls[s] = c;
+            run_end[s] = s_begin[c + 1];
+        } else {
+            const int c = cs[s];
+            int lo = s + 1, hi = n_gaps;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (cs[mid] <= c) lo = mid + 1; else hi = mid;
+            }
+            run_end[s] = lo;
+        }
+    }
+    for (int q = gid; q < n_chunks; q += stride) {
+        if (tabled) {
+            const int c = class_of(s_chunk0, q);
+            const int b = s_begin[c] + (q - s_chunk0[c]) * gc;
             chunk_begin[q] = b;
-            chunk_end[q] = min(class_begin[c + 1], b + gc);
+            chunk_end[q] = min(s_begin[c + 1], b + gc);
             chunk_class[q] = c;
-            chunk_sub[q] = class_sub0[c] + (q - class_chunk0[c]) * (gc / sb);
+            chunk_sub[q] = s_sub0[c] + (q - s_chunk0[c]) * (gc / sb);
         } else {
             chunk_begin[q] = q * gc;
             chunk_end[q] = min(n_gaps, q * gc + gc);
@@ -179,70 +256,276 @@ __global__ __launch_bounds__(1024) void k_gap_plan(int n_gaps, int gc, int sb, i
             chunk_sub[q] = 0;
         }
     }
-    const int n_subs = s_subs;
-    for (int u = t; u < n_subs; u += 1024) {
-        int c = 0;
-        while (c + 1 < n_classes && class_sub0[c + 1] <= u) ++c;
-        const int b = class_begin[c] + (u - class_sub0[c]) * sb;
+    for (int u = gid; u < n_subs; u += stride) {
+        const int c = class_of(s_sub0, u);
+        const int b = s_begin[c] + (u - s_sub0[c]) * sb;
         sub_begin[u] = b;
-        sub_end[u] = min(class_begin[c + 1], b + sb);
+        sub_end[u] = min(s_begin[c + 1], b + sb);
         sub_class[u] = c;
     }
 }
 
 // --------------------------------------------------------------------------
-// Start tables (table-driven path).  Thread (job j, class c) walks the job's
-// atoms once, in order, against the windows of the first gap of each of the
-// class's sub-blocks (runs of `sb` sorted positions; a chunk is a whole number
-// of them), ascending:
-//   start[u][j] = #atoms usable by the first gap of sub-block u
-//   ncap[c][j]  = #atoms any gap of class c can reach (peak <= C_c and
-//                 duration <= the class's largest window)
+// Start tables (table-driven path).  A row is a run of sorted positions of one
+// capacity class: the chunks of the stepping kernels (the table sja_fit and
+// sja_fit_select need) or the finer sub-blocks (the table the grant lists are
+// built from).
+//   start[row][j] = #atoms of job j usable by the first gap of the row
+//   ncap[c][j]    = #atoms any gap of class c can reach (peak <= C_c and
+//                   duration <= the class's largest window); null: not wanted
+// One wave per job: the job's atoms go to LDS once (coalesced), then the lanes
+// run along the classes and along the rows, each lane with a binary search of
+// its own: both counts are "how many atoms have a running duration (peak) of at
+// most x", and both sequences ascend.  Every global access is one trip; a walk
+// along the atoms per (job, class) paid one per cache line of atoms.
 // --------------------------------------------------------------------------
+constexpr int kStartsAtoms = 512;           // atoms of a job kept in LDS (more: the rest is read from memory)
+constexpr int kStartsJobs = 4;              // jobs a wave takes, one after the other
+constexpr int kStartsRows = 1024;           // rows whose window and class are kept in LDS
+
 __global__ __launch_bounds__(256) void k_fit_starts(
-    int n_jobs, int sb, const int32_t *__restrict__ plan, const int32_t *__restrict__ class_begin,
-    const int32_t *__restrict__ class_sub0, const int32_t *__restrict__ gap_w,
+    int n_jobs, int rows_word, const int32_t *__restrict__ plan, const int32_t *__restrict__ class_begin,
+    const int32_t *__restrict__ row_begin, const int32_t *__restrict__ row_class, const int32_t *__restrict__ gap_w,
     const int32_t *__restrict__ gap_c, const int64_t *__restrict__ seg_off,
     const int2 *__restrict__ atom_dp, const int32_t *__restrict__ n_atoms,
     int32_t *__restrict__ start_tab, int32_t *__restrict__ ncap_tab)
 {
+    constexpr int WAVES = 256 / kWave;
+    __shared__ int2 s_at[WAVES][kStartsAtoms];
+    __shared__ int s_roww[kStartsRows];
+    __shared__ int s_rowc[kStartsRows];
+    __shared__ int s_cap[kMaxClasses], s_wmax[kMaxClasses];
+    __shared__ int s_ncap[WAVES][kMaxClasses];
+    if (!plan[kPlanTabled]) return;
+    const int n_classes = plan[kPlanClasses], n_rows = plan[rows_word];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    for (int q = tid; q < min(n_rows, kStartsRows); q += 256) {
+        s_roww[q] = gap_w[row_begin[q]];
+        s_rowc[q] = row_class[q];
+    }
+    if (tid < n_classes) {
+        s_cap[tid] = gap_c[class_begin[tid]];
+        s_wmax[tid] = gap_w[class_begin[tid + 1] - 1];
+    }
+    __syncthreads();
+    int2 *at = s_at[wave];
+    for (int i = 0; i < kStartsJobs; ++i) {
+        const int j = (blockIdx.x * WAVES + wave) * kStartsJobs + i;
+        if (j >= n_jobs) break;                     // uniform over the wave
+        const int2 *dp = atom_dp + seg_off[j];
+        const int n = n_atoms[j];
+        for (int a = lane; a < min(n, kStartsAtoms); a += kWave) at[a] = dp[a];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        auto atom = [&](int a) { return a < kStartsAtoms ? at[a] : dp[a]; };
+        auto count_dur = [&](int w) {               // atoms with running duration <= w
+            int lo = 0, hi = n;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (atom(mid).x <= w) lo = mid + 1; else hi = mid;
+            }
+            return lo;
+        };
+        if (lane < n_classes) {
+            const int cap = s_cap[lane];
+            int lo = 0, hi = n;                     // atoms with running peak <= cap
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (atom(mid).y <= cap) lo = mid + 1; else hi = mid;
+            }
+            const int reach = min(lo, count_dur(s_wmax[lane]));
+            s_ncap[wave][lane] = reach;
+            if (ncap_tab) ncap_tab[int64_t(lane) * n_jobs + j] = reach;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int q = lane; q < n_rows; q += kWave) {
+            const int w = q < kStartsRows ? s_roww[q] : gap_w[row_begin[q]];
+            const int c = q < kStartsRows ? s_rowc[q] : row_class[q];
+            start_tab[int64_t(q) * n_jobs + j] = min(count_dur(w), s_ncap[wave][c]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();             // the next job overwrites the atoms
+    }
+}
+
+// --------------------------------------------------------------------------
+// Interest rows.  A job answers a gap with interest exactly when its first
+// atom fits (running duration and running peak only grow along the atoms), so
+// bit j of a gap's row is D_first(j) <= W && P_first(j) <= C.  Per capacity
+// class a table holds, for every 32-job word, the jobs whose first atom fits the
+// capacity, and the largest first duration among all of those: a gap whose
+// window reaches that duration gets the class's words as they are (a row copy);
+// the few gaps below it (the bottom of every class in the sorted order) and all
+// gaps of a plan without class tables are evaluated job by job, lanes along
+// jobs, one ballot per 64 jobs.  A block takes kBitsRows sorted positions and
+// 1024 words of their rows.
+// --------------------------------------------------------------------------
+// table[c][word] and dmax[c] for the classes of the table-driven plan (dmax is
+// cleared by k_gap_tile_sort)
+__global__ __launch_bounds__(256) void k_bits_table(int n_jobs, int words, const int32_t *__restrict__ plan,
+                                                    const int32_t *__restrict__ class_begin,
+                                                    const int32_t *__restrict__ gap_c,
+                                                    const int2 *__restrict__ first_dp, uint32_t *__restrict__ table,
+                                                    int32_t *class_dmax)
+{
+    const int word = blockIdx.x * blockDim.x + threadIdx.x;
     const int c = blockIdx.y;
     if (!plan[kPlanTabled] || c >= plan[kPlanClasses]) return;
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= n_jobs) return;
-    const int pos_b = class_begin[c], pos_e = class_begin[c + 1];
-    const int cap = gap_c[pos_b];
-    const int w_max = gap_w[pos_e - 1];
-    const int q0 = class_sub0[c], qe = class_sub0[c + 1];
-    const int2 *dp = atom_dp + seg_off[j];
-    const int n = n_atoms[j];
+    const int cap = gap_c[class_begin[c]];
+    uint32_t fits = 0;
+    int d_max = INT32_MIN;
+    if (word < words) {
+        int2 f[32];
+#pragma unroll
+        for (int b = 0; b < 32; ++b) f[b] = first_dp[min(word * 32 + b, n_jobs - 1)];
+#pragma unroll
+        for (int b = 0; b < 32; ++b) {
+            if (word * 32 + b < n_jobs && f[b].y <= cap && f[b].x != INT32_MAX) {
+                fits |= 1u << b;
+                d_max = max(d_max, f[b].x);
+            }
+        }
+        table[int64_t(c) * words + word] = fits;
+    }
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) d_max = max(d_max, __shfl_xor(d_max, d, kWave));
+    if ((threadIdx.x & (kWave - 1)) == 0 && d_max != INT32_MIN) atomicMax(&class_dmax[c], d_max);
+}
 
-    int q = q0;
-    int w_q = gap_w[pos_b];
-    int reach = n;
-    bool done = false;
-    for (int b0 = 0; b0 < n && !done; b0 += 4) {
-        int2 v[4];
+constexpr int kBitsRows = 16;      // sorted gap positions per block
+constexpr int kBitsWords = 4;      // consecutive 32-job words per thread
+
+struct BitsArgs {
+    uint32_t *bits;
+    const int2 *first_dp;
+    const uint32_t *table;
+    const int32_t *class_dmax;
+    const int32_t *gap_order;
+    const int32_t *gap_cls;
+    int n_gaps, words;
+};
+
+__global__ __launch_bounds__(256) void k_fit_bits(BitsArgs B, int n_jobs, const int32_t *__restrict__ plan,
+                                                  const int32_t *__restrict__ gap_w, const int32_t *__restrict__ gap_c)
+{
+    __shared__ int s_dmax[kMaxClasses];
+    const int words = B.words;
+    const int col_tiles = (words + 256 * kBitsWords - 1) / (256 * kBitsWords);
+    const int ct = int(blockIdx.x % unsigned(col_tiles)), rt = int(blockIdx.x / unsigned(col_tiles));
+    const int tid = threadIdx.x;
+    const int w0 = (ct * 256 + tid) * kBitsWords;
+    const int s_begin = rt * kBitsRows, s_end = min(B.n_gaps, s_begin + kBitsRows);
+    if (s_begin >= s_end) return;
+    const bool tabled = plan[kPlanTabled] != 0;
+    if (tid < kMaxClasses) s_dmax[tid] = B.class_dmax[tid];
+    const int nw = max(0, min(kBitsWords, words - w0));
+    const bool wide = nw == kBitsWords && (words % kBitsWords) == 0 &&      // 16-byte aligned row pieces
+                      (reinterpret_cast<uintptr_t>(B.bits) & 15u) == 0;
+    // the rows of this block (uniform over the block, so these sit in scalar registers)
+    int gq[kBitsRows], wq[kBitsRows], cq[kBitsRows], kq[kBitsRows];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) v[t] = dp[b0 + t];      // the tables carry 8 entries of padding
+    for (int r = 0; r < kBitsRows; ++r) {
+        const int s = min(s_begin + r, s_end - 1);
+        gq[r] = B.gap_order[s];
+        wq[r] = gap_w[s];
+        cq[r] = gap_c[s];
+        kq[r] = tabled ? B.gap_cls[s] : 0;
+    }
+    __syncthreads();
+    if (tabled) {
+        // a gap whose window reaches the class's largest first duration gets the class's words; the
+        // gaps below it are k_fit_bits_low's
+        int cls = -1;
+        uint32_t e[kBitsWords] = {0, 0, 0, 0};
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int idx = b0 + t;
-            if (done) continue;
-            if (idx >= n || v[t].y > cap || v[t].x > w_max) {
-                done = true;
-                reach = idx;
+        for (int r = 0; r < kBitsRows; ++r) {
+            if (s_begin + r >= s_end) break;
+            const int c = kq[r];
+            if (wq[r] < s_dmax[c] || nw <= 0) continue;
+            if (c != cls) {
+                cls = c;
+#pragma unroll
+                for (int i = 0; i < kBitsWords; ++i)
+                    if (i < nw) e[i] = B.table[int64_t(c) * words + w0 + i];
+            }
+            uint32_t *dst = B.bits + int64_t(gq[r]) * words + w0;
+            if (wide) {
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(e[0], e[1], e[2], e[3]);
             } else {
-                while (q < qe && v[t].x > w_q) {
-                    start_tab[int64_t(q) * n_jobs + j] = idx;
-                    ++q;
-                    if (q < qe) w_q = gap_w[pos_b + (q - q0) * sb];
-                }
+#pragma unroll
+                for (int i = 0; i < kBitsWords; ++i)
+                    if (i < nw) dst[i] = e[i];
+            }
+        }
+        return;
+    }
+    // no class tables: job by job, lanes along the jobs of this block's words, a 64-job ballot per
+    // wave and row
+    const int lane = tid & (kWave - 1);
+    const int j_begin = ct * 256 * kBitsWords * 32;
+    const int j_end = min(n_jobs, j_begin + 256 * kBitsWords * 32);
+    constexpr int AHEAD = 8;       // first atoms asked for together: the loop is a chain of memory trips otherwise
+    for (int jb = j_begin + (tid - lane); jb < j_end; jb += 256 * AHEAD) {      // jb: first job of this wave's first 64
+        int2 f[AHEAD];
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) f[k] = B.first_dp[min(jb + k * 256 + lane, n_jobs - 1)];
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k) {
+            const int j0 = jb + k * 256;
+            if (j0 >= j_end) break;                                             // uniform over the wave
+            const bool real = j0 + lane < n_jobs && f[k].x != INT32_MAX;
+#pragma unroll
+            for (int r = 0; r < kBitsRows; ++r) {
+                if (s_begin + r >= s_end) break;
+                const unsigned long long m = __ballot(real && f[k].x <= wq[r] && f[k].y <= cq[r]);
+                uint32_t *dst = B.bits + int64_t(gq[r]) * words + (j0 >> 5);
+                if (lane == 0) dst[0] = uint32_t(m);
+                if (lane == 32 && (j0 >> 5) + 1 < words) dst[1] = uint32_t(m >> 32);
             }
         }
     }
-    for (; q < qe; ++q) start_tab[int64_t(q) * n_jobs + j] = reach;
-    ncap_tab[int64_t(c) * n_jobs + j] = reach;
+}
+
+// The rows at the bottom of a class: windows below the class's largest first
+// duration.  Thread (class c, word): the first durations of the word's 32 jobs
+// are fetched once and compared with every such window in turn; a wave stores
+// 256 contiguous bytes of a row per step.
+__global__ __launch_bounds__(256) void k_fit_bits_low(BitsArgs B, int n_jobs, const int32_t *__restrict__ plan,
+                                                      const int32_t *__restrict__ class_begin,
+                                                      const int32_t *__restrict__ gap_w)
+{
+    const int c = blockIdx.y;
+    if (!plan[kPlanTabled] || c >= plan[kPlanClasses]) return;
+    const int words = B.words;
+    const int word = blockIdx.x * blockDim.x + threadIdx.x;
+    const int dmax = B.class_dmax[c];
+    const int pos_b = class_begin[c], pos_e = class_begin[c + 1];
+    if (gap_w[pos_b] >= dmax) return;                    // no such row in this class (uniform)
+    const bool live = word < words;
+    const uint32_t fits = live ? B.table[int64_t(c) * words + word] : 0u;
+    int d[32];
+#pragma unroll
+    for (int b = 0; b < 32; ++b) d[b] = B.first_dp[min(word * 32 + b, n_jobs - 1)].x;
+    for (int s0 = pos_b; s0 < pos_e; s0 += 8) {
+        int wv[8], gv[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int s = min(s0 + t, pos_e - 1);
+            wv[t] = gap_w[s];
+            gv[t] = B.gap_order[s];
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            if (s0 + t >= pos_e || wv[t] >= dmax) return;         // windows ascend inside a class (uniform)
+            uint32_t le = 0;
+#pragma unroll
+            for (int b = 0; b < 32; ++b) le |= (d[b] <= wv[t] ? 1u : 0u) << b;
+            if (live) B.bits[int64_t(gv[t]) * words + word] = le & fits;
+        }
+    }
 }
 
 // --------------------------------------------------------------------------
@@ -316,7 +599,7 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     auto init = [&](int s) {
         c_cur = gap_c[s];
         if (tabled) {
-            a = start_tab[int64_t(chunk_sub[chunk]) * n_jobs + j];
+            a = start_tab[int64_t(chunk) * n_jobs + j];
             n_cap = ncap_tab[int64_t(chunk_class[chunk]) * n_jobs + j];
         } else {
             n_cap = upper_bound_peak(dp, n, c_cur);
@@ -400,94 +683,6 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
                 step(gap_w[s], gap_row[s]);
             }
         }
-    }
-}
-
-// --------------------------------------------------------------------------
-// Interest rows.  A job answers a gap with interest exactly when its first
-// atom fits (running duration and running peak only grow along the atoms), so
-// bit j of a gap's row is D_first(j) <= W && P_first(j) <= C.  Per (capacity
-// class, 32-job word) a small table holds the word of jobs whose first atom
-// fits the capacity and the smallest and largest first duration among them:
-// a window at or above the largest gives that word, one below the smallest
-// gives 0, and only windows in between (a few hundred ticks at the bottom of a
-// class) look at the 32 jobs one by one.  One thread per (gap, word); a wave
-// stores 256 contiguous bytes of a row.
-// --------------------------------------------------------------------------
-__device__ __forceinline__ int4 bits_word_entry(int n_jobs, int j0, int c, const int2 *__restrict__ first_dp)
-{
-    int2 f[32];
-#pragma unroll
-    for (int b = 0; b < 32; ++b) f[b] = first_dp[min(j0 + b, n_jobs - 1)];
-    uint32_t fits = 0;
-    int d_min = INT32_MAX, d_max = INT32_MIN;
-#pragma unroll
-    for (int b = 0; b < 32; ++b) {
-        if (j0 + b < n_jobs && f[b].y <= c && f[b].x != INT32_MAX) {
-            fits |= 1u << b;
-            d_min = min(d_min, f[b].x);
-            d_max = max(d_max, f[b].x);
-        }
-    }
-    return make_int4(int(fits), d_min, d_max, 0);
-}
-
-// table[c][word] for the classes of the table-driven plan
-__global__ __launch_bounds__(256) void k_bits_table(int n_jobs, int words, const int32_t *__restrict__ plan,
-                                                    const int32_t *__restrict__ class_begin,
-                                                    const int32_t *__restrict__ gap_c,
-                                                    const int2 *__restrict__ first_dp, int4 *__restrict__ table)
-{
-    const int word = blockIdx.x * blockDim.x + threadIdx.x;
-    const int c = blockIdx.y;
-    if (!plan[kPlanTabled] || c >= plan[kPlanClasses] || word >= words) return;
-    table[int64_t(c) * words + word] = bits_word_entry(n_jobs, word * 32, gap_c[class_begin[c]], first_dp);
-}
-
-constexpr int kBitsRows = 8;       // gaps per block
-
-// Rows are taken in the caller's gap order, so the blocks write the interest
-// matrix front to back.
-__global__ __launch_bounds__(256) void k_fit_bits(int n_jobs, int n_gaps, int words,
-                                                  const int32_t *__restrict__ plan,
-                                                  const int2 *__restrict__ first_dp,
-                                                  const int4 *__restrict__ table,
-                                                  const int32_t *__restrict__ gap_rank,
-                                                  const int32_t *__restrict__ gap_cls,
-                                                  const int32_t *__restrict__ gap_w,
-                                                  const int32_t *__restrict__ gap_c,
-                                                  uint32_t *__restrict__ bits)
-{
-    const int word = blockIdx.x * blockDim.x + threadIdx.x;
-    if (word >= words) return;
-    const bool tabled = plan[kPlanTabled] != 0;
-    const int j0 = word * 32;
-    const int g_begin = blockIdx.y * kBitsRows, g_end = min(n_gaps, g_begin + kBitsRows);
-    int pos[kBitsRows];
-#pragma unroll
-    for (int r = 0; r < kBitsRows; ++r) pos[r] = gap_rank[min(g_begin + r, n_gaps - 1)];
-    int cls = -1;
-    int4 e = make_int4(0, INT32_MAX, INT32_MIN, 0);
-#pragma unroll
-    for (int r = 0; r < kBitsRows; ++r) {
-        const int g = g_begin + r;
-        if (g >= g_end) break;
-        const int s = pos[r];
-        const int w = gap_w[s];
-        if (tabled) {
-            const int c = gap_cls[s];
-            if (c != cls) { cls = c; e = table[int64_t(c) * words + word]; }
-        } else {
-            e = bits_word_entry(n_jobs, j0, gap_c[s], first_dp);
-        }
-        uint32_t v = 0;
-        if (w >= e.z) {
-            v = uint32_t(e.x);
-        } else if (w >= e.y) {
-            for (int b = 0; b < 32; ++b)
-                if ((uint32_t(e.x) >> b) & 1u) v |= (first_dp[j0 + b].x <= w ? 1u : 0u) << b;
-        }
-        bits[int64_t(g) * words + word] = v;
     }
 }
 

@@ -177,7 +177,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
         if (!usable) {
             n_cap = 0; a = 0;
         } else if (tabled) {
-            a = start_tab[int64_t(chunk_sub[chunk]) * n_jobs + j];
+            a = start_tab[int64_t(chunk) * n_jobs + j];
             n_cap = ncap_tab[int64_t(chunk_class[chunk]) * n_jobs + j];
         } else {
             n_cap = upper_bound_peak(dp, n, c_cur);

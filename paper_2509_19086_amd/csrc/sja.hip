@@ -208,7 +208,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     const int32_t *sub_class = ws_ptr<int32_t>(ctx, L.sub_class);
     int32_t *lb_begin = ws_ptr<int32_t>(ctx, L.lb_begin), *lb_end = ws_ptr<int32_t>(ctx, L.lb_end);
     int32_t *lb_sub = ws_ptr<int32_t>(ctx, L.lb_sub), *lb_off = ws_ptr<int32_t>(ctx, L.lb_off);
-    const int32_t *start_tab = ws_ptr<int32_t>(ctx, L.start_tab), *ncap_tab = ws_ptr<int32_t>(ctx, L.ncap_tab);
+    const int32_t *ncap_tab = ws_ptr<int32_t>(ctx, L.ncap_tab);
     const int32_t *gap_w = ws_ptr<int32_t>(ctx, L.gap_w);
     unsigned long long *key_hi = ws_ptr<unsigned long long>(ctx, L.g_key_hi);
     unsigned long long *key_lo = ws_ptr<unsigned long long>(ctx, L.g_key_lo);
@@ -226,6 +226,13 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     hipLaunchKernelGGL(k_list_blocks_write, dim3((sub_bound + 255) / 256), dim3(256), 0, st, lb_bound, plan, sub_begin,
                        sub_end, gap_w, lb_off, lb_begin, lb_end, lb_sub);
     SJA_HIP(hipGetLastError(), "list block launch");
+    // where every sub-block starts in every job's atom list (the fit only keeps this per chunk)
+    int32_t *sub_tab = ws_ptr<int32_t>(ctx, L.sub_tab);
+    const int starts_jobs = (256 / kWave) * kStartsJobs;
+    hipLaunchKernelGGL(k_fit_starts, dim3((J + starts_jobs - 1) / starts_jobs), dim3(256), 0, st, J, int(kPlanSubBlocks), plan,
+                       ws_ptr<int32_t>(ctx, L.class_begin), sub_begin, sub_class, gap_w, ws_ptr<int32_t>(ctx, L.gap_c),
+                       ctx->seg_off, atom_dp, ws_ptr<int32_t>(ctx, L.n_atoms), sub_tab, static_cast<int32_t *>(nullptr));
+    SJA_HIP(hipGetLastError(), "k_fit_starts launch");
     hipLaunchKernelGGL(k_reach, dim3((J + 1 + 255) / 256), dim3(256), 0, st, J, plan, ncap_tab, abase);
     SJA_HIP(hipGetLastError(), "k_reach launch");
     SJA_HIP(enqueue_scan(st, abase, int64_t(J) + 1, tmp, counters + 2), "atom scan launch");
@@ -282,7 +289,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     const int sub_bits = bits_for(n_subs > 1 ? n_subs : 2);
     const dim3 emit_grid((J + 256 * kEmitTiles - 1) / (256 * kEmitTiles), lb_bound);
     hipLaunchKernelGGL(k_list_emit, emit_grid, dim3(256), 0, st, J, rank_bits, lb_bound, (long long)L.entry_cap, plan,
-                       lb_begin, lb_end, lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, start_tab, ncap_tab, abase, rank,
+                       lb_begin, lb_end, lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, sub_tab, ncap_tab, abase, rank,
                        list_off, reinterpret_cast<unsigned long long *>(counters), ekey[0]);
     SJA_HIP(hipGetLastError(), "k_list_emit launch");
     long long n_entries = 0;
@@ -390,30 +397,35 @@ int enqueue_gap_plan(sja_ctx *ctx, hipStream_t st, const Layout &L, int32_t n_ga
     int32_t *rank = ws_ptr<int32_t>(ctx, L.gap_rank);
     int32_t *gw = ws_ptr<int32_t>(ctx, L.gap_w), *gcap = ws_ptr<int32_t>(ctx, L.gap_c);
     int32_t *plan = ws_ptr<int32_t>(ctx, L.plan);
-    hipLaunchKernelGGL(k_fill_i32, per_gap, b256, 0, st, rank, int64_t(n_gaps), 0);
-    SJA_HIP(hipGetLastError(), "k_fill_i32 launch");
-    hipLaunchKernelGGL(k_gap_rank, dim3((n_gaps + 255) / 256, (n_gaps + kRankSpan - 1) / kRankSpan), b256, 0, st,
-                       n_gaps, W, C, rank);
+    const int gap_tiles = (n_gaps + kGapTile - 1) / kGapTile;
+    unsigned long long *tile_key = ws_ptr<unsigned long long>(ctx, L.gap_tile_key);
+    int32_t *tile_idx = ws_ptr<int32_t>(ctx, L.gap_tile_idx);
+    hipLaunchKernelGGL(k_gap_tile_sort, dim3(gap_tiles), dim3(kGapSortThreads), 0, st, n_gaps, W, C, tile_key, tile_idx,
+                       plan, ws_ptr<int32_t>(ctx, L.class_dmax));
+    SJA_HIP(hipGetLastError(), "k_gap_tile_sort launch");
+    hipLaunchKernelGGL(k_gap_rank, dim3(gap_tiles * (kGapTile / kGapRankBlock)), dim3(kGapRankBlock), 0, st, n_gaps, J,
+                       gap_tiles, tile_key, tile_idx, W, C, rank, ws_ptr<int32_t>(ctx, L.gap_order), gw, gcap,
+                       ws_ptr<int64_t>(ctx, L.gap_row));
     SJA_HIP(hipGetLastError(), "k_gap_rank launch");
-    hipLaunchKernelGGL(k_gap_scatter, per_gap, b256, 0, st, n_gaps, J, W, C, rank,
-                       ws_ptr<int32_t>(ctx, L.gap_order), gw, gcap, ws_ptr<int64_t>(ctx, L.gap_row));
-    SJA_HIP(hipGetLastError(), "k_gap_scatter launch");
     if (J > 0) {
-        hipLaunchKernelGGL(k_gap_run_end, per_gap, b256, 0, st, n_gaps, gcap,
-                           ws_ptr<int32_t>(ctx, L.gap_run_end));
-        SJA_HIP(hipGetLastError(), "k_gap_run_end launch");
-        hipLaunchKernelGGL(k_gap_plan, dim3(1), dim3(1024), 0, st, n_gaps, gc, sb, chunk_bound, sub_bound, gcap,
+        int32_t *marks = ws_ptr<int32_t>(ctx, L.class_marks);
+        hipLaunchKernelGGL(k_gap_marks, per_gap, b256, 0, st, n_gaps, gcap, plan, marks);
+        SJA_HIP(hipGetLastError(), "k_gap_marks launch");
+        const int plan_blocks = (n_gaps + 255) / 256 < 64 ? (n_gaps + 255) / 256 : 64;
+        hipLaunchKernelGGL(k_gap_plan, dim3(plan_blocks), b256, 0, st, n_gaps, gc, sb, chunk_bound, sub_bound, gcap, marks,
                            plan, ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_chunk0),
                            ws_ptr<int32_t>(ctx, L.class_sub0), ws_ptr<int32_t>(ctx, L.chunk_begin),
                            ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
                            ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.sub_begin),
                            ws_ptr<int32_t>(ctx, L.sub_end), ws_ptr<int32_t>(ctx, L.sub_class),
-                           ws_ptr<int32_t>(ctx, L.gap_cls));
+                           ws_ptr<int32_t>(ctx, L.gap_cls), ws_ptr<int32_t>(ctx, L.gap_run_end));
         SJA_HIP(hipGetLastError(), "k_gap_plan launch");
-        hipLaunchKernelGGL(k_fit_starts, dim3((J + 255) / 256, kMaxClasses), b256, 0, st, J, sb, plan,
-                           ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.class_sub0), gw, gcap,
-                           ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int32_t>(ctx, L.n_atoms),
-                           ws_ptr<int32_t>(ctx, L.start_tab), ws_ptr<int32_t>(ctx, L.ncap_tab));
+        const int jobs_per_block = (256 / kWave) * kStartsJobs;
+        hipLaunchKernelGGL(k_fit_starts, dim3((J + jobs_per_block - 1) / jobs_per_block), b256, 0, st, J, int(kPlanChunks),
+                           plan, ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.chunk_begin),
+                           ws_ptr<int32_t>(ctx, L.chunk_class), gw, gcap, ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp),
+                           ws_ptr<int32_t>(ctx, L.n_atoms), ws_ptr<int32_t>(ctx, L.start_tab),
+                           ws_ptr<int32_t>(ctx, L.ncap_tab));
         SJA_HIP(hipGetLastError(), "k_fit_starts launch");
     }
     return SJA_OK;
@@ -719,14 +731,26 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
                 ctx->timed = true;
             }
             if (interest_bits) {
-                int4 *table = ws_ptr<int4>(ctx, L.bits_table);
+                uint32_t *table = ws_ptr<uint32_t>(ctx, L.bits_table);
+                int32_t *class_dmax = ws_ptr<int32_t>(ctx, L.class_dmax);
                 hipLaunchKernelGGL(k_bits_table, dim3((words + 255) / 256, kMaxClasses), b256, 0, st, J, words, plan,
-                                   ws_ptr<int32_t>(ctx, L.class_begin), gcap, ws_ptr<int2>(ctx, L.first_dp), table);
+                                   ws_ptr<int32_t>(ctx, L.class_begin), gcap, ws_ptr<int2>(ctx, L.first_dp), table, class_dmax);
                 SJA_HIP(hipGetLastError(), "k_bits_table launch");
-                const dim3 bits_grid((words + 255) / 256, (n_gaps + kBitsRows - 1) / kBitsRows);
-                hipLaunchKernelGGL(k_fit_bits, bits_grid, b256, 0, st, J, n_gaps, words, plan,
-                                   ws_ptr<int2>(ctx, L.first_dp), table, ws_ptr<int32_t>(ctx, L.gap_rank),
-                                   ws_ptr<int32_t>(ctx, L.gap_cls), gw, gcap, interest_bits);
+                BitsArgs bits{};
+                bits.bits = interest_bits;
+                bits.first_dp = ws_ptr<int2>(ctx, L.first_dp);
+                bits.table = table;
+                bits.class_dmax = class_dmax;
+                bits.gap_order = ws_ptr<int32_t>(ctx, L.gap_order);
+                bits.gap_cls = ws_ptr<int32_t>(ctx, L.gap_cls);
+                bits.n_gaps = n_gaps;
+                bits.words = words;
+                const int64_t col_tiles = (words + 256 * kBitsWords - 1) / (256 * kBitsWords);
+                const int64_t row_tiles = (n_gaps + kBitsRows - 1) / kBitsRows;
+                hipLaunchKernelGGL(k_fit_bits, dim3(unsigned(col_tiles * row_tiles)), b256, 0, st, bits, J, plan, gw, gcap);
+                SJA_HIP(hipGetLastError(), "k_fit_bits launch");
+                hipLaunchKernelGGL(k_fit_bits_low, dim3((words + 255) / 256, kMaxClasses), b256, 0, st, bits, J, plan,
+                                   ws_ptr<int32_t>(ctx, L.class_begin), gw);
                 SJA_HIP(hipGetLastError(), "k_fit_bits launch");
             }
         }

@@ -21,6 +21,7 @@ constexpr int kFitPeriod = 64;        // steps between window top-ups (multiple 
 constexpr int kMaxClasses = 64;       // distinct capacities served by the table-driven path
 constexpr int kSelBlock = 256;        // threads per select block, one job per thread
 constexpr int kSelGapChunk = 64;      // sorted gap positions walked by one select block
+constexpr int kGapTile = 4096;        // gaps sorted together in LDS when the gaps are ordered
 constexpr int kListSplits = 40;       // most pieces one capacity class's small windows are split into
 
 // One partial arg-max per (job tile, gap): 32 bytes.
@@ -33,7 +34,7 @@ struct SelPartial {
 };
 
 // Gap plan header written by k_gap_plan (device memory, int32 each).
-enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanSubBlocks = 3, kPlanListBlocks = 4, kPlanWords = 8 };
+enum { kPlanClasses = 0, kPlanChunks = 1, kPlanTabled = 2, kPlanSubBlocks = 3, kPlanListBlocks = 4, kPlanMarks = 5, kPlanWords = 8 };
 
 // Byte offsets of the private tables inside the caller's workspace.
 struct Layout {
@@ -42,15 +43,19 @@ struct Layout {
     size_t first_dp;                       // [J] int2: a job's first atom (duration, peak), INT32_MAX twice if none
     size_t atom_area, pre_area;            // area score only: int64 area under the envelope per atom / per segment
     size_t gap_rank, gap_order;            // [G] int32
+    size_t gap_tile_key, gap_tile_idx;     // [ceil(G / kGapTile) * kGapTile] uint64 / int32: gaps sorted tile by tile
     size_t gap_w, gap_c, gap_run_end;      // [G+16] int32, in sorted order
     size_t gap_cls;                        // [G+16] int32: capacity class of a sorted position
-    size_t bits_table;                     // [kMaxClasses * ceil(J/32)] int4: per class and job word (fitting jobs, min, max first duration)
+    size_t bits_table;                     // [kMaxClasses * ceil(J/32)] uint32: per class and job word, the jobs whose first atom fits the capacity
     size_t gap_row;                        // [G+16] int64: element offset of a gap's cut row
     size_t plan;                           // [kPlanWords] int32 header
     size_t class_begin, class_chunk0, class_sub0;   // [kMaxClasses+1] int32
+    size_t class_marks;                    // [kMaxClasses+1] int32: first positions of the capacity runs, unordered
+    size_t class_dmax;                     // [kMaxClasses] int32: largest first-atom duration among the jobs that fit the class
     size_t chunk_begin, chunk_end, chunk_class, chunk_sub;  // [chunk_bound] int32
     size_t sub_begin, sub_end, sub_class;  // [sub_bound] int32
-    size_t start_tab;                      // [sub_bound * J] int32
+    size_t start_tab;                      // [chunk_bound * J] int32: per chunk of the stepping kernels
+    size_t sub_tab;                        // [sub_bound * J] int32: per sub-block, built by sja_resolve for its lists
     size_t ncap_tab;                       // [kMaxClasses * J] int32
     size_t sel_part;                       // [ceil(J/kSelBlock) * G] SelPartial
     size_t res_cand_job, res_cand_cut;     // [G] int32
@@ -125,16 +130,21 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.pre_area = take(size_t(S + 8) * 8);
     L.gap_rank = take(size_t(G) * 4);
     L.gap_order = take(size_t(G) * 4);
+    const size_t gap_tiles = size_t((G + kGapTile - 1) / kGapTile);
+    L.gap_tile_key = take(gap_tiles * kGapTile * 8);
+    L.gap_tile_idx = take(gap_tiles * kGapTile * 4);
     L.gap_w = take(size_t(G + 16) * 4);
     L.gap_c = take(size_t(G + 16) * 4);
     L.gap_run_end = take(size_t(G + 16) * 4);
     L.gap_cls = take(size_t(G + 16) * 4);
-    L.bits_table = take(size_t(kMaxClasses) * size_t((J + 31) / 32) * 16);
+    L.bits_table = take(size_t(kMaxClasses) * size_t((J + 31) / 32) * 4);
     L.gap_row = take(size_t(G + 16) * 8);
     L.plan = take(kPlanWords * 4);
     L.class_begin = take((kMaxClasses + 1) * 4);
     L.class_chunk0 = take((kMaxClasses + 1) * 4);
     L.class_sub0 = take((kMaxClasses + 1) * 4);
+    L.class_marks = take((kMaxClasses + 1) * 4);
+    L.class_dmax = take(kMaxClasses * 4);
     const size_t cb = size_t(fit_chunk_bound(G, J));
     const size_t ub = size_t(fit_sub_bound(G, J));
     L.chunk_begin = take(cb * 4);
@@ -144,7 +154,8 @@ inline Layout make_layout(int64_t G, int64_t J, int64_t S)
     L.sub_begin = take(ub * 4);
     L.sub_end = take(ub * 4);
     L.sub_class = take(ub * 4);
-    L.start_tab = take(ub * size_t(J) * 4);
+    L.start_tab = take(cb * size_t(J) * 4);
+    L.sub_tab = take(ub * size_t(J) * 4);
     L.ncap_tab = take(size_t(kMaxClasses) * size_t(J) * 4);
     size_t job_tiles = size_t((J + kSelBlock - 1) / kSelBlock);
     L.sel_part = take(job_tiles * size_t(G) * sizeof(SelPartial));

@@ -461,18 +461,26 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     auto second = [&](unsigned long long key, int src) -> unsigned long long {
         return MIXED ? ((key - 1ull) & ((1ull << 62) - 1ull)) / s_mult[wave][src] : 0ull;
     };
-    for (int s0 = s_begin; s0 < s_end; s0 += kSelBatch) {
+    // the cuts of one batch of steps (cut rows are read coalesced)
+    auto load_cuts = [&](int s0, int (&out)[kSelBatch]) {
         const int n_step = min(kSelBatch, s_end - s0);
-        // phase 1: every lane's key for each step of the batch (cut rows are read coalesced)
-        int cv[kSelBatch];
 #pragma unroll
         for (int t = 0; t < kSelBatch; ++t) {
-            cv[t] = -1;
+            out[t] = -1;
             if (t < n_step && usable) {
                 const int g = gap_order[s0 + t];
-                if (!gap_active || gap_active[g]) cv[t] = cut[int64_t(g) * n_jobs + j];
+                if (!gap_active || gap_active[g]) out[t] = cut[int64_t(g) * n_jobs + j];
             }
         }
+    };
+    int cv_next[kSelBatch];
+    load_cuts(s_begin, cv_next);
+    for (int s0 = s_begin; s0 < s_end; s0 += kSelBatch) {
+        const int n_step = min(kSelBatch, s_end - s0);
+        // phase 1: every lane's key for each step of the batch
+        int cv[kSelBatch];
+#pragma unroll
+        for (int t = 0; t < kSelBatch; ++t) cv[t] = cv_next[t];
         // a job's cut rarely changes from one sorted position to the next: only the changes
         // gather (duration, peak), all of a batch's gathers in flight together
         int dv[kSelBatch], pv[kSelBatch];    // AREA: the two halves of F itself, read instead of (duration, peak)
@@ -495,6 +503,8 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
             prev = c >= 0 ? c : prev;
         }
         last_cut = prev;
+        // the next batch's cuts travel together with this batch's gathers
+        if (s0 + kSelBatch < s_end) load_cuts(s0 + kSelBatch, cv_next);
 #pragma unroll
         for (int t = 0; t < kSelBatch; ++t) {
             if (fresh[t]) {
