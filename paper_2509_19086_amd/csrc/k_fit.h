@@ -659,7 +659,7 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
                 adv = a < hi && nd <= w;
             } while (__any(adv));
         }
-        (cut + row)[j] = cur;
+        __builtin_nontemporal_store(cur, cut + row + j);      // written once, read by a later kernel: keep it out of the caches
     };
 
     for (int s0 = s_begin; s0 < s_end; s0 += PERIOD) {

@@ -125,14 +125,14 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
     };
 
     auto key_from = [&](unsigned long long F) {
-        key_hi = ((tier << 62) | (F * mult)) + 1ull;
+        key_hi = ((tier << 62) | times_mult(F, mult)) + 1ull;
         key_lo = MIXED ? F : 0ull;
     };
     // key of the atom just passed: a - 1, whose window slot is still intact (a top-up writes at most
     // up to atom a + CAP - 1)
     auto key_of = [&](int d, int p) {
         if (AREA) key_from((unsigned long long)win_area[(a - 1) & (CAP - 1)][tid]);
-        else key_from((unsigned long long)d * (unsigned long long)p);
+        else key_from(rect_of(d, p));
     };
     // a key changed in the lanes of `ch` (those that can matter): move the running best
     auto challenge = [&](bool in) {
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(8, 8))) v
                 key_from((unsigned long long)da[a - 1]);
             } else {
                 const int2 v = dp[a - 1];
-                key_from((unsigned long long)v.x * (unsigned long long)v.y);
+                key_from(rect_of(v.x, v.y));
             }
         }
         hi = a;

@@ -60,6 +60,21 @@ __device__ __forceinline__ void job_policy(const PolicyDev &pol, const int32_t *
     }
 }
 
+// F = duration x peak and F x multiplier with as few of the (slow) 32-bit integer
+// multiplies as the value ranges allow: durations, peaks and multipliers are
+// non-negative and fit 32 bits, and a score stays below 2^62.
+__device__ __forceinline__ unsigned long long rect_of(int dur, int peak)
+{
+    return static_cast<unsigned long long>(uint32_t(dur)) * uint32_t(peak);
+}
+
+__device__ __forceinline__ unsigned long long times_mult(unsigned long long F, unsigned long long mult)
+{
+    const uint32_t m = uint32_t(mult);            // wait_scale + wait, or an SLA weight: below 2^32
+    return static_cast<unsigned long long>(uint32_t(F)) * m +
+           (static_cast<unsigned long long>(uint32_t(F >> 32) * m) << 32);
+}
+
 // reach[j] = atoms of job j that some capacity class can reach; reach[n_jobs] = 0.
 __global__ void k_reach(int n_jobs, const int32_t *__restrict__ plan, const int32_t *__restrict__ ncap_tab,
                         int32_t *__restrict__ reach)

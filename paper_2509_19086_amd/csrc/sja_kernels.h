@@ -16,20 +16,49 @@ __device__ __forceinline__ unsigned long long lanes_below(int lane)
     return lane == 0 ? 0ull : (~0ull >> (64 - lane));
 }
 
-// Inclusive wave scan of (sum, max, max) triples, Hillis-Steele over 64 lanes.
+// Lane i receives lane i - n of its row of 16 (n = 1, 2, 4, 8), or lane 15 of the
+// row before it (rows 1 and 3) / lane 31 (rows 2 and 3); lanes with no source
+// keep `identity`.  These run in the vector ALU's own data path (DPP), not
+// through the LDS crossbar as a shuffle does.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_from(int identity, int v)
+{
+    return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
+}
+constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+
+// Inclusive scans over the 64 lanes of a wave: four shifts inside each row of
+// 16, then the row totals handed on to the rows after them.
+__device__ __forceinline__ int wave_scan_add(int v)
+{
+    v += dpp_from<kDppRowShr1, 0xf>(0, v);
+    v += dpp_from<kDppRowShr2, 0xf>(0, v);
+    v += dpp_from<kDppRowShr4, 0xf>(0, v);
+    v += dpp_from<kDppRowShr8, 0xf>(0, v);
+    v += dpp_from<kDppRowBcast15, 0xa>(0, v);
+    v += dpp_from<kDppRowBcast31, 0xc>(0, v);
+    return v;
+}
+
+__device__ __forceinline__ int wave_scan_max_dpp(int v)
+{
+    v = max(v, dpp_from<kDppRowShr1, 0xf>(INT32_MIN, v));
+    v = max(v, dpp_from<kDppRowShr2, 0xf>(INT32_MIN, v));
+    v = max(v, dpp_from<kDppRowShr4, 0xf>(INT32_MIN, v));
+    v = max(v, dpp_from<kDppRowShr8, 0xf>(INT32_MIN, v));
+    v = max(v, dpp_from<kDppRowBcast15, 0xa>(INT32_MIN, v));
+    v = max(v, dpp_from<kDppRowBcast31, 0xc>(INT32_MIN, v));
+    return v;
+}
+
+// Inclusive wave scan of (sum, max, max) triples.
 __device__ __forceinline__ void wave_scan_add_max_max(int &s, int &m, int &l, int lane)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        int s2 = __shfl_up(s, d, kWave);
-        int m2 = __shfl_up(m, d, kWave);
-        int l2 = __shfl_up(l, d, kWave);
-        if (lane >= d) {
-            s += s2;
-            m = max(m, m2);
-            l = max(l, l2);
-        }
-    }
+    (void)lane;
+    s = wave_scan_add(s);
+    m = wave_scan_max_dpp(m);
+    l = wave_scan_max_dpp(l);
 }
 
 // --------------------------------------------------------------------------
@@ -57,11 +86,8 @@ struct JobLimits {
 
 __device__ __forceinline__ void wave_scan_max(int &q, int lane)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int q2 = __shfl_up(q, d, kWave);
-        if (lane >= d) q = max(q, q2);
-    }
+    (void)lane;
+    q = wave_scan_max_dpp(q);
 }
 
 // Inclusive wave scan of 64-bit sums.
@@ -97,17 +123,33 @@ __device__ __forceinline__ void prepare_job(
             if (room < d_hi) d_hi = room < 0 ? -1 : int(room);
         }
     }
+    // the next 64 segments are asked for before the current ones are scanned, so the scans
+    // and stores of one step cover the memory trip of the next
+    int n_dur = 0, n_mem = 0, n_pow = INT32_MIN;
+    uint8_t n_safe = 0;
+    auto fetch = [&](int k0) {
+        const int k = k0 + lane;
+        if (k < L) {
+            n_dur = dur[base + k];
+            n_mem = mem[base + k];
+            n_safe = safe[base + k];
+            if (LIMITED && lim.power) n_pow = lim.power[base + k];
+        }
+    };
+    fetch(p);
     for (int k0 = p; k0 < L; k0 += kWave) {
         const int k = k0 + lane;
         const bool valid = k < L;
         int s = 0, m = INT32_MIN, l = -1;
         bool flag = false;
+        const int c_pow = n_pow;
         if (valid) {
-            s = dur[base + k];
-            m = mem[base + k];
-            flag = (safe[base + k] != 0) || (k + 1 == L);
+            s = n_dur;
+            m = n_mem;
+            flag = (n_safe != 0) || (k + 1 == L);
             l = flag ? k + 1 : -1;
         }
+        if (k0 + kWave < L) fetch(k0 + kWave);
         long long ar = 0;
         if (pre_area) {
             ar = valid ? (long long)s * (long long)m : 0ll;
@@ -128,7 +170,7 @@ __device__ __forceinline__ void prepare_job(
         if (LIMITED) {
             bool keep = flag && s <= d_hi && (s >= lim.tau_min || k + 1 == L);
             if (lim.power) {
-                int q = valid ? lim.power[base + k] : INT32_MIN;
+                int q = valid ? c_pow : INT32_MIN;
                 wave_scan_max(q, lane);
                 q = max(q, carry_pow);
                 keep = keep && q <= lim.power_cap;
@@ -431,7 +473,6 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     __shared__ unsigned long long s_hi[WAVES][kSelGapChunk];
     __shared__ unsigned long long s_lo[WAVES][kSelGapChunk];
     __shared__ int s_job[WAVES][kSelGapChunk];
-    __shared__ int s_cut[WAVES][kSelGapChunk];
 
     const int xcd = blockIdx.x & 7;
     const int k = blockIdx.x >> 3;
@@ -509,8 +550,8 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
         for (int t = 0; t < kSelBatch; ++t) {
             if (fresh[t]) {
                 const unsigned long long F = AREA ? (((unsigned long long)uint32_t(pv[t]) << 32) | uint32_t(dv[t]))
-                                                  : (unsigned long long)dv[t] * (unsigned long long)pv[t];
-                hi = ((tier << 62) | (F * mult)) + 1ull;
+                                                  : rect_of(dv[t], pv[t]);
+                hi = ((tier << 62) | times_mult(F, mult)) + 1ull;
             }
             s_key[wave][t][lane] = cv[t] >= 0 ? hi : 0ull;
         }
@@ -540,28 +581,30 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
         }
         if (lane < n_step) {
             const int slot = s0 - s_begin + lane;
-            int wj = -1, wc = -1;
+            int wj = -1;
             unsigned long long wl = 0;
             if (bh) {
                 wj = wave_job0 + bsrc;
-                wc = cut[int64_t(gap_order[s0 + lane]) * n_jobs + wj];
                 wl = second(bh, bsrc);
             }
-            s_hi[wave][slot] = bh; s_lo[wave][slot] = wl; s_job[wave][slot] = bh ? wj : INT32_MAX; s_cut[wave][slot] = wc;
+            s_hi[wave][slot] = bh; s_lo[wave][slot] = wl; s_job[wave][slot] = bh ? wj : INT32_MAX;
         }
     }
     __syncthreads();
     for (int slot = threadIdx.x; slot < s_end - s_begin; slot += kSelBlock) {
         unsigned long long bh = s_hi[0][slot], bl = s_lo[0][slot];
-        int bj = s_job[0][slot], bc = s_cut[0][slot];
+        int bj = s_job[0][slot];
         if (bh == 0) bj = INT32_MAX;
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) {
             const unsigned long long oh = s_hi[w][slot], ol = s_lo[w][slot];
             const int oj = oh ? s_job[w][slot] : INT32_MAX;
-            if (key_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; bc = s_cut[w][slot]; }
+            if (key_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; }
         }
         const int g = gap_order[s_begin + slot];
+        // the winner's cut, fetched here for all of the block's positions at once (inside the
+        // stepping loop it would be one more memory trip per batch)
+        const int bc = bh ? cut[int64_t(g) * n_jobs + bj] : -1;
         SelPartial out;
         out.hi = bh; out.lo = bl; out.job = bh ? bj : -1; out.cut = bh ? bc : -1; out.pad = 0;
         part[int64_t(job_tile) * n_gaps + g] = out;
