@@ -201,6 +201,141 @@ __device__ __forceinline__ void prepare_job(
     }
 }
 
+// The same walk for the plain case (no admission limits, no area score), four
+// consecutive segments per lane: 256 segments per step, 16-byte loads and stores,
+// a lane-local scan of its four values plus one wave scan of the lane totals.  With
+// one segment per lane a step is a memory trip for 64 segments, and the trips,
+// not the bytes, bound the kernel.
+struct __attribute__((packed, aligned(4))) Int4U {      // a 16-byte group of ints at any 4-byte boundary
+    int v[4];
+};
+
+__device__ __forceinline__ void prepare_job_wide(
+    int j, int lane, int64_t base, int L, int p, const int32_t *__restrict__ dur,
+    const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe, int32_t *__restrict__ pre_dur,
+    int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
+    int2 *__restrict__ atom_dp, int2 *__restrict__ atom_db, int32_t *__restrict__ n_atoms,
+    int2 *__restrict__ first_dp)
+{
+    constexpr int PER = 4, STEP = PER * kWave;
+    int carry_sum = 0, carry_peak = INT32_MIN, carry_last = -1, count = 0;
+    int first_d = INT32_MAX, first_p = INT32_MAX;
+    int nd[PER], nm[PER];
+    uint32_t nf = 0;
+    auto fetch = [&](int k0) {
+        const int k = k0 + PER * lane;
+        if (k + PER <= L) {
+            const Int4U d4 = *reinterpret_cast<const Int4U *>(dur + base + k);
+            const Int4U m4 = *reinterpret_cast<const Int4U *>(mem + base + k);
+            uint32_t f4;
+            __builtin_memcpy(&f4, safe + base + k, 4);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) { nd[i] = d4.v[i]; nm[i] = m4.v[i]; }
+            nf = f4;
+        } else {
+            nf = 0;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const bool in = k + i < L;
+                nd[i] = in ? dur[base + k + i] : 0;
+                nm[i] = in ? mem[base + k + i] : INT32_MIN;
+                nf |= (in && safe[base + k + i] != 0 ? 1u : 0u) << (8 * i);
+            }
+        }
+    };
+    fetch(p);
+    for (int k0 = p; k0 < L; k0 += STEP) {
+        const int k = k0 + PER * lane;
+        int s[PER], m[PER], l[PER];
+        bool flag[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const bool valid = k + i < L;
+            flag[i] = valid && (((nf >> (8 * i)) & 0xffu) != 0 || k + i + 1 == L);
+            s[i] = valid ? nd[i] : 0;
+            m[i] = valid ? nm[i] : INT32_MIN;
+            l[i] = flag[i] ? k + i + 1 : -1;
+        }
+        if (k0 + STEP < L) fetch(k0 + STEP);
+        // lane-local inclusive scans, then the lanes before this one
+#pragma unroll
+        for (int i = 1; i < PER; ++i) {
+            s[i] += s[i - 1];
+            m[i] = max(m[i], m[i - 1]);
+            l[i] = max(l[i], l[i - 1]);
+        }
+        int ts = wave_scan_add(s[PER - 1]), tm = wave_scan_max_dpp(m[PER - 1]), tl = wave_scan_max_dpp(l[PER - 1]);
+        const int tot_s = __shfl(ts, kWave - 1, kWave), tot_m = __shfl(tm, kWave - 1, kWave), tot_l = __shfl(tl, kWave - 1, kWave);
+        // exclusive over lanes = inclusive of the lane before
+        int es = __shfl_up(ts, 1, kWave), em = __shfl_up(tm, 1, kWave), el = __shfl_up(tl, 1, kWave);
+        if (lane == 0) { es = 0; em = INT32_MIN; el = -1; }
+        es += carry_sum;
+        em = max(em, carry_peak);
+        el = max(el, carry_last);
+        int nflag = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            s[i] += es;
+            m[i] = max(m[i], em);
+            l[i] = max(l[i], el);
+            nflag += flag[i] ? 1 : 0;
+        }
+        if (k + PER <= L) {
+            Int4U o;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) o.v[i] = s[i];
+            *reinterpret_cast<Int4U *>(pre_dur + base + k) = o;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) o.v[i] = m[i];
+            *reinterpret_cast<Int4U *>(pre_peak + base + k) = o;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) o.v[i] = l[i];
+            *reinterpret_cast<Int4U *>(prev_safe + base + k) = o;
+        } else {
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                if (k + i < L) {
+                    pre_dur[base + k + i] = s[i];
+                    pre_peak[base + k + i] = m[i];
+                    prev_safe[base + k + i] = l[i];
+                }
+            }
+        }
+        // atoms: the flagged boundaries, compacted in order
+        const int incl = wave_scan_add(nflag);
+        const int total = __shfl(incl, kWave - 1, kWave);
+        int idx = count + incl - nflag;
+        if (count == 0 && total > 0) {
+            // the first atom of the job: the lowest lane with a flag, its first flagged value
+            const unsigned long long has = __ballot(nflag > 0);
+            const int src = __ffsll((long long)has) - 1;
+            int fd = 0, fp = 0;
+            bool got = false;
+#pragma unroll
+            for (int i = 0; i < PER; ++i)
+                if (!got && flag[i]) { fd = s[i]; fp = m[i]; got = true; }
+            first_d = __shfl(fd, src, kWave);
+            first_p = __shfl(fp, src, kWave);
+        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (flag[i]) {
+                atom_dp[base + idx] = make_int2(s[i], m[i]);
+                atom_db[base + idx] = make_int2(s[i], k + i + 1);
+                ++idx;
+            }
+        }
+        count += total;
+        carry_sum += tot_s;
+        carry_peak = max(carry_peak, tot_m);
+        carry_last = max(carry_last, tot_l);
+    }
+    if (lane == 0) {
+        n_atoms[j] = count;
+        first_dp[j] = make_int2(first_d, first_p);
+    }
+}
+
 template <bool LIMITED>
 __global__ __launch_bounds__(256) void k_prepare(
     JobLimits lim, long long *__restrict__ pre_area, long long *__restrict__ atom_area, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
@@ -217,8 +352,11 @@ __global__ __launch_bounds__(256) void k_prepare(
     const int L = int(seg_off[j + 1] - base);
     int p = progress[j];
     p = p < 0 ? 0 : (p > L ? L : p);
-    prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db,
-                         n_atoms, first_dp);
+    if (!LIMITED && !pre_area)
+        prepare_job_wide(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db, n_atoms, first_dp);
+    else
+        prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp,
+                             atom_db, n_atoms, first_dp);
 }
 
 // --------------------------------------------------------------------------
@@ -350,8 +488,12 @@ __global__ __launch_bounds__(256) void k_advance_jobs(
         // every lane evaluates the same scalars, so the branch is uniform over the wave
         if (grant_holds(job_gap[j], j, n_gaps, n_jobs, seg_off, grant_job, grant_cut, job_gap, progress, cut)) {
             p = cut;
-            prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp,
-                                 atom_db, n_atoms, first_dp);
+            if (!LIMITED && !pre_area)
+                prepare_job_wide(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db, n_atoms,
+                                 first_dp);
+            else
+                prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe,
+                                     atom_dp, atom_db, n_atoms, first_dp);
             if (lane == 0) {
                 progress[j] = p;
                 if (wait) wait[j] = 0;
