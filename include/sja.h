@@ -266,7 +266,10 @@ int sja_select(sja_ctx *ctx, void *stream, const sja_params *params, const int32
  * sja_fit on the same inputs.  No cut matrix and no interest rows exist
  * afterwards: sja_select needs a sja_fit of its own, sja_resolve works (its
  * candidate lists need no matrix) unless it is switched to, or has to fall back
- * to, the matrix-scanning rounds (then SJA_ERR_STATE).  Only enqueues work.
+ * to, the matrix-scanning rounds: that is the case when the batch has more than
+ * 64 distinct capacities (the candidate lists are built per capacity class and
+ * serve at most 64 of them).  sja_resolve then returns SJA_ERR_STATE before it
+ * writes any output; call sja_fit and sja_resolve instead.  Only enqueues work.
  * With sja_enable_timing the events bracket this call's stepping kernel.
  */
 int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,

@@ -876,6 +876,17 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
     unsigned long long *claim = ws_ptr<unsigned long long>(ctx, L.res_claim);
     int32_t *counters = ws_ptr<int32_t>(ctx, L.res_counters);
 
+    if (!ctx->fitted && G > 0 && J > 0) {
+        // after sja_fit_select there is no cut matrix: only the candidate lists can run the rounds, and
+        // they need the table-driven plan.  Found out before any output is touched.
+        int32_t tabled = 0;
+        SJA_HIP(hipMemcpyAsync(&tabled, ws_ptr<int32_t>(ctx, L.plan) + kPlanTabled, sizeof(tabled), hipMemcpyDeviceToHost, st),
+                "plan readback");
+        SJA_HIP(hipStreamSynchronize(st), "plan synchronise");
+        if (!tabled)
+            return fail(ctx, SJA_ERR_STATE, "more than 64 distinct capacities: the rounds need the cut matrix of sja_fit "
+                                            "(outputs left untouched)");
+    }
     const int n_init = G > J ? G : J;
     if (n_init > 0) {
         hipLaunchKernelGGL(k_resolve_init, dim3((n_init + 255) / 256), dim3(256), 0, st, G, J, grant_job,

@@ -697,6 +697,10 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
             }
             s_key[wave][t][lane] = cv[t] >= 0 ? hi : 0ull;
         }
+        // the keys just written are read by other lanes of this wave: order the two
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         // phase 2: lane l reduces step (l % 16) over lanes [16 * (l / 16), +16), then the four
         // quarter results of a step are combined across lanes l, l+16, l+32, l+48
         const int t = lane & (kSelBatch - 1), q = lane / kSelBatch;

@@ -317,3 +317,32 @@ def test_more_jobs_than_the_held_bitmap_holds(engine, oracle):
     walk by claim words from the first round on: same grants."""
     wl = make_workload("tiny", 5, n_gaps=96, n_jobs=140000)
     full_tick_check(engine, oracle, wl, policies=[wl.policy, 3], resolve_modes=(0,))
+
+
+def test_fused_resolve_with_too_many_capacities_leaves_outputs_alone(engine):
+    """After sja_fit_select a batch with more than 64 distinct capacities cannot be resolved
+    (the rounds would need the cut matrix): SJA_ERR_STATE, and nothing written before it."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("medium", 13, n_gaps=300, n_jobs=200)
+    wl.C = np.ascontiguousarray((9000 + 7 * np.arange(wl.n_gaps)).astype(np.int32))     # 300 distinct capacities
+    t = P.DeviceTick(engine, wl, want_cut=False)
+    par = P.Params.make(0)
+    t.prepare(); t.fit_select(par)
+    outs = (t.grant_job, t.grant_cut, t.grant_score, t.job_gap, t.rounds)
+    for o in outs:
+        o.fill_(-5)
+    with pytest.raises(P.SjaError) as e:
+        t.resolve(par)
+    assert e.value.status == -4
+    torch.cuda.synchronize()
+    for o in outs:
+        assert bool((o == -5).all())
+
+
+def test_largest_gap_count(engine, oracle):
+    """The advertised maximum of 2^20 gaps with a handful of jobs (two capacity classes, ragged
+    job count): every output of the tick against the oracle, both kinds of rounds."""
+    wl = make_workload("small", 21, n_gaps=1 << 20, n_jobs=37)
+    wl.C = np.ascontiguousarray(np.where(np.arange(wl.n_gaps) % 3 == 0, 20480, 40960).astype(np.int32))
+    full_tick_check(engine, oracle, wl, policies=[wl.policy])
