@@ -183,3 +183,40 @@ def cover_one(peak: int, cap_set: Sequence[int]):
     """Smallest capacity of the set that covers the peak (Sec. 3.9), or None."""
     fits = [int(c) for c in cap_set if int(c) >= peak]
     return min(fits) if fits else None
+
+
+def fit_one_hysteresis(dur, mem, safe, p, W, C, cap_set, min_gain, tau_min=0, tau_max=None, power=None,
+                       power_cap=None, deadline=None, now=0) -> int:
+    """The hysteresis rule of Sec. 3.9 (safeguard ii) as a set definition: among the boundaries the
+    pair admits, the longest one b* stands unless a shorter one maps to a covering capacity at least
+    min_gain below that of b*; then the longest such shorter boundary is the cut."""
+    L = len(dur)
+    admitted = []
+    for b in range(p + 1, L + 1):
+        if not ((b == L) or bool(safe[b - 1])):
+            continue
+        total = sum(dur[p:b])
+        ok = total <= W and max(mem[p:b]) <= C
+        if tau_max is not None:
+            ok = ok and total <= tau_max
+        if b != L:
+            ok = ok and total >= tau_min
+        if power is not None:
+            ok = ok and max(power[p:b]) <= power_cap
+        if deadline is not None:
+            ok = ok and now + total <= deadline
+        if ok:
+            admitted.append(b)
+    if not admitted:
+        return -1
+    b_star = max(admitted)
+    if not len(cap_set):
+        return b_star
+    inf = float("inf")
+    cov = {}
+    for b in admitted:
+        c = cover_one(max(mem[p:b]), cap_set)
+        cov[b] = inf if c is None else c
+    worth = [b for b in admitted if b < b_star and cov[b] != inf
+             and (cov[b_star] == inf or cov[b_star] - cov[b] >= min_gain)]
+    return max(worth) if worth else b_star

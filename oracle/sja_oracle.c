@@ -260,6 +260,128 @@ int sjo_fit_pairs(int64_t n_pairs, const int32_t *gap_idx, const int32_t *job_id
 }
 
 /* ------------------------------------------------------------------------
+ * Hysteresis on subdivision (Sec. 3.9, safeguard ii): a job prefers its longest
+ * fitting fragment and accepts a shorter one only for a minimum gain in slack.
+ * The paper names the rule and gives no formula; the reading taken here:
+ *   - cover(x) = the smallest capacity of the set (ascending) that is >= x,
+ *     +infinity if there is none (the mapping of the same section);
+ *   - b* = the cut of the fit without hysteresis (limits included), the longest
+ *     fragment the pair admits; a pair without one stays a decline;
+ *   - a boundary b with p < b < b* that may be offered (safe, and not shorter
+ *     than tau_min under limits; every upper bound holds for it because it
+ *     holds for b* and the running sums and peaks never decrease) is "worth
+ *     the subdivision" if cover(P(b)) is finite and lies at least min_gain below
+ *     cover(P(b*)) (any finite cover counts when cover(P(b*)) is infinite);
+ *   - the cut is the longest boundary worth the subdivision, b* if none is.
+ * min_gain >= 1; an empty set (n_caps = 0) switches the rule off.
+ * ---------------------------------------------------------------------- */
+#define SJO_NO_COVER INT64_MAX
+
+static int64_t cover_of(int64_t x, int32_t n_caps, const int32_t *cap_set)
+{
+    for (int32_t i = 0; i < n_caps; ++i)
+        if (cap_set[i] >= x) return cap_set[i];
+    return SJO_NO_COVER;
+}
+
+static int32_t fit_pair_hysteresis(int64_t L, int64_t p, const int32_t *dur, const int32_t *mem,
+                                   const uint8_t *safe, int64_t W, int64_t C, const sjo_limits *lim,
+                                   const int32_t *power, const int32_t *deadline_j, int32_t n_caps,
+                                   const int32_t *cap_set, int64_t min_gain,
+                                   int64_t *out_dur, int64_t *out_peak)
+{
+    int64_t d_star = 0, p_star = 0;
+    int32_t b_star = fit_pair(L, p, dur, mem, safe, W, C, lim, power, deadline_j, &d_star, &p_star);
+    int32_t cut = b_star;
+    int64_t cut_dur = d_star, cut_peak = p_star;
+    if (b_star >= 0 && n_caps > 0) {
+        int64_t cov_star = cover_of(p_star, n_caps, cap_set);
+        int64_t sum = 0, peak = 0;
+        for (int64_t b = p + 1; b < b_star; ++b) {
+            int64_t k = b - 1;
+            sum += dur[k];
+            if (b == p + 1 || mem[k] > peak) peak = mem[k];
+            if (!safe[k]) continue;
+            if (lim && sum < lim->tau_min) continue;
+            int64_t cov = cover_of(peak, n_caps, cap_set);
+            if (cov == SJO_NO_COVER) continue;
+            if (cov_star != SJO_NO_COVER && cov_star - cov < min_gain) continue;
+            cut = (int32_t)b;
+            cut_dur = sum;
+            cut_peak = peak;
+        }
+    }
+    if (out_dur) *out_dur = cut_dur;
+    if (out_peak) *out_peak = cut_peak;
+    return cut;
+}
+
+static int hysteresis_args_ok(int32_t n_caps, const int32_t *cap_set, int32_t min_gain)
+{
+    if (n_caps < 0 || (n_caps > 0 && (!cap_set || min_gain < 1))) return 0;
+    for (int32_t i = 1; i < n_caps; ++i)
+        if (cap_set[i] < cap_set[i - 1]) return 0;
+    return 1;
+}
+
+/* The cut matrix and interest bits of sjo_fit_limited under the hysteresis rule
+ * (lim, power, deadline may be NULL as there). */
+int sjo_fit_hysteresis(int32_t n_gaps, int32_t n_jobs, const int64_t *seg_off, const int32_t *dur,
+                       const int32_t *mem, const uint8_t *safe, const int32_t *progress,
+                       const int32_t *W, const int32_t *C, const sjo_limits *lim, const int32_t *power,
+                       const int32_t *deadline, int32_t n_caps, const int32_t *cap_set, int32_t min_gain,
+                       int32_t *cut, uint32_t *interest_bits)
+{
+    if (n_gaps < 0 || n_jobs < 0) return SJO_ERR_ARG;
+    if (lim && (lim->tau_min < 0 || lim->tau_max < 0)) return SJO_ERR_ARG;
+    if (!hysteresis_args_ok(n_caps, cap_set, min_gain)) return SJO_ERR_ARG;
+    int64_t words = ((int64_t)n_jobs + 31) / 32;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t g = 0; g < n_gaps; ++g) {
+        int32_t *row = cut + (int64_t)g * n_jobs;
+        uint32_t *bits = interest_bits ? interest_bits + (int64_t)g * words : NULL;
+        if (bits) memset(bits, 0, (size_t)words * sizeof(uint32_t));
+        for (int32_t j = 0; j < n_jobs; ++j) {
+            int64_t base = seg_off[j];
+            int64_t L = seg_off[j + 1] - base;
+            int32_t c = fit_pair_hysteresis(L, progress[j], dur + base, mem + base, safe + base,
+                                            W[g], C[g], lim, power ? power + base : NULL,
+                                            deadline ? deadline + j : NULL, n_caps, cap_set, min_gain,
+                                            NULL, NULL);
+            row[j] = c;
+            if (bits && c >= 0) bits[j >> 5] |= (uint32_t)1 << (j & 31);
+        }
+    }
+    return SJO_OK;
+}
+
+/* The same on sampled pairs, with the chosen subjob's duration and peak. */
+int sjo_fit_pairs_hysteresis(int64_t n_pairs, const int32_t *gap_idx, const int32_t *job_idx,
+                             const int64_t *seg_off, const int32_t *dur, const int32_t *mem,
+                             const uint8_t *safe, const int32_t *progress, const int32_t *W,
+                             const int32_t *C, const sjo_limits *lim, const int32_t *power,
+                             const int32_t *deadline, int32_t n_caps, const int32_t *cap_set,
+                             int32_t min_gain, int32_t *cut, int64_t *sub_dur, int64_t *sub_peak)
+{
+    if (n_pairs < 0) return SJO_ERR_ARG;
+    if (lim && (lim->tau_min < 0 || lim->tau_max < 0)) return SJO_ERR_ARG;
+    if (!hysteresis_args_ok(n_caps, cap_set, min_gain)) return SJO_ERR_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_pairs; ++i) {
+        int32_t g = gap_idx[i], j = job_idx[i];
+        int64_t base = seg_off[j];
+        int64_t L = seg_off[j + 1] - base;
+        int64_t d = 0, pk = 0;
+        cut[i] = fit_pair_hysteresis(L, progress[j], dur + base, mem + base, safe + base, W[g], C[g],
+                                     lim, power ? power + base : NULL, deadline ? deadline + j : NULL,
+                                     n_caps, cap_set, min_gain, &d, &pk);
+        if (sub_dur) sub_dur[i] = d;
+        if (sub_peak) sub_peak[i] = pk;
+    }
+    return SJO_OK;
+}
+
+/* ------------------------------------------------------------------------
  * Slack-minimising capacity mapping (Sec. 3.9): for each granted gap, the
  * smallest capacity of the set (ascending, n_caps entries) that covers the
  * granted subjob's memory peak, and the slack left against the gap's own

@@ -149,6 +149,46 @@ def fit_pairs_limited(gap_idx, job_idx, seg_off, dur, mem, safe, progress, W, C,
     return cut, sd, sp
 
 
+def fit_hysteresis(seg_off, dur, mem, safe, progress, W, C, cap_set, min_gain, limits=None, power=None,
+                   deadline=None, want_bits: bool = False):
+    """fit_limited() under the hysteresis rule of Sec. 3.9 (cap_set ascending, min_gain >= 1):
+    returns (cut [G, J] int32, bits or None)."""
+    G, J = len(W), len(seg_off) - 1
+    cap_set = np.ascontiguousarray(cap_set, dtype=np.int32)
+    cut = np.empty((G, J), dtype=np.int32)
+    bits = np.zeros((G, (J + 31) // 32), dtype=np.uint32) if want_bits else None
+    rc = _load().sjo_fit_hysteresis(ctypes.c_int32(G), ctypes.c_int32(J), _p(seg_off, np.int64),
+                                    _p(dur, np.int32), _p(mem, np.int32), _p(safe, np.uint8),
+                                    _p(progress, np.int32), _p(W, np.int32), _p(C, np.int32),
+                                    ctypes.byref(limits) if limits is not None else None,
+                                    _p(power, np.int32), _p(deadline, np.int32),
+                                    ctypes.c_int32(len(cap_set)), _p(cap_set, np.int32),
+                                    ctypes.c_int32(min_gain), _p(cut, np.int32), _p(bits, np.uint32))
+    _check(rc, "sjo_fit_hysteresis")
+    return cut, bits
+
+
+def fit_pairs_hysteresis(gap_idx, job_idx, seg_off, dur, mem, safe, progress, W, C, cap_set, min_gain,
+                         limits=None, power=None, deadline=None):
+    """fit_hysteresis() on sampled pairs; returns (cut int32, sub_dur int64, sub_peak int64)."""
+    n = len(gap_idx)
+    cap_set = np.ascontiguousarray(cap_set, dtype=np.int32)
+    cut = np.empty(n, dtype=np.int32)
+    sd = np.empty(n, dtype=np.int64)
+    sp = np.empty(n, dtype=np.int64)
+    rc = _load().sjo_fit_pairs_hysteresis(ctypes.c_int64(n), _p(gap_idx, np.int32), _p(job_idx, np.int32),
+                                          _p(seg_off, np.int64), _p(dur, np.int32), _p(mem, np.int32),
+                                          _p(safe, np.uint8), _p(progress, np.int32), _p(W, np.int32),
+                                          _p(C, np.int32),
+                                          ctypes.byref(limits) if limits is not None else None,
+                                          _p(power, np.int32), _p(deadline, np.int32),
+                                          ctypes.c_int32(len(cap_set)), _p(cap_set, np.int32),
+                                          ctypes.c_int32(min_gain), _p(cut, np.int32), _p(sd, np.int64),
+                                          _p(sp, np.int64))
+    _check(rc, "sjo_fit_pairs_hysteresis")
+    return cut, sd, sp
+
+
 def cover(seg_off, pre_peak, C, grant_job, grant_cut, cap_set):
     """Smallest capacity of cap_set (ascending) covering each grant's peak, and the slack
     against the gap's own capacity: (cover int32 [G], slack int32 [G])."""
