@@ -8,6 +8,9 @@
  *   sja_set_limits        optional admission limits applied by the next prepare:
  *                         power trace under a cap, per-job deadline (Sec. 4.4),
  *                         minimum / maximum subjob duration (Sec. 4.3)
+ *   sja_set_hysteresis    optional rule on subdivision applied by the next
+ *                         prepare: a shorter fragment only for a minimum gain in
+ *                         slack (Sec. 3.9)
  *   sja_prepare_profiles  per-job running duration / running peak / last safe
  *                         boundary from the job's progress point (the on-demand
  *                         evaluation of the envelope U(t), Sec. 3.9)
@@ -182,6 +185,33 @@ typedef struct {
  */
 int sja_set_limits(sja_ctx *ctx, const sja_limits *limits, const int32_t *power,
                    const int32_t *deadline);
+
+/*
+ * Hysteresis on subdivision (Sec. 3.9, safeguard ii: a minimum gain in slack is
+ * required before a further subdivision is accepted; otherwise the longer, more
+ * stable fragment is preferred).  The paper names the rule without a formula;
+ * the reading built here, with cover(x) = the smallest capacity of cap_set that
+ * is >= x (Sec. 3.9's slack-minimising mapping), +infinity if there is none:
+ *   for a pair (gap, job) let b* be the cut without the rule (limits included).
+ *   A boundary b, progress < b < b*, that may be offered (a safe boundary, not
+ *   shorter than tau_min under limits) is worth the subdivision if cover(P(b)) is
+ *   finite and cover(P(b*)) - cover(P(b)) >= min_gain (any finite cover counts
+ *   when cover(P(b*)) is infinite).  cut[g][j] is the longest boundary worth the
+ *   subdivision, and b* if none is.  A decline stays a decline, so the interest
+ *   bits do not change.
+ * Every call that reports or scores a subjob (sja_fit, sja_select,
+ * sja_fit_select, sja_resolve, sja_cover on their grants, sja_advance) then
+ * works with the cut the rule chose.
+ *   n_caps in [0, SJA_MAX_CAPS]; 0 switches the rule off (the state of a new
+ *   context) and ignores the other arguments.
+ *   cap_set [n_caps] int32, HOST pointer, ascending; copied.
+ *   min_gain >= 1, in the units of the capacities.
+ * Takes effect at the next sja_prepare_profiles and is kept by the sja_advance
+ * calls on top of it.  SJA_ERR_SIZE for n_caps out of range, min_gain < 1 or a
+ * set that does not ascend; SJA_ERR_NULL for a missing set.  Touches no device.
+ */
+#define SJA_MAX_CAPS 32
+int sja_set_hysteresis(sja_ctx *ctx, int32_t n_caps, const int32_t *cap_set, int32_t min_gain);
 
 /*
  * Per-job segmented scans from the progress point (Sec. 3.9: segmentation is

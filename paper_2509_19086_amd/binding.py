@@ -93,6 +93,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_set_score.restype = ctypes.c_int
     lib.sja_set_limits.argtypes = [vp, ctypes.POINTER(Limits), vp, vp]
     lib.sja_set_limits.restype = ctypes.c_int
+    lib.sja_set_hysteresis.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_int32), i32]
+    lib.sja_set_hysteresis.restype = ctypes.c_int
     lib.sja_cover.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp, vp]
     lib.sja_cover.restype = ctypes.c_int
     lib.sja_validate.argtypes = [vp, vp, i32, i64, vp, vp, vp, vp, ctypes.POINTER(Params), vp, vp, vp]
@@ -259,6 +261,12 @@ class Engine:
         rc = self.lib.sja_set_limits(self.h, ctypes.byref(limits) if limits is not None else None,
                                      _ptr(power, torch.int32), _ptr(deadline, torch.int32))
         self._check(rc, self.h)
+
+    def sja_set_hysteresis(self, cap_set, min_gain: int = 1) -> None:
+        """cap_set: a host sequence of ascending capacities (empty or None switches the rule off)."""
+        caps = [int(c) for c in (cap_set if cap_set is not None else [])]
+        arr = (ctypes.c_int32 * max(len(caps), 1))(*caps)
+        self._check(self.lib.sja_set_hysteresis(self.h, len(caps), arr, int(min_gain)), self.h)
 
     def sja_cover(self, C, grant_job, grant_cut, cap_set, cover, slack):
         G, K = C.numel(), cap_set.numel()

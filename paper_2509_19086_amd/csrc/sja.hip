@@ -76,10 +76,13 @@ int fail_hip(sja_ctx *ctx, hipError_t e, const char *what)
 template <typename T>
 T *ws_ptr(sja_ctx *ctx, size_t off) { return reinterpret_cast<T *>(ctx->ws + off); }
 
-// The area tables exist (and are read) only while the area score is in force.
+// The per-atom table of F is read while the area score or the hysteresis rule is in force
+// (without either an atom's F is its own duration x peak); the per-segment area table only
+// with the area score.
 const long long *atom_area_of(const sja_ctx *ctx, const Layout &L)
 {
-    return ctx->score_used == SJA_SCORE_AREA ? reinterpret_cast<const long long *>(ctx->ws + L.atom_area) : nullptr;
+    return (ctx->score_used == SJA_SCORE_AREA || ctx->hyst_used_n_caps > 0)
+               ? reinterpret_cast<const long long *>(ctx->ws + L.atom_area) : nullptr;
 }
 const long long *pre_area_of(const sja_ctx *ctx, const Layout &L)
 {
@@ -443,6 +446,15 @@ JobLimits job_limits(const sja_limits &l, const int32_t *power, const int32_t *d
     return out;
 }
 
+Hysteresis hysteresis_of(int32_t n_caps, int32_t min_gain, const int32_t *cap)
+{
+    Hysteresis h{};
+    h.n_caps = n_caps;
+    h.min_gain = min_gain;
+    for (int i = 0; i < n_caps; ++i) h.cap[i] = cap[i];
+    return h;
+}
+
 // sja_prepare_profiles and its variant on the built-in scratch: the same checks and the same
 // kernel; only where the private tables live differs.
 int prepare_into(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
@@ -480,16 +492,17 @@ int prepare_into(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
         const int jobs_per_block = 256 / kWave;
         const dim3 grid((n_jobs + jobs_per_block - 1) / jobs_per_block), block(256);
         const bool by_area = ctx->score_mode == SJA_SCORE_AREA;
+        const Hysteresis hyst = hysteresis_of(ctx->hyst_n_caps, ctx->hyst_min_gain, ctx->hyst_cap);
         long long *pre_area = by_area ? ws_ptr<long long>(ctx, L.pre_area) : nullptr;
-        long long *atom_area = by_area ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
+        long long *atom_area = by_area || hyst.n_caps > 0 ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
         if (ctx->limits_on) {
             const JobLimits lim = job_limits(ctx->limits, ctx->lim_power, ctx->lim_deadline);
-            hipLaunchKernelGGL(k_prepare<true>, grid, block, 0, st, lim, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe, progress,
+            hipLaunchKernelGGL(k_prepare<true>, grid, block, 0, st, lim, hyst, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe, progress,
                                pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
                                ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int2>(ctx, L.first_dp));
         } else {
-            hipLaunchKernelGGL(k_prepare<false>, grid, block, 0, st, JobLimits{}, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe,
+            hipLaunchKernelGGL(k_prepare<false>, grid, block, 0, st, JobLimits{}, hyst, pre_area, atom_area, n_jobs, seg_off, dur, mem, safe,
                                progress, pre_dur, pre_peak, prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
                                ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int2>(ctx, L.first_dp));
@@ -498,6 +511,9 @@ int prepare_into(sja_ctx *ctx, void *stream, int32_t n_jobs, int64_t n_segments,
     }
     ctx->limits_used = ctx->limits_on;
     ctx->score_used = ctx->score_mode;
+    ctx->hyst_used_n_caps = ctx->hyst_n_caps;
+    ctx->hyst_used_min_gain = ctx->hyst_min_gain;
+    memcpy(ctx->hyst_used_cap, ctx->hyst_cap, sizeof(ctx->hyst_cap));
     ctx->limits_applied = ctx->limits;
     ctx->used_power = ctx->lim_power;
     ctx->used_deadline = ctx->lim_deadline;
@@ -657,6 +673,24 @@ int sja_set_limits(sja_ctx *ctx, const sja_limits *limits, const int32_t *power,
     ctx->lim_power = power;
     ctx->lim_deadline = deadline;
     ctx->limits_on = true;
+    return SJA_OK;
+}
+
+int sja_set_hysteresis(sja_ctx *ctx, int32_t n_caps, const int32_t *cap_set, int32_t min_gain)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (n_caps < 0 || n_caps > SJA_MAX_CAPS) return fail(ctx, SJA_ERR_SIZE, "n_caps");
+    if (n_caps == 0) {
+        ctx->hyst_n_caps = 0;
+        return SJA_OK;
+    }
+    if (!cap_set) return fail(ctx, SJA_ERR_NULL, "cap_set");
+    if (min_gain < 1) return fail(ctx, SJA_ERR_SIZE, "min_gain must be >= 1");
+    for (int i = 1; i < n_caps; ++i)
+        if (cap_set[i] < cap_set[i - 1]) return fail(ctx, SJA_ERR_SIZE, "cap_set must ascend");
+    ctx->hyst_n_caps = n_caps;
+    ctx->hyst_min_gain = min_gain;
+    for (int i = 0; i < n_caps; ++i) ctx->hyst_cap[i] = cap_set[i];
     return SJA_OK;
 }
 
@@ -963,17 +997,18 @@ int sja_advance(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, co
         const int jobs_per_block = 256 / kWave;
         const dim3 grid((J + jobs_per_block - 1) / jobs_per_block), block(256);
         const bool by_area = ctx->score_used == SJA_SCORE_AREA;
+        const Hysteresis hyst = hysteresis_of(ctx->hyst_used_n_caps, ctx->hyst_used_min_gain, ctx->hyst_used_cap);
         long long *pre_area = by_area ? ws_ptr<long long>(ctx, L.pre_area) : nullptr;
-        long long *atom_area = by_area ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
+        long long *atom_area = by_area || hyst.n_caps > 0 ? ws_ptr<long long>(ctx, L.atom_area) : nullptr;
         if (ctx->limits_used) {
             const JobLimits lim = job_limits(ctx->limits_applied, ctx->used_power, ctx->used_deadline);
-            hipLaunchKernelGGL(k_advance_jobs<true>, grid, block, 0, st, lim, pre_area, atom_area, n_gaps, J, ctx->seg_off, ctx->dur,
+            hipLaunchKernelGGL(k_advance_jobs<true>, grid, block, 0, st, lim, hyst, pre_area, atom_area, n_gaps, J, ctx->seg_off, ctx->dur,
                                ctx->mem, ctx->safe, grant_job, grant_cut, job_gap, progress, wait, wait_step,
                                ctx->pre_dur, ctx->pre_peak, ctx->prev_safe, ws_ptr<int2>(ctx, L.atom_dp),
                                ws_ptr<int2>(ctx, L.atom_db), ws_ptr<int32_t>(ctx, L.n_atoms),
                                ws_ptr<int2>(ctx, L.first_dp), m);
         } else {
-            hipLaunchKernelGGL(k_advance_jobs<false>, grid, block, 0, st, JobLimits{}, pre_area, atom_area, n_gaps, J, ctx->seg_off,
+            hipLaunchKernelGGL(k_advance_jobs<false>, grid, block, 0, st, JobLimits{}, hyst, pre_area, atom_area, n_gaps, J, ctx->seg_off,
                                ctx->dur, ctx->mem, ctx->safe, grant_job, grant_cut, job_gap, progress, wait,
                                wait_step, ctx->pre_dur, ctx->pre_peak, ctx->prev_safe,
                                ws_ptr<int2>(ctx, L.atom_dp), ws_ptr<int2>(ctx, L.atom_db),

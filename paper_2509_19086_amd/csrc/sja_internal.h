@@ -226,6 +226,10 @@ struct sja_ctx {
     // how F is read (sja_set_score), and how the last prepare built the tables
     int score_mode, score_used;
 
+    // hysteresis rule: as set by sja_set_hysteresis, and as the last prepare applied it
+    int32_t hyst_n_caps, hyst_min_gain, hyst_cap[SJA_MAX_CAPS];
+    int32_t hyst_used_n_caps, hyst_used_min_gain, hyst_used_cap[SJA_MAX_CAPS];
+
     // optional timing of the pair-evaluation kernel
     bool timing;
     bool timed;

@@ -84,10 +84,98 @@ struct JobLimits {
     const int32_t *deadline;     // per job, or null
 };
 
+// Hysteresis on subdivision (Sec. 3.9, safeguard ii: a shorter fragment is accepted
+// only for a minimum gain in slack).  The capacity set of the same section,
+// ascending; n_caps = 0 switches the rule off.
+constexpr int kMaxCaps = 32;
+struct Hysteresis {
+    int n_caps;
+    int min_gain;
+    int cap[kMaxCaps];
+};
+
 __device__ __forceinline__ void wave_scan_max(int &q, int lane)
 {
     (void)lane;
     q = wave_scan_max_dpp(q);
+}
+
+// The rule as a remap of one job's atoms, run by the wave that has just compacted
+// them.  A gap's plain answer is its last fitting atom a; with cover(x) = the
+// smallest capacity of the set >= x, the rule prefers the longest earlier atom
+// whose peak maps to a capacity at least min_gain below cover(P(a)) (any covered
+// atom when P(a) itself has no cover).  Peaks ascend along the atoms, so that atom
+// is found by a search for the threshold capacity, and it depends on a alone: the
+// boundary each atom reports (atom_db[].y) and the F it is scored with (atom_f[])
+// are overwritten with those of its target, and every kernel downstream reads
+// them as it reads any other atom.  atom_f holds the areas under the envelope on
+// entry when f_is_area, and is filled with duration x peak otherwise.
+// Chunks go from the job's last atom down and each lane loads its target's values
+// before it stores its own, so no atom is read after it was overwritten.
+__device__ __forceinline__ void hysteresis_remap(const Hysteresis &h, int lane, int64_t base, int count,
+                                                 const int2 *__restrict__ atom_dp, int2 *atom_db,
+                                                 long long *atom_f, bool f_is_area)
+{
+    const int2 *dp = atom_dp + base;
+    for (int c0 = ((count - 1) / kWave) * kWave; c0 >= 0; c0 -= kWave) {
+        const int a = c0 + lane;
+        const bool valid = a < count;
+        int src = a;
+        if (valid) {
+            const int peak = dp[a].y;
+            bool covered = false;
+            long long room = 0;                          // cover(P(a)) - min_gain
+            for (int i = 0; i < h.n_caps; ++i)
+                if (!covered && h.cap[i] >= peak) {
+                    covered = true;
+                    room = (long long)h.cap[i] - h.min_gain;
+                }
+            bool any = false;
+            int thr = 0;                                 // the largest capacity worth moving to
+            for (int i = 0; i < h.n_caps; ++i)
+                if (!covered || h.cap[i] <= room) {
+                    any = true;
+                    thr = h.cap[i];
+                }
+            if (any) {
+                int lo = 0, hi = a;                      // atoms [0, lo) have peak <= thr
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (dp[mid].y <= thr) lo = mid + 1;
+                    else hi = mid;
+                }
+                if (lo > 0) src = lo - 1;
+            }
+        }
+        int boundary = 0;
+        long long f = 0;
+        if (valid) {
+            boundary = atom_db[base + src].y;
+            if (f_is_area) {
+                f = atom_f[base + src];
+            } else {
+                const int2 v = dp[src];
+                f = (long long)((unsigned long long)uint32_t(v.x) * uint32_t(v.y));
+            }
+        }
+        if (valid) {
+            atom_db[base + a].y = boundary;
+            atom_f[base + a] = f;
+        }
+    }
+}
+
+// After prepare_job / prepare_job_wide of the same wave: make the wave's own atom
+// stores visible to its other lanes, then apply the rule.
+__device__ __forceinline__ void hysteresis_after_prepare(const Hysteresis &h, int j, int lane, int64_t base,
+                                                         const int2 *atom_dp, int2 *atom_db,
+                                                         const int32_t *n_atoms, long long *atom_f,
+                                                         bool f_is_area)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const int count = n_atoms[j];
+    hysteresis_remap(h, lane, base, count, atom_dp, atom_db, atom_f, f_is_area);
 }
 
 // Inclusive wave scan of 64-bit sums.
@@ -338,7 +426,7 @@ __device__ __forceinline__ void prepare_job_wide(
 
 template <bool LIMITED>
 __global__ __launch_bounds__(256) void k_prepare(
-    JobLimits lim, long long *__restrict__ pre_area, long long *__restrict__ atom_area, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    JobLimits lim, Hysteresis hyst, long long *__restrict__ pre_area, long long *__restrict__ atom_area, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ progress, int32_t *__restrict__ pre_dur,
     int32_t *__restrict__ pre_peak, int32_t *__restrict__ prev_safe,
@@ -355,8 +443,10 @@ __global__ __launch_bounds__(256) void k_prepare(
     if (!LIMITED && !pre_area)
         prepare_job_wide(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db, n_atoms, first_dp);
     else
-        prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp,
+        prepare_job<LIMITED>(lim, pre_area, pre_area ? atom_area : nullptr, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp,
                              atom_db, n_atoms, first_dp);
+    if (hyst.n_caps > 0)
+        hysteresis_after_prepare(hyst, j, lane, base, atom_dp, atom_db, n_atoms, atom_area, pre_area != nullptr);
 }
 
 // --------------------------------------------------------------------------
@@ -467,7 +557,7 @@ __global__ __launch_bounds__(256) void k_cover(
 // wait_step longer.  metrics[3] counts the jobs with nothing left afterwards.
 template <bool LIMITED>
 __global__ __launch_bounds__(256) void k_advance_jobs(
-    JobLimits lim, long long *__restrict__ pre_area, long long *__restrict__ atom_area, int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
+    JobLimits lim, Hysteresis hyst, long long *__restrict__ pre_area, long long *__restrict__ atom_area, int n_gaps, int n_jobs, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ dur,
     const int32_t *__restrict__ mem, const uint8_t *__restrict__ safe,
     const int32_t *__restrict__ grant_job, const int32_t *__restrict__ grant_cut,
     const int32_t *__restrict__ job_gap, int32_t *__restrict__ progress, int32_t *__restrict__ wait,
@@ -492,8 +582,10 @@ __global__ __launch_bounds__(256) void k_advance_jobs(
                 prepare_job_wide(j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe, atom_dp, atom_db, n_atoms,
                                  first_dp);
             else
-                prepare_job<LIMITED>(lim, pre_area, atom_area, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe,
+                prepare_job<LIMITED>(lim, pre_area, pre_area ? atom_area : nullptr, j, lane, base, L, p, dur, mem, safe, pre_dur, pre_peak, prev_safe,
                                      atom_dp, atom_db, n_atoms, first_dp);
+            if (hyst.n_caps > 0)
+                hysteresis_after_prepare(hyst, j, lane, base, atom_dp, atom_db, n_atoms, atom_area, pre_area != nullptr);
             if (lane == 0) {
                 progress[j] = p;
                 if (wait) wait[j] = 0;

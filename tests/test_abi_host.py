@@ -118,6 +118,17 @@ def test_tick_end_calls_validate_on_the_host(lib):
         assert lib.sja_set_limits(h, ctypes.byref(P.Limits.make(tau_max=-1)), None, None) == -2
         assert lib.sja_set_limits(h, None, None, None) == 0
         assert lib.sja_set_limits(None, None, None, None) == -1
+        # hysteresis: host-side copy, range checks, clearing
+        caps = (ctypes.c_int32 * 3)(10, 20, 40)
+        down = (ctypes.c_int32 * 3)(10, 40, 20)
+        assert lib.sja_set_hysteresis(h, 3, caps, 10) == 0
+        assert lib.sja_set_hysteresis(h, 3, caps, 0) == -2
+        assert lib.sja_set_hysteresis(h, 3, down, 1) == -2
+        assert lib.sja_set_hysteresis(h, 33, caps, 1) == -2
+        assert lib.sja_set_hysteresis(h, -1, caps, 1) == -2
+        assert lib.sja_set_hysteresis(h, 2, None, 1) == -1
+        assert lib.sja_set_hysteresis(h, 0, None, 0) == 0
+        assert lib.sja_set_hysteresis(None, 0, None, 0) == -1
         # validate: sizes and required pointers
         assert lib.sja_validate(h, None, -1, 0, junk, None, None, junk, None, None, None, junk) == -2
         assert lib.sja_validate(h, None, 4, 8, None, junk, junk, junk, None, None, None, junk) == -1
