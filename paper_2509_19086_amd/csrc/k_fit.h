@@ -490,41 +490,56 @@ __global__ __launch_bounds__(256) void k_fit_bits(BitsArgs B, int n_jobs, const 
 }
 
 // The rows at the bottom of a class: windows below the class's largest first
-// duration.  Thread (class c, word): the first durations of the word's 32 jobs
-// are fetched once and compared with every such window in turn; a wave stores
-// 256 contiguous bytes of a row per step.
+// duration.  A block takes kLowRows sorted positions and 256 words of their rows
+// and leaves at once when none of the positions is such a row (the usual case
+// wherever windows are long against first durations).  Otherwise a thread
+// fetches the first durations of its word's 32 jobs once and compares them with
+// every such window in turn; a wave stores 256 contiguous bytes of a row per step.
+constexpr int kLowRows = 32;
+
 __global__ __launch_bounds__(256) void k_fit_bits_low(BitsArgs B, int n_jobs, const int32_t *__restrict__ plan,
-                                                      const int32_t *__restrict__ class_begin,
                                                       const int32_t *__restrict__ gap_w)
 {
-    const int c = blockIdx.y;
-    if (!plan[kPlanTabled] || c >= plan[kPlanClasses]) return;
+    __shared__ int s_w[kLowRows], s_g[kLowRows], s_c[kLowRows];
+    __shared__ unsigned s_low;
+    if (!plan[kPlanTabled]) return;
     const int words = B.words;
     const int word = blockIdx.x * blockDim.x + threadIdx.x;
-    const int dmax = B.class_dmax[c];
-    const int pos_b = class_begin[c], pos_e = class_begin[c + 1];
-    if (gap_w[pos_b] >= dmax) return;                    // no such row in this class (uniform)
+    const int s_begin = blockIdx.y * kLowRows;
+    if (threadIdx.x < kWave) {
+        const int s = s_begin + int(threadIdx.x);
+        bool low = false;
+        if (threadIdx.x < kLowRows && s < B.n_gaps) {
+            const int w = gap_w[s], c = B.gap_cls[s];
+            low = w < B.class_dmax[c];
+            s_w[threadIdx.x] = w;
+            s_c[threadIdx.x] = c;
+            s_g[threadIdx.x] = B.gap_order[s];
+        }
+        const unsigned long long m = __ballot(low);
+        if (threadIdx.x == 0) s_low = unsigned(m);
+    }
+    __syncthreads();
+    unsigned todo = s_low;                               // uniform over the block
+    if (!todo) return;
     const bool live = word < words;
-    const uint32_t fits = live ? B.table[int64_t(c) * words + word] : 0u;
     int d[32];
 #pragma unroll
     for (int b = 0; b < 32; ++b) d[b] = B.first_dp[min(word * 32 + b, n_jobs - 1)].x;
-    for (int s0 = pos_b; s0 < pos_e; s0 += 8) {
-        int wv[8], gv[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int s = min(s0 + t, pos_e - 1);
-            wv[t] = gap_w[s];
-            gv[t] = B.gap_order[s];
+    int cls = -1;
+    uint32_t fits = 0;
+    while (todo) {
+        const int r = __ffs(int(todo)) - 1;
+        todo &= todo - 1;
+        const int w = s_w[r], c = s_c[r];
+        if (c != cls) {
+            cls = c;
+            fits = live ? B.table[int64_t(c) * words + word] : 0u;
         }
+        uint32_t le = 0;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            if (s0 + t >= pos_e || wv[t] >= dmax) return;         // windows ascend inside a class (uniform)
-            uint32_t le = 0;
-#pragma unroll
-            for (int b = 0; b < 32; ++b) le |= (d[b] <= wv[t] ? 1u : 0u) << b;
-            if (live) B.bits[int64_t(gv[t]) * words + word] = le & fits;
-        }
+        for (int b = 0; b < 32; ++b) le |= (d[b] <= w ? 1u : 0u) << b;
+        if (live) B.bits[int64_t(s_g[r]) * words + word] = le & fits;
     }
 }
 

@@ -783,8 +783,8 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
                 const int64_t row_tiles = (n_gaps + kBitsRows - 1) / kBitsRows;
                 hipLaunchKernelGGL(k_fit_bits, dim3(unsigned(col_tiles * row_tiles)), b256, 0, st, bits, J, plan, gw, gcap);
                 SJA_HIP(hipGetLastError(), "k_fit_bits launch");
-                hipLaunchKernelGGL(k_fit_bits_low, dim3((words + 255) / 256, kMaxClasses), b256, 0, st, bits, J, plan,
-                                   ws_ptr<int32_t>(ctx, L.class_begin), gw);
+                hipLaunchKernelGGL(k_fit_bits_low, dim3((words + 255) / 256, (n_gaps + kLowRows - 1) / kLowRows), b256, 0, st,
+                                   bits, J, plan, gw);
                 SJA_HIP(hipGetLastError(), "k_fit_bits launch");
             }
         }
