@@ -294,12 +294,11 @@ int sja_select(sja_ctx *ctx, void *stream, const sja_params *params, const int32
  * job_held, gap_active, cand_*), with the same meaning, layout and results:
  * cand_job / cand_cut / cand_score equal what sja_select would report after
  * sja_fit on the same inputs.  No cut matrix and no interest rows exist
- * afterwards: sja_select needs a sja_fit of its own, sja_resolve works (its
- * candidate lists need no matrix) unless it is switched to, or has to fall back
- * to, the matrix-scanning rounds: that is the case when the batch has more than
- * 64 distinct capacities (the candidate lists are built per capacity class and
- * serve at most 64 of them).  sja_resolve then returns SJA_ERR_STATE before it
- * writes any output; call sja_fit and sja_resolve instead.  Only enqueues work.
+ * afterwards: sja_select needs a sja_fit of its own; sja_resolve works (its
+ * candidate lists need no matrix, and where they cannot run - more than 64
+ * distinct capacities, the lists are built per capacity class - its scanning
+ * rounds evaluate the pairs again each round instead of reading a matrix).
+ * Only enqueues work.
  * With sja_enable_timing the events bracket this call's stepping kernel.
  */
 int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
@@ -419,8 +418,10 @@ int sja_last_fit_kernel_ms(sja_ctx *ctx, float *ms_host);
  *                       launch per round (the default).  Falls back to the
  *                       other mode by itself with more than 64 distinct
  *                       capacities or when the lists would not fit the workspace.
- *   SJA_RESOLVE_MATRIX  every round re-scans the cut matrix rows of the gaps
- *                       that are still ungranted.
+ *   SJA_RESOLVE_MATRIX  every round re-scans the gaps that are still
+ *                       ungranted: the rows of the cut matrix after sja_fit,
+ *                       the pairs themselves (evaluated again, nothing stored)
+ *                       after sja_fit_select.
  * SJA_ERR_SIZE for any other value.
  */
 typedef enum {

@@ -446,6 +446,54 @@ JobLimits job_limits(const sja_limits &l, const int32_t *power, const int32_t *d
     return out;
 }
 
+// The fused fit -> select pass over the planned batch of gaps (the plan of enqueue_gap_plan is in
+// the workspace): candidates per gap among the jobs that job_held does not mark, for the gaps that
+// gap_active does not switch off.  No cut matrix is read or written.
+int launch_fused(sja_ctx *ctx, hipStream_t st, const Layout &L, int32_t n_gaps, const sja_params *params,
+                 const int32_t *wait, const uint8_t *sla_class, const int32_t *job_held, const uint8_t *gap_active,
+                 int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score, bool timed)
+{
+    const int J = ctx->n_jobs;
+    const int job_tiles = (J + kFusedBlock - 1) / kFusedBlock;
+    if (job_tiles > 0) {
+        const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
+        const int tiles8 = (job_tiles + 7) / 8 * 8;
+        const unsigned grid = unsigned(tiles8) * unsigned(chunk_bound);
+        const bool mixed = params->policy == SJA_POLICY_MIXED;
+        const long long *atom_area = atom_area_of(ctx, L);
+        auto kern = atom_area ? (mixed ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true, true>
+                                       : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false, true>)
+                              : (mixed ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true, false>
+                                       : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false, false>);
+        if (timed) {
+            if (!ctx->ev_start) {
+                SJA_HIP(hipEventCreate(&ctx->ev_start), "hipEventCreate");
+                SJA_HIP(hipEventCreate(&ctx->ev_stop), "hipEventCreate");
+            }
+            SJA_HIP(hipEventRecord(ctx->ev_start, st), "hipEventRecord");
+        }
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedBlock), 0, st, J, n_gaps, chunk_bound, to_dev(params),
+                           ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), atom_area, ws_ptr<int32_t>(ctx, L.n_atoms),
+                           ws_ptr<int32_t>(ctx, L.plan), ws_ptr<int32_t>(ctx, L.chunk_begin),
+                           ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
+                           ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.start_tab),
+                           ws_ptr<int32_t>(ctx, L.ncap_tab), ws_ptr<int32_t>(ctx, L.gap_w),
+                           ws_ptr<int32_t>(ctx, L.gap_c), ws_ptr<int32_t>(ctx, L.gap_order),
+                           ws_ptr<int32_t>(ctx, L.gap_run_end), wait, sla_class, job_held, gap_active,
+                           ws_ptr<SelPartial>(ctx, L.sel_part));
+        SJA_HIP(hipGetLastError(), "k_fit_select launch");
+        if (timed) {
+            SJA_HIP(hipEventRecord(ctx->ev_stop, st), "hipEventRecord");
+            ctx->timed = true;
+        }
+    }
+    hipLaunchKernelGGL(k_fused_reduce, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, job_tiles,
+                       ws_ptr<SelPartial>(ctx, L.sel_part), ctx->seg_off, ws_ptr<int2>(ctx, L.atom_db), cand_job,
+                       cand_cut, cand_score);
+    SJA_HIP(hipGetLastError(), "k_fused_reduce launch");
+    return SJA_OK;
+}
+
 Hysteresis hysteresis_of(int32_t n_caps, int32_t min_gain, const int32_t *cap)
 {
     Hysteresis h{};
@@ -821,43 +869,9 @@ int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W,
     if (n_gaps > 0) {
         rc = enqueue_gap_plan(ctx, st, L, n_gaps, W, C);
         if (rc != SJA_OK) return rc;
-        const int job_tiles = (J + kFusedBlock - 1) / kFusedBlock;
-        if (job_tiles > 0) {
-            const int chunk_bound = int(fit_chunk_bound(n_gaps, J));
-            const int tiles8 = (job_tiles + 7) / 8 * 8;
-            const unsigned grid = unsigned(tiles8) * unsigned(chunk_bound);
-            const bool mixed = params->policy == SJA_POLICY_MIXED;
-            const long long *atom_area = atom_area_of(ctx, L);
-            auto kern = atom_area ? (mixed ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true, true>
-                                           : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false, true>)
-                                  : (mixed ? k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, true, false>
-                                           : k_fit_select<kFusedBlock, kFusedWindow, kFusedPeriod, false, false>);
-            if (ctx->timing) {
-                if (!ctx->ev_start) {
-                    SJA_HIP(hipEventCreate(&ctx->ev_start), "hipEventCreate");
-                    SJA_HIP(hipEventCreate(&ctx->ev_stop), "hipEventCreate");
-                }
-                SJA_HIP(hipEventRecord(ctx->ev_start, st), "hipEventRecord");
-            }
-            hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedBlock), 0, st, J, n_gaps, chunk_bound, to_dev(params),
-                               ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp), atom_area, ws_ptr<int32_t>(ctx, L.n_atoms),
-                               ws_ptr<int32_t>(ctx, L.plan), ws_ptr<int32_t>(ctx, L.chunk_begin),
-                               ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int32_t>(ctx, L.chunk_class),
-                               ws_ptr<int32_t>(ctx, L.chunk_sub), ws_ptr<int32_t>(ctx, L.start_tab),
-                               ws_ptr<int32_t>(ctx, L.ncap_tab), ws_ptr<int32_t>(ctx, L.gap_w),
-                               ws_ptr<int32_t>(ctx, L.gap_c), ws_ptr<int32_t>(ctx, L.gap_order),
-                               ws_ptr<int32_t>(ctx, L.gap_run_end), wait, sla_class, job_held, gap_active,
-                               ws_ptr<SelPartial>(ctx, L.sel_part));
-            SJA_HIP(hipGetLastError(), "k_fit_select launch");
-            if (ctx->timing) {
-                SJA_HIP(hipEventRecord(ctx->ev_stop, st), "hipEventRecord");
-                ctx->timed = true;
-            }
-        }
-        hipLaunchKernelGGL(k_fused_reduce, dim3((n_gaps + 255) / 256), dim3(256), 0, st, n_gaps, job_tiles,
-                           ws_ptr<SelPartial>(ctx, L.sel_part), ctx->seg_off, ws_ptr<int2>(ctx, L.atom_db), cand_job,
-                           cand_cut, cand_score);
-        SJA_HIP(hipGetLastError(), "k_fused_reduce launch");
+        rc = launch_fused(ctx, st, L, n_gaps, params, wait, sla_class, job_held, gap_active, cand_job, cand_cut,
+                          cand_score, ctx->timing);
+        if (rc != SJA_OK) return rc;
     }
     ctx->n_gaps = n_gaps;
     ctx->cut = nullptr;
@@ -888,8 +902,6 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
 {
     if (!ctx) return SJA_ERR_NULL;
     if (!ctx->planned) return fail(ctx, SJA_ERR_STATE, "sja_resolve before sja_fit or sja_fit_select");
-    if (ctx->resolve_mode == SJA_RESOLVE_MATRIX && !ctx->fitted)
-        return fail(ctx, SJA_ERR_STATE, "matrix-scanning rounds need the cut matrix of sja_fit");
     int rc = check_params(ctx, params, wait, sla_class);
     if (rc != SJA_OK) return rc;
     const int G = ctx->n_gaps, J = ctx->n_jobs;
@@ -910,17 +922,6 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
     unsigned long long *claim = ws_ptr<unsigned long long>(ctx, L.res_claim);
     int32_t *counters = ws_ptr<int32_t>(ctx, L.res_counters);
 
-    if (!ctx->fitted && G > 0 && J > 0) {
-        // after sja_fit_select there is no cut matrix: only the candidate lists can run the rounds, and
-        // they need the table-driven plan.  Found out before any output is touched.
-        int32_t tabled = 0;
-        SJA_HIP(hipMemcpyAsync(&tabled, ws_ptr<int32_t>(ctx, L.plan) + kPlanTabled, sizeof(tabled), hipMemcpyDeviceToHost, st),
-                "plan readback");
-        SJA_HIP(hipStreamSynchronize(st), "plan synchronise");
-        if (!tabled)
-            return fail(ctx, SJA_ERR_STATE, "more than 64 distinct capacities: the rounds need the cut matrix of sja_fit "
-                                            "(outputs left untouched)");
-    }
     const int n_init = G > J ? G : J;
     if (n_init > 0) {
         hipLaunchKernelGGL(k_resolve_init, dim3((n_init + 255) / 256), dim3(256), 0, st, G, J, grant_job,
@@ -938,13 +939,17 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
                                 result, &done);
         if (rc != SJA_OK) return rc;
     }
-    if (!done && G > 0 && J > 0 && !ctx->fitted)
-        return fail(ctx, SJA_ERR_STATE, "this batch needs the matrix-scanning rounds, which need the cut matrix of sja_fit");
     for (int64_t r = 1; !done && r <= cap; ++r) {
         ++result[0];
         int32_t host_counters[2] = {0, 0};
         if (G > 0) {
-            rc = launch_select(ctx, st, params, wait, sla_class, job_gap, active, cand_job, cand_cut, cand_score);
+            // the round's selection over the still-active gaps and un-held jobs: from the cut matrix if
+            // sja_fit left one, else by evaluating the pairs again (the fused pass; nothing is stored)
+            if (ctx->fitted)
+                rc = launch_select(ctx, st, params, wait, sla_class, job_gap, active, cand_job, cand_cut, cand_score);
+            else
+                rc = launch_fused(ctx, st, L, G, params, wait, sla_class, job_gap, active, cand_job, cand_cut, cand_score,
+                                  false);
             if (rc != SJA_OK) return rc;
             const dim3 grid((G + 255) / 256), block(256);
             hipLaunchKernelGGL(k_claim, grid, block, 0, st, G, int(r), active, cand_job, claim, counters);

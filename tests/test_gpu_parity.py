@@ -268,10 +268,12 @@ def test_fused_many_capacity_classes(engine, oracle, n_classes):
     rng = np.random.default_rng(n_classes)
     caps = np.sort(rng.choice(np.arange(2000, 60000), size=n_classes, replace=False)).astype(np.int32)
     wl.C = caps[rng.integers(0, n_classes, size=wl.n_gaps)].astype(np.int32)
-    fused_check(engine, oracle, wl, policies=[3, 0], resolve=n_classes <= 64)
+    fused_check(engine, oracle, wl, policies=[3, 0], resolve=True)
 
 
-def test_fused_then_matrix_rounds_is_refused(engine):
+def test_fused_then_select_is_refused_and_scanning_rounds_work(engine, oracle):
+    """After sja_fit_select there is no matrix: sja_select is refused, while the scanning rounds
+    re-evaluate the pairs and give the oracle's grants."""
     import torch
     import paper_2509_19086_amd as P
     wl = make_workload("tiny", 0)
@@ -279,10 +281,15 @@ def test_fused_then_matrix_rounds_is_refused(engine):
     t.prepare()
     par = P.Params.make(0)
     t.fit_select(par)
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cut, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C, False)
+    want = oracle.resolve(cut, wl.seg_off, pd, pp, oracle.Params.make(0), wl.wait, wl.sla_class)
     try:
         engine.sja_set_resolve_mode(1)
-        with pytest.raises(P.SjaError):
-            t.resolve(par)
+        t.resolve(par)
+        for got, exp in zip((t.grant_job, t.grant_cut, t.grant_score, t.job_gap), want[:4]):
+            np.testing.assert_array_equal(got.cpu().numpy(), exp)
+        assert t.rounds.cpu().tolist() == [want[4], want[5]]
         with pytest.raises(P.SjaError):
             t.select(par)
     finally:
@@ -319,25 +326,35 @@ def test_more_jobs_than_the_held_bitmap_holds(engine, oracle):
     full_tick_check(engine, oracle, wl, policies=[wl.policy, 3], resolve_modes=(0,))
 
 
-def test_fused_resolve_with_too_many_capacities_leaves_outputs_alone(engine):
-    """After sja_fit_select a batch with more than 64 distinct capacities cannot be resolved
-    (the rounds would need the cut matrix): SJA_ERR_STATE, and nothing written before it."""
-    import torch
+@pytest.mark.parametrize("policy", [0, 3])
+def test_resolve_after_the_fused_call_with_too_many_capacities(engine, oracle, policy):
+    """After sja_fit_select there is no cut matrix, and with more than 64 distinct capacities the
+    candidate lists cannot run either: the rounds then re-evaluate the pairs of the still-active
+    gaps each round.  Same grants as the oracle's, in both resolve modes, also under a round cap."""
     import paper_2509_19086_amd as P
     wl = make_workload("medium", 13, n_gaps=300, n_jobs=200)
     wl.C = np.ascontiguousarray((9000 + 7 * np.arange(wl.n_gaps)).astype(np.int32))     # 300 distinct capacities
     t = P.DeviceTick(engine, wl, want_cut=False)
-    par = P.Params.make(0)
-    t.prepare(); t.fit_select(par)
-    outs = (t.grant_job, t.grant_cut, t.grant_score, t.job_gap, t.rounds)
-    for o in outs:
-        o.fill_(-5)
-    with pytest.raises(P.SjaError) as e:
-        t.resolve(par)
-    assert e.value.status == -4
-    torch.cuda.synchronize()
-    for o in outs:
-        assert bool((o == -5).all())
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cut, _ = oracle.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C, False)
+    t.prepare()
+    for cap in (0, 3):
+        par = P.Params.make(policy, wl.wait_scale, wl.sla_weight, wl.class0_override, cap)
+        opar = oracle.Params.make(policy, wl.wait_scale, wl.sla_weight, wl.class0_override, cap)
+        want = oracle.resolve(cut, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+        assert want[4] > 3 or cap == 3
+        try:
+            for mode in (0, 1):
+                engine.sja_set_resolve_mode(mode)
+                t.fit_select(par)
+                for o in (t.grant_job, t.grant_cut, t.grant_score, t.job_gap, t.rounds):
+                    o.fill_(-5)
+                t.resolve(par)
+                for got, exp in zip((t.grant_job, t.grant_cut, t.grant_score, t.job_gap), want[:4]):
+                    np.testing.assert_array_equal(got.cpu().numpy(), exp, err_msg=f"cap {cap} mode {mode}")
+                assert t.rounds.cpu().tolist() == [want[4], want[5]]
+        finally:
+            engine.sja_set_resolve_mode(0)
 
 
 def test_largest_gap_count(engine, oracle):
