@@ -412,6 +412,20 @@ int sja_enable_timing(sja_ctx *ctx, int on);
 int sja_last_fit_kernel_ms(sja_ctx *ctx, float *ms_host);
 
 /*
+ * Measurement aid, no step of the method: writes the (n_gaps x n_jobs) int32
+ * matrix `cut` (device) with the launch shape, the block-to-tile mapping and the
+ * store stream of sja_fit's pair-evaluation kernel - one 256-byte piece of a
+ * row per wave and step, along the sorted gap positions of the last sja_fit or
+ * sja_fit_select - but computes nothing: cut[g][j] = j afterwards.  Its
+ * duration is what the memory system allows for that address pattern, the
+ * ceiling the pair-evaluation kernel is measured against.  Needs the plan of
+ * the last sja_fit / sja_fit_select (SJA_ERR_STATE otherwise); if `cut` is the
+ * matrix that sja_fit wrote, that matrix is gone and sja_select / matrix rounds
+ * need a new sja_fit.  Only enqueues work.
+ */
+int sja_store_reference(sja_ctx *ctx, void *stream, int32_t *cut);
+
+/*
  * How sja_resolve runs the rounds of Sec. 3.5's grant phase.  Both modes give
  * the same grants, rounds_used and stable flag; they differ in speed only.
  *   SJA_RESOLVE_LISTS   per-gap candidate lists in preference order, one cheap

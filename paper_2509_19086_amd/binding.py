@@ -105,6 +105,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.sja_enable_timing.restype = ctypes.c_int
     lib.sja_last_fit_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.sja_last_fit_kernel_ms.restype = ctypes.c_int
+    lib.sja_store_reference.argtypes = [vp, vp, vp]
+    lib.sja_store_reference.restype = ctypes.c_int
     lib.sja_set_resolve_mode.argtypes = [vp, ctypes.c_int]
     lib.sja_set_resolve_mode.restype = ctypes.c_int
     if path is None:
@@ -172,6 +174,11 @@ class Engine:
 
     def sja_enable_timing(self, on: bool) -> None:
         self._check(self.lib.sja_enable_timing(self.h, int(on)), self.h)
+
+    def sja_store_reference(self, cut) -> None:
+        """Overwrites cut [n_gaps, n_jobs] with the pair-evaluation kernel's store stream (cut[g][j] = j)."""
+        self._check(self.lib.sja_store_reference(self.h, _stream(), _ptr(cut, torch.int32, self.n_gaps * self.n_jobs)),
+                    self.h)
 
     def sja_set_resolve_mode(self, mode: int) -> None:
         """0 = candidate lists (default), 1 = matrix-scanning rounds."""

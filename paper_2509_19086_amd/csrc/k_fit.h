@@ -701,4 +701,26 @@ __global__ __launch_bounds__(BLOCK) void k_fit_main(
     }
 }
 
+// Measurement aid, no step of the method: the store stream of k_fit_main with nothing
+// computed.  Same grid, same block -> (job tile, chunk) mapping, same walk over the
+// chunk's sorted positions, one 256-byte piece of a cut row per wave and step, the
+// same non-temporal stores; the value stored is the lane's job index.  Its duration
+// is what the memory system allows for this address pattern.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_store_reference(int n_jobs, int chunk_bound, const int32_t *__restrict__ plan,
+                                                           const int32_t *__restrict__ chunk_begin,
+                                                           const int32_t *__restrict__ chunk_end,
+                                                           const int64_t *__restrict__ gap_row, int32_t *__restrict__ cut)
+{
+    const int xcd = blockIdx.x & 7;
+    const int k = blockIdx.x >> 3;
+    const int job_tile = (k / chunk_bound) * 8 + xcd;
+    const int chunk = k % chunk_bound;
+    if (job_tile * BLOCK >= n_jobs || chunk >= plan[kPlanChunks]) return;
+    const int j_raw = job_tile * BLOCK + threadIdx.x;
+    const int j = j_raw < n_jobs ? j_raw : n_jobs - 1;
+    const int s_begin = chunk_begin[chunk], s_end = chunk_end[chunk];
+    for (int s = s_begin; s < s_end; ++s) __builtin_nontemporal_store(j, cut + gap_row[s] + j);
+}
+
 }  // namespace sja

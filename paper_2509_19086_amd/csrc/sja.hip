@@ -844,6 +844,30 @@ int sja_fit(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const 
     return SJA_OK;
 }
 
+int sja_store_reference(sja_ctx *ctx, void *stream, int32_t *cut)
+{
+    if (!ctx) return SJA_ERR_NULL;
+    if (!ctx->planned) return fail(ctx, SJA_ERR_STATE, "sja_store_reference before sja_fit or sja_fit_select");
+    const int G = ctx->n_gaps, J = ctx->n_jobs;
+    if (G > 0 && J > 0 && !cut) return fail(ctx, SJA_ERR_NULL, "cut");
+    const Layout L = make_layout(G, J, ctx->n_segments);
+    if (!ctx->ws || ctx->ws_bytes < L.total) return fail(ctx, SJA_ERR_WORKSPACE, "workspace too small");
+    DeviceGuard guard(ctx->device);
+    SJA_HIP(guard.err, "hipSetDevice");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int job_tiles = (J + kFitBlock - 1) / kFitBlock;
+    if (G > 0 && job_tiles > 0) {
+        const int chunk_bound = int(fit_chunk_bound(G, J));
+        const int tiles8 = (job_tiles + 7) / 8 * 8;
+        hipLaunchKernelGGL(k_store_reference<kFitBlock>, dim3(unsigned(tiles8) * unsigned(chunk_bound)), dim3(kFitBlock), 0, st,
+                           J, chunk_bound, ws_ptr<int32_t>(ctx, L.plan), ws_ptr<int32_t>(ctx, L.chunk_begin),
+                           ws_ptr<int32_t>(ctx, L.chunk_end), ws_ptr<int64_t>(ctx, L.gap_row), cut);
+        SJA_HIP(hipGetLastError(), "k_store_reference launch");
+    }
+    if (cut == ctx->cut) ctx->fitted = false;      // the matrix of the last sja_fit no longer holds its replies
+    return SJA_OK;
+}
+
 int sja_fit_select(sja_ctx *ctx, void *stream, int32_t n_gaps, const int32_t *W, const int32_t *C,
                    const sja_params *params, const int32_t *wait, const uint8_t *sla_class,
                    const int32_t *job_held, const uint8_t *gap_active, int32_t *cand_job, int32_t *cand_cut,

@@ -363,3 +363,26 @@ def test_largest_gap_count(engine, oracle):
     wl = make_workload("small", 21, n_gaps=1 << 20, n_jobs=37)
     wl.C = np.ascontiguousarray(np.where(np.arange(wl.n_gaps) % 3 == 0, 20480, 40960).astype(np.int32))
     full_tick_check(engine, oracle, wl, policies=[wl.policy])
+
+
+def test_store_reference_writes_the_whole_matrix(engine):
+    """The measurement aid covers exactly the pair matrix: afterwards cut[g][j] = j for every pair
+    (ragged sizes, several capacity classes), and it refuses to run without a plan."""
+    import torch
+    import paper_2509_19086_amd as P
+    for name, seed, kw in (("tiny", 0, {}), ("small", 2, {}), ("medium", 3, dict(n_gaps=333, n_jobs=1111))):
+        wl = make_workload(name, seed, **kw)
+        t = P.DeviceTick(engine, wl, want_bits=False)
+        t.prepare()
+        with pytest.raises(P.SjaError):
+            engine.sja_store_reference(t.cut)
+        t.fit()
+        t.cut.fill_(-7)
+        guard = torch.full((64,), -9, dtype=torch.int32, device="cuda:0")     # allocated right behind: must stay as it is
+        engine.sja_store_reference(t.cut)
+        torch.cuda.synchronize()
+        want = torch.arange(wl.n_jobs, dtype=torch.int32, device="cuda:0").expand(wl.n_gaps, wl.n_jobs)
+        assert torch.equal(t.cut.view(wl.n_gaps, wl.n_jobs), want)
+        assert bool((guard == -9).all())
+        with pytest.raises(P.SjaError):                    # the matrix no longer holds the replies
+            t.select(P.Params.make(0))
