@@ -201,6 +201,7 @@ class Engine:
         rc = getattr(self.lib, _entry)(self.h, _stream(), J, S, *args)
         self._check(rc, self.h)
         self.n_jobs = J
+        self.n_gaps = 0          # a new prepare ends the last batch of gaps, as in the library
 
     def sja_prepare_profiles_static(self, seg_off, dur, mem, safe, progress, pre_dur, pre_peak, prev_safe):
         """The same call on the library's built-in scratch: no workspace tensor is involved."""
