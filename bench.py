@@ -52,9 +52,9 @@ def secondary_rates(wl, n_atoms_total, call_ms, rounds):
 # sources are hashed, and a different hash means the counters are stale.
 FIT_TRAFFIC = {
     "workload": ("stress", 0),
-    "sources_sha256": "b089018c3e7012e8ab5733925295e5e53dd4934a0521787dcb9fcfca52b489b4",
-    "fetch_kib": 51076.0, "fetch_scale": 2.0,
-    "write_kib": 8393686.0, "write_scale": 1.0,
+    "sources_sha256": "14ee7b0dc06ab05fd6a4a4f7c25c8ad1e6d0bdd284448aca611afc22c17fcb26",
+    "fetch_kib": 51533.7, "fetch_scale": 2.0,
+    "write_kib": 8391656.0, "write_scale": 1.0,
 }
 
 

@@ -17,7 +17,7 @@ constexpr int kWave = 64;
 constexpr int kFitBlock = 128;        // threads per fit block, one job per thread
 constexpr int kFitMaxChunk = 512;     // most sorted gap positions one fit block walks
 constexpr int kFitWindow = 16;        // atoms per job staged ahead in LDS (power of two)
-constexpr int kFitPeriod = 64;        // steps between window top-ups (multiple of 4)
+constexpr int kFitPeriod = 32;        // steps between window top-ups (multiple of 4)
 constexpr int kMaxClasses = 64;       // distinct capacities served by the table-driven path
 constexpr int kSelBlock = 256;        // threads per select block, one job per thread
 constexpr int kSelGapChunk = 64;      // sorted gap positions walked by one select block
