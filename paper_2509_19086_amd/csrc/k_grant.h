@@ -191,13 +191,19 @@ __global__ void k_list_blocks_write(int lb_cap, const int32_t *__restrict__ plan
 // that some position of v gets: atom a applies to lanes [lo, hi) where lo is
 // the first position whose window reaches D_a and hi the first one that
 // already reaches atom a+1.  Every entry is one 64-bit word, v : rank : hi (7
-// bits) : lo (6 bits), stored wherever the running total puts it (the sort
-// orders them); entries beyond entry_cap are counted but not stored.
-// A block takes kEmitTiles tiles of 256 jobs for one list block: it counts
-// first, reserves its room with ONE addition to the running total (additions
-// to one word are served one after the other: one per wave made this kernel
-// three times slower), then writes.
+// bits) : lo (6 bits); where it is stored does not matter (the sort orders
+// them); entries beyond entry_cap are counted but not stored.
+// A block takes kEmitTiles tiles of 256 jobs for one list block.  Each tile is
+// visited once: the entries go to a buffer in LDS as they are found (the lanes
+// of a wave that find one in the same step of the visit take their places with
+// one addition); once the buffer is half full, and after the last tile, the
+// block reserves room in the output with one addition to the running total
+// (additions to one word are served one after the other: one per wave made
+// this kernel three times slower) and copies the buffer out with coalesced
+// stores.  Entries that find the buffer full go straight to the output, a
+// wave's step at a time.
 constexpr int kEmitTiles = 8;
+constexpr int kEmitBuffer = 3072;     // entries staged in LDS (24 KB: six blocks per compute unit)
 
 template <typename Sink>
 __device__ __forceinline__ void list_visit(const int2 *__restrict__ dp, const int *s_w, int len, int a_first, int n_cap,
@@ -228,72 +234,68 @@ __global__ __launch_bounds__(256) void k_list_emit(
     unsigned long long *__restrict__ ekey)
 {
     __shared__ int s_w[64];
-    __shared__ int s_total, s_cursor;
+    __shared__ unsigned long long s_buf[kEmitBuffer];
+    __shared__ int s_cursor, s_all;
     __shared__ unsigned long long s_base;
     const int u = blockIdx.y;                  // list block
     if (!plan[kPlanTabled] || u >= min(plan[kPlanListBlocks], lb_cap)) return;
     const int b0 = lb_begin[u], len = lb_end[u] - b0;
     if (threadIdx.x < 64) s_w[threadIdx.x] = threadIdx.x < len ? gap_w[b0 + threadIdx.x] : INT32_MAX;
-    if (threadIdx.x == 0) { s_total = 0; s_cursor = 0; }
+    if (threadIdx.x == 0) { s_cursor = 0; s_all = 0; }
     __syncthreads();
     const int lane = threadIdx.x & (kWave - 1);
     const int sub = lb_sub[u];
     const int cls = sub_class[sub];
     const int j0 = blockIdx.x * (kEmitTiles * 256) + threadIdx.x;
-
-    int a_first[kEmitTiles], n_cap[kEmitTiles], cnt[kEmitTiles];
-    int mine = 0;
-#pragma unroll
+    const unsigned long long head = (unsigned long long)u << rank_bits;
     for (int it = 0; it < kEmitTiles; ++it) {
         const int j = j0 + it * 256;
-        a_first[it] = 0; n_cap[it] = 0; cnt[it] = 0;
         if (j < n_jobs) {
             int af = start_tab[int64_t(sub) * n_jobs + j];
             const int nc = ncap_tab[int64_t(cls) * n_jobs + j];
             const int2 *dp = atom_dp + seg_off[j];
             // the table holds the count at the sub-block's first position; a later piece starts further on
             while (af < nc && dp[af].x <= s_w[0]) ++af;
-            int c = 0;
-            list_visit(dp, s_w, len, af, nc, [&](int, int, int) { ++c; });
-            a_first[it] = af; n_cap[it] = nc; cnt[it] = c;
-            mine += c;
-        }
-    }
-    int wave_sum = mine;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) wave_sum += __shfl_xor(wave_sum, d, kWave);
-    if (lane == 0 && wave_sum) atomicAdd(&s_total, wave_sum);
-    __syncthreads();
-    if (threadIdx.x == 0 && s_total) {
-        atomicAdd(&sub_count[u], s_total);
-        s_base = atomicAdd(total, (unsigned long long)s_total);
-    }
-    __syncthreads();
-    const int block_total = s_total;
-    if (block_total == 0 || (long long)(s_base + block_total) > entry_cap) return;
-#pragma unroll
-    for (int it = 0; it < kEmitTiles; ++it) {
-        int incl = cnt[it];
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int t = __shfl_up(incl, d, kWave);
-            if (lane >= d) incl += t;
-        }
-        const int wave_total = __shfl(incl, kWave - 1, kWave);
-        int wave_off = 0;
-        if (lane == 0 && wave_total) wave_off = atomicAdd(&s_cursor, wave_total);
-        wave_off = __shfl(wave_off, 0, kWave);
-        if (cnt[it]) {
-            const int j = j0 + it * 256;
-            int64_t slot = int64_t(s_base) + wave_off + incl - cnt[it];
             const int a0 = abase[j];
-            list_visit(atom_dp + seg_off[j], s_w, len, a_first[it], n_cap[it], [&](int a, int lo, int hi) {
-                ekey[slot] = ((((unsigned long long)u << rank_bits) | rank[a0 + a]) << kEntryLaneBits) |
-                             (unsigned long long)((hi << 6) | lo);
-                ++slot;
+            list_visit(dp, s_w, len, af, nc, [&](int a, int lo, int hi) {
+                const unsigned long long key = ((head | rank[a0 + a]) << kEntryLaneBits) | (unsigned long long)((hi << 6) | lo);
+                // the lanes of this wave that are at this point together
+                const unsigned long long peers = __ballot(true);
+                const int n_peers = __popcll(peers);
+                const int mine = __popcll(peers & lanes_below(lane));
+                int at = 0;
+                if (mine == 0) at = atomicAdd(&s_cursor, n_peers);
+                at = __shfl(at, __ffsll((long long)peers) - 1, kWave) + mine;
+                if (at < kEmitBuffer) {
+                    s_buf[at] = key;
+                } else {
+                    // the buffer is full: this step's surplus goes straight out
+                    const unsigned long long over = __ballot(true);
+                    unsigned long long to = 0;
+                    if (lane == __ffsll((long long)over) - 1) to = atomicAdd(total, (unsigned long long)__popcll(over));
+                    to = __shfl(to, __ffsll((long long)over) - 1, kWave) + __popcll(over & lanes_below(lane));
+                    if ((long long)to < entry_cap) ekey[to] = key;
+                }
             });
         }
+        __syncthreads();
+        const int found = s_cursor;                           // entries since the last copy, surplus included
+        __syncthreads();                                      // everybody has read it before anybody adds to it again
+        if (found < kEmitBuffer / 2 && it + 1 < kEmitTiles) continue;       // uniform over the block
+        const int staged = min(found, kEmitBuffer);
+        if (threadIdx.x == 0) {
+            s_all += found;
+            s_base = staged ? atomicAdd(total, (unsigned long long)staged) : 0ull;
+        }
+        __syncthreads();
+        const unsigned long long out0 = s_base;
+        for (int i = threadIdx.x; i < staged; i += 256)
+            if ((long long)(out0 + i) < entry_cap) ekey[out0 + i] = s_buf[i];
+        __syncthreads();
+        if (threadIdx.x == 0) s_cursor = 0;
+        __syncthreads();
     }
+    if (threadIdx.x == 0 && s_all) atomicAdd(&sub_count[u], s_all);
 }
 
 __device__ __forceinline__ unsigned long long claim_of(int round, int g)
@@ -322,7 +324,7 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // 1 = granted, 2 = no candidate left (in memory the flag shares its word with
 // the gap index).  r[] holds the records at st.x on entry.
 constexpr int kWalk = 1;         // records a lane reads per trip on its own (8: 2.7 ms slower per Stress resolve)
-constexpr int kSweep = 3;        // chunks of 64 records the wave reads per trip when it walks together
+constexpr int kSweep = 2;        // chunks of 64 records the wave reads per trip when it walks together (3: 1.7 ms slower per Stress resolve, 4: 3.7 ms)
 constexpr int kSweepHeld = 8;    // the same with the held bitmap: no claim words to fetch, so a wider trip costs little
 constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
 constexpr int kRoundBlock = 256; // threads per block of the round kernel

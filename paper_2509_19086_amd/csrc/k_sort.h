@@ -134,13 +134,24 @@ __global__ __launch_bounds__(256) void k_keys_hist(const unsigned long long *__r
     hist[int64_t(tid) * n_tiles + blockIdx.x] = s_h[tid];
 }
 
-// PAY: every key carries a 32-bit payload that moves with it.
-template <bool PAY>
+// What the last pass over list entries writes instead of the keys themselves: 16-byte records
+// (job, atom, lo | hi << 8, 0), the (job, atom) looked up by the key's rank field, lo (6 bits) and
+// hi (7 bits) its lowest lane_bits bits.
+struct KeyRecords {
+    const int2 *ranked;
+    uint4 *rec;
+    int lane_bits, rank_bits;
+};
+
+// PAY: every key carries a 32-bit payload that moves with it.  REC: the sorted keys are not
+// written at all, their records are (the pass that finishes the order of the list entries).
+template <bool PAY, bool REC = false>
 __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *__restrict__ src,
                                                       unsigned long long *__restrict__ dst,
                                                       const uint32_t *__restrict__ pay_src,
                                                       uint32_t *__restrict__ pay_dst, const int32_t *n_ptr,
-                                                      int shift, const int32_t *__restrict__ hist, int n_tiles)
+                                                      int shift, const int32_t *__restrict__ hist, int n_tiles,
+                                                      KeyRecords out = KeyRecords{})
 {
     __shared__ unsigned long long s_key[kKeyTile];
     __shared__ uint32_t s_pay[PAY ? kKeyTile : 1];
@@ -213,7 +224,13 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
         const unsigned long long v = s_key[k];
         const unsigned d = unsigned(v >> shift) & 255u;
         const int64_t o = int64_t(s_goff[d]) + (k - s_start[d]);
-        dst[o] = v;
+        if (REC) {
+            const int2 ja = out.ranked[(v >> out.lane_bits) & ((1ull << out.rank_bits) - 1ull)];
+            const unsigned int lo = unsigned(v) & 63u, hi = unsigned(v >> 6) & 127u;
+            out.rec[o] = make_uint4(uint32_t(ja.x), uint32_t(ja.y), lo | (hi << 8), 0u);
+        } else {
+            dst[o] = v;
+        }
         if (PAY) pay_dst[o] = s_pay[k];
     }
 }

@@ -152,9 +152,13 @@ int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const 
 // needs no pass).
 int radix_sort_keys(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t *n_dev, int64_t n_host,
                     unsigned byte_mask, int bit_offset, bool &flip, unsigned long long *const buf[2],
-                    uint32_t *const pay[2])
+                    uint32_t *const pay[2], const KeyRecords *records = nullptr, bool *records_written = nullptr)
 {
+    if (records_written) *records_written = false;
     if (n_host <= 0) return SJA_OK;
+    int last_byte = -1;         // the pass that finishes the order: with `records` it writes those instead of keys
+    for (int b = 0; b < 8; ++b)
+        if (((byte_mask >> b) & 1u) && bit_offset + 8 * b < 64) last_byte = b;
     const int n_tiles = int((n_host + kKeyTile - 1) / kKeyTile);
     int32_t *hist = ws_ptr<int32_t>(ctx, L.g_hist);
     int32_t *tmp = ws_ptr<int32_t>(ctx, L.g_scan_tmp);
@@ -168,12 +172,17 @@ int radix_sort_keys(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t
         SJA_HIP(hipGetLastError(), "k_keys_hist launch");
         SJA_HIP(enqueue_scan(st, hist, int64_t(256) * n_tiles, tmp, nullptr), "radix scan launch");
         if (pay)
-            hipLaunchKernelGGL(k_keys_scatter<true>, dim3(n_tiles), dim3(256), 0, st, src, dst, pay[flip ? 1 : 0],
-                               pay[flip ? 0 : 1], n_dev, shift, hist, n_tiles);
-        else
-            hipLaunchKernelGGL(k_keys_scatter<false>, dim3(n_tiles), dim3(256), 0, st, src, dst,
+            hipLaunchKernelGGL((k_keys_scatter<true, false>), dim3(n_tiles), dim3(256), 0, st, src, dst, pay[flip ? 1 : 0],
+                               pay[flip ? 0 : 1], n_dev, shift, hist, n_tiles, KeyRecords{});
+        else if (records && b == last_byte) {
+            hipLaunchKernelGGL((k_keys_scatter<false, true>), dim3(n_tiles), dim3(256), 0, st, src, dst,
                                static_cast<const uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), n_dev, shift,
-                               hist, n_tiles);
+                               hist, n_tiles, *records);
+            if (records_written) *records_written = true;
+        } else
+            hipLaunchKernelGGL((k_keys_scatter<false, false>), dim3(n_tiles), dim3(256), 0, st, src, dst,
+                               static_cast<const uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), n_dev, shift,
+                               hist, n_tiles, KeyRecords{});
         SJA_HIP(hipGetLastError(), "k_keys_scatter launch");
         flip = !flip;
     }
@@ -300,16 +309,18 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(hipStreamSynchronize(st), "entry count synchronise");
     if (n_entries > L.entry_cap || n_entries >= (1ll << 31)) return SJA_OK;
     SJA_HIP(enqueue_scan(st, list_off, int64_t(lb_bound) + 2, tmp, nullptr), "list offset scan launch");
-    bool eflip = false;
+    bool eflip = false, packed = false;
+    uint4 *rec = ws_ptr<uint4>(ctx, L.g_rec);
     if (n_entries > 0) {
+        // the pass that finishes the order writes the 16-byte records straight away
         const int key_bytes = (rank_bits + sub_bits + 7) / 8;
+        const KeyRecords records{ranked, rec, kEntryLaneBits, rank_bits};
         int rc = radix_sort_keys(ctx, st, L, counters, n_entries, (1u << key_bytes) - 1u, kEntryLaneBits, eflip, ekey,
-                                 nullptr);
+                                 nullptr, &records, &packed);
         if (rc != SJA_OK) return rc;
     }
     const int fb = eflip ? 1 : 0;
-    uint4 *rec = ws_ptr<uint4>(ctx, L.g_rec);
-    if (n_entries > 0) {
+    if (n_entries > 0 && !packed) {
         hipLaunchKernelGGL(k_list_pack, dim3(unsigned((n_entries + 255) / 256)), dim3(256), 0, st, counters, ekey[fb],
                            rank_bits, ranked, rec);
         SJA_HIP(hipGetLastError(), "k_list_pack launch");
