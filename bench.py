@@ -113,7 +113,21 @@ def cpu_baseline(wl, sample_gaps):
     res = O.resolve(cut, wl.seg_off, pd, pp, par, wl.wait, wl.sla_class)
     t4 = time.perf_counter()
     total = t4 - t0
+    # one core, for scale: the per-pair walk on a slice of the same batch (about a second of work)
+    one = {}
+    threads = O.num_threads()
+    try:
+        O.set_num_threads(1)
+        n1 = max(1, min(n, 64))
+        t5 = time.perf_counter()
+        O.fit(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, np.ascontiguousarray(wl.W[:n1]),
+              np.ascontiguousarray(wl.C[:n1]), False)
+        t6 = time.perf_counter()
+        one = {"fit_only_value_one_core": n1 * wl.n_jobs / (t6 - t5), "one_core_sample_gaps": n1}
+    finally:
+        O.set_num_threads(threads)
     return {
+        **one,
         "value": n * wl.n_jobs / total,
         "unit": "fit evaluations/s",
         "cores": O.num_threads(),
