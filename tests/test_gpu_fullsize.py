@@ -393,3 +393,64 @@ def test_stress_area_score_full_size(oracle):
     torch.cuda.synchronize()
     for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
         assert torch.equal(a, b)
+
+
+def test_stress_hysteresis_full_size(oracle):
+    """The hysteresis rule at the full Stress size (the gaps' own capacity set, a gain of one slice):
+    sampled pairs and whole sampled rows of the cut matrix, the fused candidates for every gap, and
+    every grant's cut and score recomputed by the oracle under the rule."""
+    import torch
+    import paper_2509_19086_amd as P
+    wl = make_workload("stress", 0)
+    G, J = wl.n_gaps, wl.n_jobs
+    cap_set = np.unique(wl.C).astype(np.int32)
+    min_gain = int(cap_set[0])
+    eng = P.Engine(0)
+    eng.sja_set_hysteresis(cap_set, min_gain)
+    t = P.DeviceTick(eng, wl, want_bits=True)
+    par = P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 8)
+    opar = oracle.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, 8)
+    t.prepare(); t.fit(); t.select(par)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(47)
+    gi = rng.integers(0, G, size=300_000).astype(np.int32)
+    ji = rng.integers(0, J, size=300_000).astype(np.int32)
+    want, _, _ = oracle.fit_pairs_hysteresis(gi, ji, wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C,
+                                             cap_set, min_gain)
+    plain, _, _ = oracle.fit_pairs(gi, ji, wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress, wl.W, wl.C)
+    assert (want != plain).mean() > 0.05                       # the rule acts
+    flat = torch.from_numpy(gi.astype(np.int64) * J + ji.astype(np.int64)).cuda()
+    np.testing.assert_array_equal(t.cut.view(-1)[flat].cpu().numpy(), want)
+
+    rows = np.unique(np.concatenate([[0, G - 1, int(np.argmax(wl.W))], rng.integers(0, G, size=8)])).astype(np.int64)
+    cut_r, bits_r = oracle.fit_hysteresis(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress,
+                                          np.ascontiguousarray(wl.W[rows]), np.ascontiguousarray(wl.C[rows]),
+                                          cap_set, min_gain, want_bits=True)
+    rows_t = torch.from_numpy(rows).cuda()
+    np.testing.assert_array_equal(t.cut[rows_t].cpu().numpy(), cut_r)
+    np.testing.assert_array_equal(t.bits[rows_t].cpu().numpy().view(np.uint32), bits_r)
+    pd, pp, _ = oracle.prepare(wl.seg_off, wl.dur, wl.mem, wl.safe, wl.progress)
+    cj, cc, cs = oracle.select(cut_r, wl.seg_off, pd, pp, opar, wl.wait, wl.sla_class)
+    np.testing.assert_array_equal(t.cand_job[rows_t].cpu().numpy(), cj)
+    np.testing.assert_array_equal(t.cand_cut[rows_t].cpu().numpy(), cc)
+    np.testing.assert_array_equal(t.cand_score[rows_t].cpu().numpy(), cs)
+
+    sel = (t.cand_job.clone(), t.cand_cut.clone(), t.cand_score.clone())
+    t.fit_select(par)
+    torch.cuda.synchronize()
+    for a, b in zip(sel, (t.cand_job, t.cand_cut, t.cand_score)):
+        assert torch.equal(a, b)
+
+    t.resolve(par)
+    gj = t.grant_job.cpu().numpy(); gc = t.grant_cut.cpu().numpy(); gs = t.grant_score.cpu().numpy()
+    jg = t.job_gap.cpu().numpy()
+    granted = np.nonzero(gj >= 0)[0]
+    assert len(granted) > 500 and len(np.unique(gj[granted])) == len(granted)
+    np.testing.assert_array_equal(jg[gj[granted]], granted)
+    ocut, sd, sp = oracle.fit_pairs_hysteresis(granted.astype(np.int32), gj[granted], wl.seg_off, wl.dur, wl.mem,
+                                               wl.safe, wl.progress, wl.W, wl.C, cap_set, min_gain)
+    np.testing.assert_array_equal(gc[granted], ocut)
+    np.testing.assert_array_equal(gs[granted], sd * sp * (wl.wait_scale + wl.wait[gj[granted]].astype(np.int64)))
+    assert gj[0] == cj[0] and gc[0] == cc[0] and gs[0] == cs[0]
+    eng.sja_set_hysteresis(None)
