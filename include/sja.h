@@ -26,6 +26,10 @@
  *                         (Sec. 3.9)
  *   sja_advance           end of the tick: granted jobs move to their cut and
  *                         only their tables are rebuilt (Sec. 3.1 / 3.5)
+ * Beside the method: sja_validate (input preconditions, checked on the device),
+ * sja_prepare_profiles_static (the prepare for callers that cannot allocate),
+ * sja_set_score, sja_set_resolve_mode, and two measurement aids
+ * (sja_enable_timing / sja_last_fit_kernel_ms, sja_store_reference).
  *
  * Conventions
  *   - Every array argument is a DEVICE pointer owned by the caller, unless the
