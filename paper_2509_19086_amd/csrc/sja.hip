@@ -117,24 +117,35 @@ PolicyDev to_dev(const sja_params *p)
     return d;
 }
 
-// Enqueues the two select kernels; outputs may be user or workspace arrays.
+// Enqueues the select kernels; outputs may be user or workspace arrays.  The
+// per-prefix keys live in the space the list building of sja_resolve uses for
+// its atom keys (the two never run at the same time); `keys_ready` says that an
+// earlier call with the same policy inputs left them there and nothing has
+// written that space since.
 int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const int32_t *wait,
                   const uint8_t *sla_class, const int32_t *job_held, const uint8_t *gap_active,
-                  int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score)
+                  int32_t *cand_job, int32_t *cand_cut, int64_t *cand_score, bool keys_ready = false)
 {
     const Layout L = make_layout(ctx->n_gaps, ctx->n_jobs, ctx->n_segments);
     const int G = ctx->n_gaps, J = ctx->n_jobs;
     if (G == 0) return SJA_OK;
     const int job_tiles = (J + kSelBlock - 1) / kSelBlock;
+    unsigned long long *seg_key = ws_ptr<unsigned long long>(ctx, L.g_key_hi);
+    if (job_tiles > 0 && !keys_ready) {
+        const long long *pre_area = pre_area_of(ctx, L);
+        auto kern = pre_area ? k_select_keys<true> : k_select_keys<false>;
+        hipLaunchKernelGGL(kern, dim3((J + 3) / 4), dim3(256), 0, st, J, to_dev(params), ctx->seg_off, ctx->pre_dur,
+                           ctx->pre_peak, pre_area, wait, sla_class, seg_key);
+        SJA_HIP(hipGetLastError(), "k_select_keys launch");
+    }
     if (job_tiles > 0) {
         const int n_chunks = (G + kSelGapChunk - 1) / kSelGapChunk;
         const int tiles8 = (job_tiles + 7) / 8 * 8;
         const unsigned grid = unsigned(tiles8) * unsigned(n_chunks);
         const bool mixed = params->policy == SJA_POLICY_MIXED;
-        auto kern = pre_area_of(ctx, L) ? (mixed ? k_select_pass<true, true> : k_select_pass<false, true>)
-                                        : (mixed ? k_select_pass<true, false> : k_select_pass<false, false>);
+        auto kern = mixed ? k_select_pass<true> : k_select_pass<false>;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(kSelBlock), 0, st, J, G, n_chunks,
-                           to_dev(params), ctx->seg_off, ctx->pre_dur, ctx->pre_peak, pre_area_of(ctx, L), ctx->cut,
+                           to_dev(params), ctx->seg_off, seg_key, ctx->cut,
                            ws_ptr<int32_t>(ctx, L.gap_order), wait, sla_class, job_held, gap_active,
                            ws_ptr<SelPartial>(ctx, L.sel_part));
         SJA_HIP(hipGetLastError(), "k_select_pass launch");
@@ -981,7 +992,8 @@ int sja_resolve(sja_ctx *ctx, void *stream, const sja_params *params, const int3
             // the round's selection over the still-active gaps and un-held jobs: from the cut matrix if
             // sja_fit left one, else by evaluating the pairs again (the fused pass; nothing is stored)
             if (ctx->fitted)
-                rc = launch_select(ctx, st, params, wait, sla_class, job_gap, active, cand_job, cand_cut, cand_score);
+                rc = launch_select(ctx, st, params, wait, sla_class, job_gap, active, cand_job, cand_cut, cand_score,
+                                   /*keys_ready=*/r > 1);
             else
                 rc = launch_fused(ctx, st, L, G, params, wait, sla_class, job_gap, active, cand_job, cand_cut, cand_score,
                                   false);

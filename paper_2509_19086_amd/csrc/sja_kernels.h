@@ -688,14 +688,40 @@ __device__ __forceinline__ bool key_better(unsigned long long hi_a, unsigned lon
     return j_a < j_b;
 }
 
+// The key of every prefix of every job, ((tier << 62) | F * multiplier) + 1, once
+// per call: the stepping kernel below then fetches a finished key where a job's
+// cut changes instead of (duration, peak) and three 64-bit multiplies per lane.
+// One wave per job; the kernel moves 16 bytes per segment and runs at the rate
+// of a copy (a wave running along four neighbouring jobs as one stretch, so that
+// the shortest jobs fill it, was no faster).  Prefixes before a job's progress
+// hold whatever the prefix arrays hold there; no cut points at them.
+template <bool AREA>
+__global__ __launch_bounds__(256) void k_select_keys(
+    int n_jobs, PolicyDev pol, const int64_t *__restrict__ seg_off, const int32_t *__restrict__ pre_dur,
+    const int32_t *__restrict__ pre_peak, const long long *__restrict__ pre_area,
+    const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
+    unsigned long long *__restrict__ seg_key)
+{
+    const int lane = lane_id();
+    const int j = blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+    if (j >= n_jobs) return;
+    const int64_t base = seg_off[j];
+    const int L = int(seg_off[j + 1] - base);
+    unsigned long long mult, tier;
+    job_policy(pol, wait, sla_class, j, mult, tier);
+    for (int k = lane; k < L; k += kWave) {
+        const unsigned long long F = AREA ? (unsigned long long)pre_area[base + k] : rect_of(pre_dur[base + k], pre_peak[base + k]);
+        seg_key[base + k] = ((tier << 62) | times_mult(F, mult)) + 1ull;
+    }
+}
+
 // Steps reduced together by one wave (see k_select_pass).
 constexpr int kSelBatch = 8;
 
-template <bool MIXED, bool AREA>
+template <bool MIXED>
 __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     int n_jobs, int n_gaps, int n_chunks, PolicyDev pol, const int64_t *__restrict__ seg_off,
-    const int32_t *__restrict__ pre_dur, const int32_t *__restrict__ pre_peak,
-    const long long *__restrict__ pre_area, const int32_t *__restrict__ cut, const int32_t *__restrict__ gap_order,
+    const unsigned long long *__restrict__ seg_key, const int32_t *__restrict__ cut, const int32_t *__restrict__ gap_order,
     const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
     const int32_t *__restrict__ job_held, const uint8_t *__restrict__ gap_active,
     SelPartial *__restrict__ part)
@@ -705,7 +731,6 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     __shared__ unsigned long long s_key[WAVES][kSelBatch][ROW];   // one batch of per-lane keys per wave
     __shared__ unsigned long long s_mult[WAVES][kWave];           // per-lane score multiplier (MIXED ties)
     __shared__ unsigned long long s_hi[WAVES][kSelGapChunk];
-    __shared__ unsigned long long s_lo[WAVES][kSelGapChunk];
     __shared__ int s_job[WAVES][kSelGapChunk];
 
     const int xcd = blockIdx.x & 7;
@@ -724,7 +749,7 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
     if (usable) {
         if (job_held && job_held[j] >= 0) usable = false;
         base = seg_off[j];
-        job_policy(pol, wait, sla_class, j, mult, tier);
+        if (MIXED) job_policy(pol, wait, sla_class, j, mult, tier);    // the multiplier, for ties only
     }
     s_mult[wave][lane] = mult;
 
@@ -757,24 +782,15 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
 #pragma unroll
         for (int t = 0; t < kSelBatch; ++t) cv[t] = cv_next[t];
         // a job's cut rarely changes from one sorted position to the next: only the changes
-        // gather (duration, peak), all of a batch's gathers in flight together
-        int dv[kSelBatch], pv[kSelBatch];    // AREA: the two halves of F itself, read instead of (duration, peak)
+        // gather the prefix's key, all of a batch's gathers in flight together
+        unsigned long long kv[kSelBatch];
         bool fresh[kSelBatch];
         int prev = last_cut;
 #pragma unroll
         for (int t = 0; t < kSelBatch; ++t) {
             const int c = cv[t];
             fresh[t] = c >= 0 && c != prev;
-            if (fresh[t]) {
-                if (AREA) {
-                    const long long a = pre_area[base + c - 1];
-                    dv[t] = int(uint32_t(a));
-                    pv[t] = int(uint32_t((unsigned long long)a >> 32));
-                } else {
-                    dv[t] = pre_dur[base + c - 1];
-                    pv[t] = pre_peak[base + c - 1];
-                }
-            }
+            if (fresh[t]) kv[t] = seg_key[base + c - 1];
             prev = c >= 0 ? c : prev;
         }
         last_cut = prev;
@@ -782,11 +798,7 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
         if (s0 + kSelBatch < s_end) load_cuts(s0 + kSelBatch, cv_next);
 #pragma unroll
         for (int t = 0; t < kSelBatch; ++t) {
-            if (fresh[t]) {
-                const unsigned long long F = AREA ? (((unsigned long long)uint32_t(pv[t]) << 32) | uint32_t(dv[t]))
-                                                  : rect_of(dv[t], pv[t]);
-                hi = ((tier << 62) | times_mult(F, mult)) + 1ull;
-            }
+            if (fresh[t]) hi = kv[t];
             s_key[wave][t][lane] = cv[t] >= 0 ? hi : 0ull;
         }
         // the keys just written are read by other lanes of this wave: order the two
@@ -817,28 +829,31 @@ __global__ __launch_bounds__(kSelBlock) void k_select_pass(
             }
             if (better) { bh = oh; bsrc = osrc; }
         }
+        // the winner's secondary score is a 64-bit division: it is left to the end, where it is
+        // needed once per position (and per tie between waves), not once per wave and batch
         if (lane < n_step) {
             const int slot = s0 - s_begin + lane;
-            int wj = -1;
-            unsigned long long wl = 0;
-            if (bh) {
-                wj = wave_job0 + bsrc;
-                wl = second(bh, bsrc);
-            }
-            s_hi[wave][slot] = bh; s_lo[wave][slot] = wl; s_job[wave][slot] = bh ? wj : INT32_MAX;
+            s_hi[wave][slot] = bh; s_job[wave][slot] = bh ? wave_job0 + bsrc : INT32_MAX;
         }
     }
     __syncthreads();
+    // secondary score of wave w's winner (its multiplier sits in that wave's row of s_mult)
+    auto second_of = [&](unsigned long long key, int w, int job) -> unsigned long long {
+        return MIXED ? ((key - 1ull) & ((1ull << 62) - 1ull)) / s_mult[w][job - (job_tile * kSelBlock + w * kWave)] : 0ull;
+    };
     for (int slot = threadIdx.x; slot < s_end - s_begin; slot += kSelBlock) {
-        unsigned long long bh = s_hi[0][slot], bl = s_lo[0][slot];
-        int bj = s_job[0][slot];
-        if (bh == 0) bj = INT32_MAX;
+        unsigned long long bh = s_hi[0][slot];
+        int bj = bh ? s_job[0][slot] : INT32_MAX, bw = 0;
 #pragma unroll
         for (int w = 1; w < WAVES; ++w) {
-            const unsigned long long oh = s_hi[w][slot], ol = s_lo[w][slot];
+            const unsigned long long oh = s_hi[w][slot];
             const int oj = oh ? s_job[w][slot] : INT32_MAX;
-            if (key_better(oh, ol, oj, bh, bl, bj)) { bh = oh; bl = ol; bj = oj; }
+            bool better = oh > bh;
+            // equal keys: the larger secondary score, then the lower job, which is the earlier wave's
+            if (MIXED && oh == bh && oh != 0) better = second_of(oh, w, oj) > second_of(bh, bw, bj);
+            if (better) { bh = oh; bj = oj; bw = w; }
         }
+        const unsigned long long bl = (MIXED && bh) ? second_of(bh, bw, bj) : 0ull;
         const int g = gap_order[s_begin + slot];
         // the winner's cut, fetched here for all of the block's positions at once (inside the
         // stepping loop it would be one more memory trip per batch)
