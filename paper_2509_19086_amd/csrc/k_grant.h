@@ -322,16 +322,24 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // the first entry that covers it and whose job is not held, and claims it.
 // st = (pointer, candidate job, candidate atom, flag) with flag 0 = active,
 // 1 = granted, 2 = no candidate left (in memory the flag shares its word with
-// the gap index).  r[] holds the records at st.x on entry.
-constexpr int kWalk = 1;         // records a lane reads per trip on its own (8: 2.7 ms slower per Stress resolve)
-constexpr int kSweep = 2;        // chunks of 64 records the wave reads per trip when it walks together (3: 1.7 ms slower per Stress resolve, 4: 3.7 ms)
+// the gap index).
+//
+// The lanes of a wave walk together: per round trip the wave reads kSweep chunks
+// of 64 records, starting at the chunk of its lowest pointer still looking, and
+// the claim words of those that cover a lane still looking.  A lane passes the
+// records of its block that cover other lanes only (a job's other cuts), so
+// most rounds some lane of most waves has more than one record to look at; a
+// first look at the lane's own next record alone, with the joint walk behind it
+// when that was not the one, made nine rounds in ten two trips longer.  The
+// first chunks are asked for before the wave knows who won round k-1 (nearly
+// every open lane lost), so they travel beside that check's claim word.
+constexpr int kSweep = 2;        // chunks of 64 records the wave reads per trip (3: 1.7 ms slower per Stress resolve, 4: 3.7 ms)
 constexpr int kSweepHeld = 8;    // the same with the held bitmap: no claim words to fetch, so a wider trip costs little
-constexpr int kOwnTrips = 1;     // batches a lane walks alone before the wave walks together
 constexpr int kRoundBlock = 256; // threads per block of the round kernel
 constexpr int kBlockClaims = 256; // claims a block merges in LDS per round
 
 constexpr int kHeldMaxWords = 4096;   // words of the held-job bitmap a block keeps in LDS (jobs / 32)
-constexpr int kHeldRounds = 512;      // rounds that keep and read the bitmap; later rounds hardly ever walk together
+constexpr int kHeldRounds = 512;      // rounds that keep and read the bitmap
 
 __device__ __forceinline__ bool held_bit(const uint32_t *s_held, uint32_t job)
 {
@@ -339,23 +347,37 @@ __device__ __forceinline__ bool held_bit(const uint32_t *s_held, uint32_t job)
 }
 
 // HELD (the early rounds, where lanes pass hundreds of records of jobs that were
-// just taken): when the wave walks together it asks a bitmap in LDS which jobs
-// were held before this round, instead of fetching a claim word per record, so a
-// joint trip is one memory trip, not two; only the record a lane settles on has
-// its claim word fetched.  Two bitmaps alternate: a round reads one and writes
-// only the other (held_next), so nothing it reads changes under it.  A job named
-// in round k is held from round k+1 on, whoever wins it: the gaps naming it set
-// its bit in the bitmap round k+1 reads, and its winner, when it learns in round
-// k+1 that it won, sets it in the other one, after which both carry it.
+// just taken): the wave asks a bitmap in LDS which jobs were held before this
+// round, instead of fetching a claim word per record, so a trip is one memory
+// trip, not two; only the record a lane settles on has its claim word fetched.
+// Two bitmaps alternate: a round reads one and writes only the other
+// (held_next), so nothing it reads changes under it.  A job named in round k is
+// held from round k+1 on, whoever wins it: the gaps naming it set its bit in the
+// bitmap round k+1 reads, and its winner, when it learns in round k+1 that it
+// won, sets it in the other one, after which both carry it.
 template <bool HELD>
 __device__ __forceinline__ void grant_step(int round, bool propose, int lane, int g, int list_begin, int list_end,
                                            const uint4 *__restrict__ rec, unsigned long long *claim, int4 &st,
-                                           uint4 (&r)[kWalk], bool &lost, bool &cand, int *s_n, int *s_job,
+                                           bool &lost, bool &cand, int *s_n, int *s_job,
                                            unsigned long long *s_word, const uint32_t *s_held,
                                            uint32_t *held_next)
 {
+    constexpr int SW = HELD ? kSweepHeld : kSweep;
     lost = false;
     cand = false;
+    // the first chunks, for every lane that is open now
+    const bool open_now = st.w == 0 && propose && st.x < list_end;
+    int e0 = open_now ? st.x : 0x7fffffff;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) e0 = min(e0, __shfl_xor(e0, d, kWave));
+    e0 = __builtin_amdgcn_readfirstlane(e0);
+    bool ahead = e0 != 0x7fffffff;                 // rr holds the chunks from c0 on
+    int c0 = ahead ? list_begin + ((e0 - list_begin) & ~(kWave - 1)) : 0;
+    uint4 rr[SW];
+    if (ahead) {
+#pragma unroll
+        for (int k = 0; k < SW; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
+    }
     if (st.w == 0 && st.y >= 0) {
         if (claim[st.y] == claim_of(round - 1, g)) {               // won: final
             st.w = 1;
@@ -368,95 +390,74 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
     unsigned long long cand_word = 0;      // the candidate job's claim word as the walk saw it
     const bool walking = st.w == 0 && propose;
     int e = st.x, found = -1, found_j = -1, found_a = -1;
-    bool by_bitmap = false;                // found while walking together with HELD: the claim word is still to fetch
-    constexpr int SW = HELD ? kSweepHeld : kSweep;
-    if (walking) {
-        // own walk: every lane from its own pointer
-        for (int trip = 0; e < list_end; ++trip) {
-            unsigned long long c[kWalk];
-#pragma unroll
-            for (int t = 0; t < kWalk; ++t) {
-                const bool covers = e + t < list_end && lane >= int(r[t].z & 255u) && lane < int(r[t].z >> 8);
-                // a huge stamp of an earlier round: "held"; with HELD the bitmap spares the fetch for a held job
-                c[t] = (covers && !(HELD && held_bit(s_held, r[t].x))) ? claim[r[t].x] : ~0ull;
-                if (!covers) r[t].z = 0;
-            }
-#pragma unroll
-            for (int t = 0; t < kWalk; ++t) {
-                const uint32_t stamp = uint32_t(c[t] >> 32);
-                const bool free_job = r[t].z != 0 && (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu));
-                if (found < 0 && free_job) { found = e + t; found_j = int(r[t].x); found_a = int(r[t].y); cand_word = c[t]; }
-            }
-            e += kWalk;
-            if (found >= 0 || e >= list_end || trip + 1 == kOwnTrips) break;
-#pragma unroll
-            for (int t = 0; t < kWalk; ++t) r[t] = rec[min(e + t, list_end - 1)];
-        }
-    }
-    // Lanes that are still looking walk on together: per round trip the wave
-    // reads SW chunks of 64 records (and their jobs' claim words, or with HELD
-    // the bitmap's answer), starting
-    // at the chunk of its lowest pointer still looking, so a record is read once
-    // per round; every lane whose pointer lies in that span takes the first free
-    // record at or after its pointer that covers the lane, or moves on past the span.
-    {
-        bool looking = walking && found < 0 && e < list_end;
-        for (;;) {
-            if (!__ballot(looking)) break;
-            int e0 = looking ? e : 0x7fffffff;              // the wave's lowest pointer still looking
+    bool by_bitmap = false;                // found with HELD: the claim word is still to fetch
+    bool looking = walking && e < list_end;
+    for (;;) {
+        const unsigned long long need = __ballot(looking);
+        if (!need) break;
+        if (!ahead) {
+            e0 = looking ? e : 0x7fffffff;                  // the wave's lowest pointer still looking
 #pragma unroll
             for (int d = 1; d < kWave; d <<= 1) e0 = min(e0, __shfl_xor(e0, d, kWave));
             e0 = __builtin_amdgcn_readfirstlane(e0);
-            const int c0 = list_begin + ((e0 - list_begin) & ~(kWave - 1));
-            uint4 rr[SW];
-            unsigned long long cw[SW];
+            c0 = list_begin + ((e0 - list_begin) & ~(kWave - 1));
 #pragma unroll
             for (int k = 0; k < SW; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
+        }
+        ahead = false;
+        // claim words only of records that cover some lane still looking
+        const int all_lo = __ffsll((long long)need) - 1, all_hi = 63 - __clzll((long long)need);
+        unsigned long long cw[SW];
 #pragma unroll
-            for (int k = 0; k < SW; ++k) {
-                if (HELD) cw[k] = held_bit(s_held, rr[k].x) ? ~0ull : 0ull;
-                else cw[k] = claim[rr[k].x];
+        for (int k = 0; k < SW; ++k) {
+            if (HELD) {
+                cw[k] = held_bit(s_held, rr[k].x) ? ~0ull : 0ull;
+            } else {
+                const bool worth = int(rr[k].z & 255u) <= all_hi && int(rr[k].z >> 8) > all_lo;
+                cw[k] = worth ? claim[rr[k].x] : ~0ull;
             }
-            const bool here = looking && e < c0 + SW * kWave;
-            int hit = -1, hj = 0, ha = 0;
-            unsigned int hw_lo = 0, hw_hi = 0;
+        }
+        const bool here = looking && e < c0 + SW * kWave;
+        int hit = -1, hj = 0, ha = 0;
+        unsigned int hw_lo = 0, hw_hi = 0;
 #pragma unroll
-            for (int k = 0; k < SW; ++k) {
-                // records worth a look: free, and covering some lane that still needs one
-                const unsigned long long need = __ballot(here && hit < 0);
-                const int need_lo = need ? __ffsll((long long)need) - 1 : 0;
-                const int need_hi = need ? 63 - __clzll((long long)need) : -1;
-                const uint32_t stamp = uint32_t(cw[k] >> 32);
-                const bool free_rec = c0 + k * kWave + lane < list_end &&
-                                      (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu)) &&
-                                      int(rr[k].z & 255u) <= need_hi && int(rr[k].z >> 8) > need_lo;
-                unsigned long long fm = __ballot(free_rec);
-                int hk = -1;
-                while (fm) {
-                    const int t = __ffsll((long long)fm) - 1;
-                    fm &= fm - 1;
-                    const unsigned int z = __builtin_amdgcn_readlane(rr[k].z, t);
-                    const bool h = here && hit < 0 && hk < 0 && c0 + k * kWave + t >= e && lane >= int(z & 255u) &&
-                                   lane < int(z >> 8);
-                    hk = h ? t : hk;
-                    if (!__any(here && hit < 0 && hk < 0)) break;
-                }
-                const int src = hk >= 0 ? hk : lane;
-                const int sj = __shfl(int(rr[k].x), src, kWave), sa = __shfl(int(rr[k].y), src, kWave);
-                const unsigned int s_lo = __shfl(int(uint32_t(cw[k])), src, kWave);
-                const unsigned int s_hi = __shfl(int(uint32_t(cw[k] >> 32)), src, kWave);
-                if (hk >= 0) { hit = k * kWave + hk; hj = sj; ha = sa; hw_lo = s_lo; hw_hi = s_hi; }
+        for (int k = 0; k < SW; ++k) {
+            // records worth a look: free, and covering some lane that still needs one
+            const unsigned long long still = __ballot(here && hit < 0);
+            const int need_lo = still ? __ffsll((long long)still) - 1 : 0;
+            const int need_hi = still ? 63 - __clzll((long long)still) : -1;
+            const uint32_t stamp = uint32_t(cw[k] >> 32);
+            const bool free_rec = c0 + k * kWave + lane < list_end &&
+                                  (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu)) &&
+                                  int(rr[k].z & 255u) <= need_hi && int(rr[k].z >> 8) > need_lo;
+            unsigned long long fm = __ballot(free_rec);
+            if (HELD && !fm) continue;          // most chunks of the early rounds: every record held
+            int hk = -1;
+            while (fm) {
+                const int t = __ffsll((long long)fm) - 1;
+                fm &= fm - 1;
+                const unsigned int z = __builtin_amdgcn_readlane(rr[k].z, t);
+                const bool h = here && hit < 0 && hk < 0 && c0 + k * kWave + t >= e && lane >= int(z & 255u) &&
+                               lane < int(z >> 8);
+                hk = h ? t : hk;
+                if (!__any(here && hit < 0 && hk < 0)) break;
             }
-            if (here) {
-                if (hit >= 0) {
-                    found = c0 + hit; found_j = hj; found_a = ha;
-                    cand_word = (static_cast<unsigned long long>(hw_hi) << 32) | hw_lo;
-                    by_bitmap = HELD;
-                    looking = false;
-                } else {
-                    e = c0 + SW * kWave;
-                    looking = e < list_end;
-                }
+            if (HELD && !__ballot(hk >= 0)) continue;   // the free records lay before every pointer
+            const int src = hk >= 0 ? hk : lane;
+            const int sj = __shfl(int(rr[k].x), src, kWave), sa = __shfl(int(rr[k].y), src, kWave);
+            const unsigned int s_lo = __shfl(int(uint32_t(cw[k])), src, kWave);
+            const unsigned int s_hi = __shfl(int(uint32_t(cw[k] >> 32)), src, kWave);
+            if (hk >= 0) { hit = k * kWave + hk; hj = sj; ha = sa; hw_lo = s_lo; hw_hi = s_hi; }
+        }
+        if (here) {
+            if (hit >= 0) {
+                found = c0 + hit; found_j = hj; found_a = ha;
+                cand_word = (static_cast<unsigned long long>(hw_hi) << 32) | hw_lo;
+                by_bitmap = HELD;
+                looking = false;
+            } else {
+                e = c0 + SW * kWave;
+                looking = e < list_end;
             }
         }
     }
@@ -507,9 +508,12 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
 // and the block sends one atomicMax per job.  A round leaves two flags: somebody
 // lost (round k-1), somebody selected (round k); the host only asks those two
 // questions.
+// n_lb, the number of list blocks, comes as an argument (the host has read it
+// back to size its launches): the state and the block's list bounds are all a
+// wave has to wait for before it can ask for its records and its claim word.
 template <bool HELD>
 __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
-    int round, int propose, int lb_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
+    int round, int propose, int n_lb, const int32_t *__restrict__ lb_begin,
     const int32_t *__restrict__ lb_end, const int32_t *__restrict__ list_off,
     const int32_t *__restrict__ gap_order, const uint4 *__restrict__ rec, unsigned long long *claim,
     int4 *state, int32_t *cnt_lost, int32_t *cnt_cand, int held_words, uint32_t *held)
@@ -526,7 +530,12 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     // that its load needs none of the block tables and travels together with them.
     const int slot = u * kWave + lane;
     int4 raw = make_int4(0, -1, -1, 2);
-    if (round > 1 && u < lb_cap) raw = state[slot];
+    int list_begin = 0, list_end = 0;
+    if (u < n_lb) {
+        if (round > 1) raw = state[slot];
+        list_begin = list_off[u];
+        list_end = list_off[u + 1];
+    }
     if (HELD) {
         // the bitmap travels together with the state; held_words is a multiple of 4 and at most
         // kHeldMaxWords, and the two bitmaps lie back to back
@@ -536,8 +545,7 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     }
     if (threadIdx.x == 0) s_n = 0;
     __syncthreads();
-    if (u < plan[kPlanListBlocks]) {
-        const int list_begin = list_off[u], list_end = list_off[u + 1];
+    if (u < n_lb) {
         if (round == 1) {
             const int b0 = lb_begin[u];
             const bool valid = lane < lb_end[u] - b0;
@@ -545,14 +553,9 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
         }
         const int g = raw.w >> 2;
         int4 st = make_int4(raw.x, raw.y, raw.z, raw.w & 3);
-        uint4 r[kWalk];
-        if (st.w == 0 && propose != 0) {
-#pragma unroll
-            for (int t = 0; t < kWalk; ++t) r[t] = rec[max(min(st.x + t, list_end - 1), 0)];
-        }
         const int4 before = st;
         bool lost, cand;
-        grant_step<HELD>(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, r, lost, cand, &s_n, s_job,
+        grant_step<HELD>(round, propose != 0, lane, g, list_begin, list_end, rec, claim, st, lost, cand, &s_n, s_job,
                          s_word, s_held, held_next);
         if (st.x != before.x || st.w != before.w || round == 1) state[slot] = make_int4(st.x, st.y, st.z, st.w | (g << 2));
         if (__ballot(lost) && lane == 0) cnt_lost[round - 1] = 1;

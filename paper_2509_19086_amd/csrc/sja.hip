@@ -360,12 +360,12 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     }
     auto launch_round = [&](int64_t k, int propose) {
         if (use_held && k <= kHeldRounds)
-            hipLaunchKernelGGL(k_grant_round<true>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, lb_bound,
-                               plan, lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
+            hipLaunchKernelGGL(k_grant_round<true>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, n_subs,
+                               lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
                                held_words, held);
         else
-            hipLaunchKernelGGL(k_grant_round<false>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, lb_bound,
-                               plan, lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
+            hipLaunchKernelGGL(k_grant_round<false>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, n_subs,
+                               lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
                                0, static_cast<uint32_t *>(nullptr));
         return hipGetLastError();
     };
