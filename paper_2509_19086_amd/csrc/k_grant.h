@@ -367,10 +367,7 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
     cand = false;
     // the first chunks, for every lane that is open now
     const bool open_now = st.w == 0 && propose && st.x < list_end;
-    int e0 = open_now ? st.x : 0x7fffffff;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) e0 = min(e0, __shfl_xor(e0, d, kWave));
-    e0 = __builtin_amdgcn_readfirstlane(e0);
+    int e0 = wave_min_dpp(open_now ? st.x : 0x7fffffff);
     bool ahead = e0 != 0x7fffffff;                 // rr holds the chunks from c0 on
     int c0 = ahead ? list_begin + ((e0 - list_begin) & ~(kWave - 1)) : 0;
     uint4 rr[SW];
@@ -396,10 +393,7 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
         const unsigned long long need = __ballot(looking);
         if (!need) break;
         if (!ahead) {
-            e0 = looking ? e : 0x7fffffff;                  // the wave's lowest pointer still looking
-#pragma unroll
-            for (int d = 1; d < kWave; d <<= 1) e0 = min(e0, __shfl_xor(e0, d, kWave));
-            e0 = __builtin_amdgcn_readfirstlane(e0);
+            e0 = wave_min_dpp(looking ? e : 0x7fffffff);    // the wave's lowest pointer still looking
             c0 = list_begin + ((e0 - list_begin) & ~(kWave - 1));
 #pragma unroll
             for (int k = 0; k < SW; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
@@ -408,14 +402,19 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
         // claim words only of records that cover some lane still looking
         const int all_lo = __ffsll((long long)need) - 1, all_hi = 63 - __clzll((long long)need);
         unsigned long long cw[SW];
+        if (HELD) {
 #pragma unroll
-        for (int k = 0; k < SW; ++k) {
-            if (HELD) {
-                cw[k] = held_bit(s_held, rr[k].x) ? ~0ull : 0ull;
-            } else {
-                const bool worth = int(rr[k].z & 255u) <= all_hi && int(rr[k].z >> 8) > all_lo;
-                cw[k] = worth ? claim[rr[k].x] : ~0ull;
-            }
+            for (int k = 0; k < SW; ++k) cw[k] = held_bit(s_held, rr[k].x) ? ~0ull : 0ull;
+        } else {
+            // every lane loads (the others word 0, one request per wave) so that the loads of all
+            // chunks are issued back to back: a load that may be skipped makes the next one wait for it
+            bool worth[SW];
+#pragma unroll
+            for (int k = 0; k < SW; ++k) worth[k] = int(rr[k].z & 255u) <= all_hi && int(rr[k].z >> 8) > all_lo;
+#pragma unroll
+            for (int k = 0; k < SW; ++k) cw[k] = claim[worth[k] ? rr[k].x : 0u];
+#pragma unroll
+            for (int k = 0; k < SW; ++k) cw[k] = worth[k] ? cw[k] : ~0ull;
         }
         const bool here = looking && e < c0 + SW * kWave;
         int hit = -1, hj = 0, ha = 0;
@@ -482,9 +481,7 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
         const int leader = __ffsll((long long)todo) - 1;
         const int job = __builtin_amdgcn_readlane(cand_job, leader);
         const bool mine = cand && cand_job == job;
-        unsigned int best = mine ? 0xffffffffu - uint32_t(g) : 0u;       // larger = lower gap index
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) best = max(best, (unsigned int)__shfl_xor(int(best), d, kWave));
+        const unsigned int best = 0xffffffffu - uint32_t(wave_min_dpp(mine ? g : 0x7fffffff));   // larger = lower gap index
         if (lane == leader) {
             const unsigned long long word = (static_cast<unsigned long long>(round) << 32) | best;
             if (cand_word < word) {

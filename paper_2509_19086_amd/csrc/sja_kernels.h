@@ -52,6 +52,19 @@ __device__ __forceinline__ int wave_scan_max_dpp(int v)
     return v;
 }
 
+// The smallest value over all 64 lanes (which must all be active), the same in
+// every lane: the scan's last lane holds it.
+__device__ __forceinline__ int wave_min_dpp(int v)
+{
+    v = min(v, dpp_from<kDppRowShr1, 0xf>(INT32_MAX, v));
+    v = min(v, dpp_from<kDppRowShr2, 0xf>(INT32_MAX, v));
+    v = min(v, dpp_from<kDppRowShr4, 0xf>(INT32_MAX, v));
+    v = min(v, dpp_from<kDppRowShr8, 0xf>(INT32_MAX, v));
+    v = min(v, dpp_from<kDppRowBcast15, 0xa>(INT32_MAX, v));
+    v = min(v, dpp_from<kDppRowBcast31, 0xc>(INT32_MAX, v));
+    return __builtin_amdgcn_readlane(v, kWave - 1);
+}
+
 // Inclusive wave scan of (sum, max, max) triples.
 __device__ __forceinline__ void wave_scan_add_max_max(int &s, int &m, int &l, int lane)
 {
