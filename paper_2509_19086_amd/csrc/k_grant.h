@@ -337,6 +337,7 @@ constexpr int kSweep = 2;        // chunks of 64 records the wave reads per trip
 constexpr int kSweepHeld = 8;    // the same with the held bitmap: no claim words to fetch, so a wider trip costs little
 constexpr int kRoundBlock = 256; // threads per block of the round kernel
 constexpr int kBlockClaims = 256; // claims a block merges in LDS per round
+constexpr int kClaimTurns = 4;    // jobs whose claims a wave merges over its lanes before the rest are sent singly
 
 constexpr int kHeldMaxWords = 4096;   // words of the held-job bitmap a block keeps in LDS (jobs / 32)
 constexpr int kHeldRounds = 512;      // rounds that keep and read the bitmap
@@ -477,7 +478,19 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
     // block merges them before anything is sent (a claim that finds the list
     // full is sent at once).
     unsigned long long todo = __ballot(cand);
-    while (todo) {
+    for (int turn = 0; todo; ++turn) {
+        if (turn == kClaimTurns) {
+            // a wave of the early rounds, whose lanes name dozens of different jobs: one turn of
+            // this loop per job costs more than the claims it merges, so the rest go out as they are
+            if ((todo >> lane) & 1ull) {
+                const unsigned long long word = claim_of(round, g);
+                if (cand_word < word) {
+                    atomicMax(&claim[cand_job], word);
+                    if (HELD) atomicOr(&held_next[uint32_t(cand_job) >> 5], 1u << (uint32_t(cand_job) & 31u));
+                }
+            }
+            break;
+        }
         const int leader = __ffsll((long long)todo) - 1;
         const int job = __builtin_amdgcn_readlane(cand_job, leader);
         const bool mine = cand && cand_job == job;
