@@ -439,15 +439,15 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
                 const unsigned int z = __builtin_amdgcn_readlane(rr[k].z, t);
                 const bool h = here && hit < 0 && hk < 0 && c0 + k * kWave + t >= e && lane >= int(z & 255u) &&
                                lane < int(z >> 8);
-                hk = h ? t : hk;
-                if (!__any(here && hit < 0 && hk < 0)) break;
+                if (__any(h)) {
+                    // record t's job, atom and claim word straight from lane t's registers
+                    const int tj = __builtin_amdgcn_readlane(int(rr[k].x), t), ta = __builtin_amdgcn_readlane(int(rr[k].y), t);
+                    const unsigned int t_lo = __builtin_amdgcn_readlane(int(uint32_t(cw[k])), t);
+                    const unsigned int t_hi = __builtin_amdgcn_readlane(int(uint32_t(cw[k] >> 32)), t);
+                    if (h) { hk = t; hit = k * kWave + t; hj = tj; ha = ta; hw_lo = t_lo; hw_hi = t_hi; }
+                }
+                if (!__any(here && hit < 0)) break;
             }
-            if (HELD && !__ballot(hk >= 0)) continue;   // the free records lay before every pointer
-            const int src = hk >= 0 ? hk : lane;
-            const int sj = __shfl(int(rr[k].x), src, kWave), sa = __shfl(int(rr[k].y), src, kWave);
-            const unsigned int s_lo = __shfl(int(uint32_t(cw[k])), src, kWave);
-            const unsigned int s_hi = __shfl(int(uint32_t(cw[k] >> 32)), src, kWave);
-            if (hk >= 0) { hit = k * kWave + hk; hj = sj; ha = sa; hw_lo = s_lo; hw_hi = s_hi; }
         }
         if (here) {
             if (hit >= 0) {
