@@ -65,6 +65,19 @@ __device__ __forceinline__ int wave_min_dpp(int v)
     return __builtin_amdgcn_readlane(v, kWave - 1);
 }
 
+// Lane `src`'s value, `src` the same in every lane: read from the registers
+// (v_readlane), not sent through the LDS crossbar as a shuffle is.
+__device__ __forceinline__ int lane_value(int v, int src)
+{
+    return __builtin_amdgcn_readlane(v, src);
+}
+__device__ __forceinline__ long long lane_value(long long v, int src)
+{
+    const unsigned int lo = uint32_t(__builtin_amdgcn_readlane(int(uint32_t((unsigned long long)v)), src));
+    const unsigned int hi = uint32_t(__builtin_amdgcn_readlane(int(uint32_t((unsigned long long)v >> 32)), src));
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
+
 // Inclusive wave scan of (sum, max, max) triples.
 __device__ __forceinline__ void wave_scan_add_max_max(int &s, int &m, int &l, int lane)
 {
@@ -257,7 +270,7 @@ __device__ __forceinline__ void prepare_job(
             wave_scan_add64(ar, lane);
             ar += carry_area;
             if (valid) pre_area[base + k] = ar;
-            carry_area = __shfl(ar, kWave - 1, kWave);
+            carry_area = lane_value(ar, kWave - 1);
         }
         wave_scan_add_max_max(s, m, l, lane);
         s += carry_sum;
@@ -275,15 +288,15 @@ __device__ __forceinline__ void prepare_job(
                 wave_scan_max(q, lane);
                 q = max(q, carry_pow);
                 keep = keep && q <= lim.power_cap;
-                carry_pow = __shfl(q, kWave - 1, kWave);
+                carry_pow = lane_value(q, kWave - 1);
             }
             flag = keep;
         }
         const unsigned long long mask = __ballot(flag);
         if (count == 0 && mask) {
             const int src = __ffsll((long long)mask) - 1;
-            first_d = __shfl(s, src, kWave);
-            first_p = __shfl(m, src, kWave);
+            first_d = lane_value(s, src);
+            first_p = lane_value(m, src);
         }
         if (flag) {
             const int idx = count + __popcll(mask & lanes_below(lane));
@@ -292,9 +305,9 @@ __device__ __forceinline__ void prepare_job(
             if (atom_area) atom_area[base + idx] = ar;
         }
         count += __popcll(mask);
-        carry_sum = __shfl(s, kWave - 1, kWave);
-        carry_peak = __shfl(m, kWave - 1, kWave);
-        carry_last = __shfl(l, kWave - 1, kWave);
+        carry_sum = lane_value(s, kWave - 1);
+        carry_peak = lane_value(m, kWave - 1);
+        carry_last = lane_value(l, kWave - 1);
     }
     if (lane == 0) {
         n_atoms[j] = count;
@@ -366,7 +379,7 @@ __device__ __forceinline__ void prepare_job_wide(
             l[i] = max(l[i], l[i - 1]);
         }
         int ts = wave_scan_add(s[PER - 1]), tm = wave_scan_max_dpp(m[PER - 1]), tl = wave_scan_max_dpp(l[PER - 1]);
-        const int tot_s = __shfl(ts, kWave - 1, kWave), tot_m = __shfl(tm, kWave - 1, kWave), tot_l = __shfl(tl, kWave - 1, kWave);
+        const int tot_s = lane_value(ts, kWave - 1), tot_m = lane_value(tm, kWave - 1), tot_l = lane_value(tl, kWave - 1);
         // exclusive over lanes = inclusive of the lane before
         int es = __shfl_up(ts, 1, kWave), em = __shfl_up(tm, 1, kWave), el = __shfl_up(tl, 1, kWave);
         if (lane == 0) { es = 0; em = INT32_MIN; el = -1; }
@@ -404,7 +417,7 @@ __device__ __forceinline__ void prepare_job_wide(
         }
         // atoms: the flagged boundaries, compacted in order
         const int incl = wave_scan_add(nflag);
-        const int total = __shfl(incl, kWave - 1, kWave);
+        const int total = lane_value(incl, kWave - 1);
         int idx = count + incl - nflag;
         if (count == 0 && total > 0) {
             // the first atom of the job: the lowest lane with a flag, its first flagged value
@@ -415,8 +428,8 @@ __device__ __forceinline__ void prepare_job_wide(
 #pragma unroll
             for (int i = 0; i < PER; ++i)
                 if (!got && flag[i]) { fd = s[i]; fp = m[i]; got = true; }
-            first_d = __shfl(fd, src, kWave);
-            first_p = __shfl(fp, src, kWave);
+            first_d = lane_value(fd, src);
+            first_p = lane_value(fp, src);
         }
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
