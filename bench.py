@@ -53,8 +53,8 @@ def secondary_rates(wl, n_atoms_total, call_ms, rounds):
 FIT_TRAFFIC = {
     "workload": ("stress", 0),
     "sources_sha256": "14ee7b0dc06ab05fd6a4a4f7c25c8ad1e6d0bdd284448aca611afc22c17fcb26",
-    "fetch_kib": 51527.8, "fetch_scale": 2.0,
-    "write_kib": 8391376.8, "write_scale": 1.0,
+    "fetch_kib": 51541.3, "fetch_scale": 2.0,
+    "write_kib": 8391247.3, "write_scale": 1.0,
 }
 
 
