@@ -573,6 +573,33 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     }
     __syncthreads();
     const int n = min(s_n, kBlockClaims);
+    if (n <= kWave) {
+        // the usual case, a handful of claims: one lane of the first wave per claim, the others'
+        // claims read from their lanes (a loop over the list in LDS pays two dependent LDS trips
+        // per entry, at the very end of every round)
+        if (threadIdx.x < kWave) {
+            const bool valid = lane < n;
+            const int job = valid ? s_job[lane] : -1;
+            const unsigned long long word = valid ? s_word[lane] : 0ull;
+            unsigned long long best = word;
+            bool first = valid;
+            for (int k = 0; k < n; ++k) {
+                const int jk = __builtin_amdgcn_readlane(job, k);
+                const unsigned long long wk =
+                    (static_cast<unsigned long long>(uint32_t(__builtin_amdgcn_readlane(int(uint32_t(word >> 32)), k))) << 32) |
+                    uint32_t(__builtin_amdgcn_readlane(int(uint32_t(word)), k));
+                if (jk == job) {
+                    best = max(best, wk);
+                    first = first && k >= lane;
+                }
+            }
+            if (first) {
+                atomicMax(&claim[job], best);
+                if (HELD) atomicOr(&held_next[uint32_t(job) >> 5], 1u << (uint32_t(job) & 31u));
+            }
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < n; i += kRoundBlock) {
         const int job = s_job[i];
         unsigned long long word = s_word[i];
