@@ -334,7 +334,7 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // first chunks are asked for before the wave knows who won round k-1 (nearly
 // every open lane lost), so they travel beside that check's claim word.
 constexpr int kSweep = 2;        // chunks of 64 records the wave reads per trip (3: 1.7 ms slower per Stress resolve, 4: 3.7 ms)
-constexpr int kSweepHeld = 8;    // the same with the held bitmap: no claim words to fetch, so a wider trip costs little
+constexpr int kSweepHeld = 8;  // the same with the held bitmap: no claim words to fetch, so a wider trip costs little
 constexpr int kRoundBlock = 256; // threads per block of the round kernel
 constexpr int kBlockClaims = 256; // claims a block merges in LDS per round
 constexpr int kClaimTurns = 4;    // jobs whose claims a wave merges over its lanes before the rest are sent singly
@@ -390,16 +390,32 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
     int e = st.x, found = -1, found_j = -1, found_a = -1;
     bool by_bitmap = false;                // found with HELD: the claim word is still to fetch
     bool looking = walking && e < list_end;
+    // HELD: the chunks behind the ones being looked at are asked for before the look starts (a wave
+    // whose lanes' pointers lie thousands of records apart takes window after window, and a lane
+    // that finds nothing goes on exactly there), so their trip overlaps the look.  Always issued,
+    // at clamped addresses: a load that may be skipped makes every later wait a wait for all.
+    uint4 rn[HELD ? SW : 1];
+    int c_next = -1;
     for (;;) {
         const unsigned long long need = __ballot(looking);
         if (!need) break;
         if (!ahead) {
             e0 = wave_min_dpp(looking ? e : 0x7fffffff);    // the wave's lowest pointer still looking
             c0 = list_begin + ((e0 - list_begin) & ~(kWave - 1));
+            if (HELD && c0 == c_next) {
 #pragma unroll
-            for (int k = 0; k < SW; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
+                for (int k = 0; k < SW; ++k) rr[k] = rn[k];
+            } else {
+#pragma unroll
+                for (int k = 0; k < SW; ++k) rr[k] = rec[min(c0 + k * kWave + lane, list_end - 1)];
+            }
         }
         ahead = false;
+        if (HELD) {
+            c_next = c0 + SW * kWave;
+#pragma unroll
+            for (int k = 0; k < SW; ++k) rn[k] = rec[min(c_next + k * kWave + lane, list_end - 1)];
+        }
         // claim words only of records that cover some lane still looking
         const int all_lo = __ffsll((long long)need) - 1, all_hi = 63 - __clzll((long long)need);
         unsigned long long cw[SW];
@@ -422,22 +438,26 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
         unsigned int hw_lo = 0, hw_hi = 0;
 #pragma unroll
         for (int k = 0; k < SW; ++k) {
-            // records worth a look: free, and covering some lane that still needs one
-            const unsigned long long still = __ballot(here && hit < 0);
-            const int need_lo = still ? __ffsll((long long)still) - 1 : 0;
-            const int need_hi = still ? 63 - __clzll((long long)still) : -1;
+            // lanes this chunk can serve: still looking, and standing before its end (the pointers of
+            // a wave of the early rounds lie thousands of records apart: most lanes `here` only
+            // start in a later chunk of the window, and nothing in this one is for them)
+            const bool elig = here && hit < 0 && e < c0 + (k + 1) * kWave;
+            const unsigned long long still = __ballot(elig);
+            if (!still) continue;
+            // records worth a look: free, and covering some lane that can take one here
+            const int need_lo = __ffsll((long long)still) - 1;
+            const int need_hi = 63 - __clzll((long long)still);
             const uint32_t stamp = uint32_t(cw[k] >> 32);
             const bool free_rec = c0 + k * kWave + lane < list_end &&
                                   (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu)) &&
                                   int(rr[k].z & 255u) <= need_hi && int(rr[k].z >> 8) > need_lo;
             unsigned long long fm = __ballot(free_rec);
-            if (HELD && !fm) continue;          // most chunks of the early rounds: every record held
             int hk = -1;
             while (fm) {
                 const int t = __ffsll((long long)fm) - 1;
                 fm &= fm - 1;
                 const unsigned int z = __builtin_amdgcn_readlane(rr[k].z, t);
-                const bool h = here && hit < 0 && hk < 0 && c0 + k * kWave + t >= e && lane >= int(z & 255u) &&
+                const bool h = elig && hk < 0 && c0 + k * kWave + t >= e && lane >= int(z & 255u) &&
                                lane < int(z >> 8);
                 if (__any(h)) {
                     // record t's job, atom and claim word straight from lane t's registers
@@ -446,7 +466,7 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
                     const unsigned int t_hi = __builtin_amdgcn_readlane(int(uint32_t(cw[k] >> 32)), t);
                     if (h) { hk = t; hit = k * kWave + t; hj = tj; ha = ta; hw_lo = t_lo; hw_hi = t_hi; }
                 }
-                if (!__any(here && hit < 0)) break;
+                if (!__any(elig && hk < 0)) break;
             }
         }
         if (here) {
@@ -542,7 +562,7 @@ __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
     int4 raw = make_int4(0, -1, -1, 2);
     int list_begin = 0, list_end = 0;
     if (u < n_lb) {
-        if (round > 1) raw = state[slot];
+        raw = state[slot];               // round 1 reads what an earlier resolve left and replaces it below
         list_begin = list_off[u];
         list_end = list_off[u + 1];
     }
