@@ -251,7 +251,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(hipGetLastError(), "list block launch");
     // where every sub-block starts in every job's atom list (the fit only keeps this per chunk)
     int32_t *sub_tab = ws_ptr<int32_t>(ctx, L.sub_tab);
-    const int starts_jobs = (256 / kWave) * kStartsJobs;
+    const int starts_jobs = kStartsJobs;
     hipLaunchKernelGGL(k_fit_starts, dim3((J + starts_jobs - 1) / starts_jobs), dim3(256), 0, st, J, int(kPlanSubBlocks), plan,
                        ws_ptr<int32_t>(ctx, L.class_begin), sub_begin, sub_class, gap_w, ws_ptr<int32_t>(ctx, L.gap_c),
                        ctx->seg_off, atom_dp, ws_ptr<int32_t>(ctx, L.n_atoms), sub_tab, static_cast<int32_t *>(nullptr));
@@ -445,7 +445,7 @@ int enqueue_gap_plan(sja_ctx *ctx, hipStream_t st, const Layout &L, int32_t n_ga
                            ws_ptr<int32_t>(ctx, L.sub_end), ws_ptr<int32_t>(ctx, L.sub_class),
                            ws_ptr<int32_t>(ctx, L.gap_cls), ws_ptr<int32_t>(ctx, L.gap_run_end));
         SJA_HIP(hipGetLastError(), "k_gap_plan launch");
-        const int jobs_per_block = (256 / kWave) * kStartsJobs;
+        const int jobs_per_block = kStartsJobs;
         hipLaunchKernelGGL(k_fit_starts, dim3((J + jobs_per_block - 1) / jobs_per_block), b256, 0, st, J, int(kPlanChunks),
                            plan, ws_ptr<int32_t>(ctx, L.class_begin), ws_ptr<int32_t>(ctx, L.chunk_begin),
                            ws_ptr<int32_t>(ctx, L.chunk_class), gw, gcap, ctx->seg_off, ws_ptr<int2>(ctx, L.atom_dp),
