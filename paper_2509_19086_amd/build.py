@@ -25,8 +25,14 @@ def hipcc() -> str:
 
 
 def command() -> list:
+    # amdgpu-kernarg-preload-count: the first 16 dwords of a kernel's arguments arrive in scalar
+    # registers with the wave instead of being loaded by it (gfx940 and later; the compiler keeps
+    # a loading prologue for firmware that does not preload).  A resolve round is one short kernel
+    # whose first memory trip otherwise waits for that load; the round kernel's argument order
+    # puts what that trip needs first.
     return [hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-mllvm", "-amdgpu-kernarg-preload-count=16",
             "-Wall", "-Wno-unused-function",
             "-o", LIB] + SOURCES
 

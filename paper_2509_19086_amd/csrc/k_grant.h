@@ -541,12 +541,14 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
 // n_lb, the number of list blocks, comes as an argument (the host has read it
 // back to size its launches): the state and the block's list bounds are all a
 // wave has to wait for before it can ask for its records and its claim word.
+// The arguments a wave needs first come first: the library is built so that
+// the leading 16 dwords of a kernel's arguments are in scalar registers when
+// the wave starts, and the state load does not wait for an argument load.
 template <bool HELD>
 __global__ __launch_bounds__(kRoundBlock) void k_grant_round(
-    int round, int propose, int n_lb, const int32_t *__restrict__ lb_begin,
-    const int32_t *__restrict__ lb_end, const int32_t *__restrict__ list_off,
-    const int32_t *__restrict__ gap_order, const uint4 *__restrict__ rec, unsigned long long *claim,
-    int4 *state, int32_t *cnt_lost, int32_t *cnt_cand, int held_words, uint32_t *held)
+    int4 *state, const int32_t *__restrict__ list_off, const uint4 *__restrict__ rec, unsigned long long *claim,
+    int round, int propose, int n_lb, int held_words, uint32_t *held, const int32_t *__restrict__ lb_begin,
+    const int32_t *__restrict__ lb_end, const int32_t *__restrict__ gap_order, int32_t *cnt_lost, int32_t *cnt_cand)
 {
     __shared__ int s_n;
     __shared__ int s_job[kBlockClaims];

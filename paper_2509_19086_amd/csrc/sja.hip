@@ -360,13 +360,11 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     }
     auto launch_round = [&](int64_t k, int propose) {
         if (use_held && k <= kHeldRounds)
-            hipLaunchKernelGGL(k_grant_round<true>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, n_subs,
-                               lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
-                               held_words, held);
+            hipLaunchKernelGGL(k_grant_round<true>, dim3(round_grid), dim3(kRoundBlock), 0, st, state, list_off, rec, claim, int(k), propose, n_subs,
+                               held_words, held, lb_begin, lb_end, gap_order, cnt_lost, cnt_cand);
         else
-            hipLaunchKernelGGL(k_grant_round<false>, dim3(round_grid), dim3(kRoundBlock), 0, st, int(k), propose, n_subs,
-                               lb_begin, lb_end, list_off, gap_order, rec, claim, state, cnt_lost, cnt_cand,
-                               0, static_cast<uint32_t *>(nullptr));
+            hipLaunchKernelGGL(k_grant_round<false>, dim3(round_grid), dim3(kRoundBlock), 0, st, state, list_off, rec, claim, int(k), propose, n_subs,
+                               0, static_cast<uint32_t *>(nullptr), lb_begin, lb_end, gap_order, cnt_lost, cnt_cand);
         return hipGetLastError();
     };
     std::vector<int32_t> h_lost, h_cand;
