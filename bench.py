@@ -52,9 +52,9 @@ def secondary_rates(wl, n_atoms_total, call_ms, rounds):
 # sources are hashed, and a different hash means the counters are stale.
 FIT_TRAFFIC = {
     "workload": ("stress", 0),
-    "sources_sha256": "14ee7b0dc06ab05fd6a4a4f7c25c8ad1e6d0bdd284448aca611afc22c17fcb26",
-    "fetch_kib": 51541.3, "fetch_scale": 2.0,
-    "write_kib": 8391247.3, "write_scale": 1.0,
+    "sources_sha256": "c8e03b40c653190bbaddc66b9dce349b1f4f729e9d9c9efb8aebfc76fe43d981",
+    "fetch_kib": 51523.7, "fetch_scale": 2.0,
+    "write_kib": 8391605.0, "write_scale": 1.0,
 }
 
 
