@@ -130,10 +130,10 @@ __global__ void k_rank_from_perm(const int32_t *n_ptr, const uint32_t *__restric
     }
 }
 
-// Number of entries of sorted w[0..len) that are < d.
-__device__ __forceinline__ int count_less(const int *w, int len, int d)
+// Number of entries of sorted w[0..len) that are < d, known to be at least `from`.
+__device__ __forceinline__ int count_less(const int *w, int len, int d, int from = 0)
 {
-    int lo = 0, hi = len;
+    int lo = from, hi = len;
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
         if (w[mid] < d) lo = mid + 1; else hi = mid;
@@ -210,17 +210,13 @@ __device__ __forceinline__ void list_visit(const int2 *__restrict__ dp, const in
                                            Sink &&sink)
 {
     const int a_begin = max(a_first - 1, 0);
-    int d_next = a_begin < n_cap ? dp[a_begin].x : 0;
-    for (int a = a_begin; a < n_cap; ++a) {
-        const int d_a = d_next;
-        const int lo = a < a_first ? 0 : count_less(s_w, len, d_a);
-        if (lo >= len) break;
-        int hi = len;
-        if (a + 1 < n_cap) {
-            d_next = dp[a + 1].x;
-            hi = count_less(s_w, len, d_next);
-        }
+    if (a_begin >= n_cap) return;
+    // an atom's range ends where the next one's begins: one search per atom
+    int lo = a_begin < a_first ? 0 : count_less(s_w, len, dp[a_begin].x);
+    for (int a = a_begin; a < n_cap && lo < len; ++a) {
+        const int hi = a + 1 < n_cap ? count_less(s_w, len, dp[a + 1].x, lo) : len;    // durations ascend
         if (hi > lo) sink(a, lo, hi);
+        lo = hi;
     }
 }
 
@@ -262,10 +258,10 @@ __global__ __launch_bounds__(256) void k_list_emit(
                 // the lanes of this wave that are at this point together
                 const unsigned long long peers = __ballot(true);
                 const int n_peers = __popcll(peers);
-                const int mine = __popcll(peers & lanes_below(lane));
+                const int mine = __builtin_amdgcn_mbcnt_hi(uint32_t(peers >> 32), __builtin_amdgcn_mbcnt_lo(uint32_t(peers), 0u));
                 int at = 0;
                 if (mine == 0) at = atomicAdd(&s_cursor, n_peers);
-                at = __shfl(at, __ffsll((long long)peers) - 1, kWave) + mine;
+                at = __builtin_amdgcn_readlane(at, __ffsll((long long)peers) - 1) + mine;
                 if (at < kEmitBuffer) {
                     s_buf[at] = key;
                 } else {
