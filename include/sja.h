@@ -440,11 +440,19 @@ int sja_store_reference(sja_ctx *ctx, void *stream, int32_t *cut);
  *                       ungranted: the rows of the cut matrix after sja_fit,
  *                       the pairs themselves (evaluated again, nothing stored)
  *                       after sja_fit_select.
+ *   SJA_RESOLVE_LISTS_LOOKUP  as SJA_RESOLVE_LISTS, but the job of every list
+ *                       record is looked up through the record's rank even
+ *                       where the list keys have room to carry it: the form
+ *                       the lists take by themselves for batches whose block,
+ *                       rank and job numbers do not fit one 64-bit key
+ *                       together; selectable so that it can be tested at any
+ *                       size.
  * SJA_ERR_SIZE for any other value.
  */
 typedef enum {
     SJA_RESOLVE_LISTS = 0,
-    SJA_RESOLVE_MATRIX = 1
+    SJA_RESOLVE_MATRIX = 1,
+    SJA_RESOLVE_LISTS_LOOKUP = 2
 } sja_resolve_mode;
 int sja_set_resolve_mode(sja_ctx *ctx, int mode);
 

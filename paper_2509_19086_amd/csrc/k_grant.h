@@ -221,7 +221,7 @@ __device__ __forceinline__ void list_visit(const int2 *__restrict__ dp, const in
 }
 
 __global__ __launch_bounds__(256) void k_list_emit(
-    int n_jobs, int rank_bits, int lb_cap, long long entry_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
+    int n_jobs, int rank_bits, int job_shift, int lb_cap, long long entry_cap, const int32_t *__restrict__ plan, const int32_t *__restrict__ lb_begin,
     const int32_t *__restrict__ lb_end, const int32_t *__restrict__ lb_sub, const int32_t *__restrict__ sub_class,
     const int32_t *__restrict__ gap_w, const int64_t *__restrict__ seg_off,
     const int2 *__restrict__ atom_dp, const int32_t *__restrict__ start_tab,
@@ -253,8 +253,10 @@ __global__ __launch_bounds__(256) void k_list_emit(
             // the table holds the count at the sub-block's first position; a later piece starts further on
             while (af < nc && dp[af].x <= s_w[0]) ++af;
             const int a0 = abase[j];
+            // the job rides above the sorted bits when there is room for it (job_shift >= 0)
+            const unsigned long long rider = job_shift >= 0 ? (unsigned long long)uint32_t(j) << job_shift : 0ull;
             list_visit(dp, s_w, len, af, nc, [&](int a, int lo, int hi) {
-                const unsigned long long key = ((head | rank[a0 + a]) << kEntryLaneBits) | (unsigned long long)((hi << 6) | lo);
+                const unsigned long long key = rider | ((head | rank[a0 + a]) << kEntryLaneBits) | (unsigned long long)((hi << 6) | lo);
                 // the lanes of this wave that are at this point together
                 const unsigned long long peers = __ballot(true);
                 const int n_peers = __popcll(peers);
@@ -299,16 +301,12 @@ __device__ __forceinline__ unsigned long long claim_of(int round, int g)
     return (static_cast<unsigned long long>(round) << 32) | (0xffffffffu - uint32_t(g));
 }
 
-// Sorted entries as 16-byte records (job, atom, lo | hi << 8, 0): one load per entry.
-__global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__restrict__ ekey, int rank_bits,
-                            const int2 *__restrict__ ranked, uint4 *__restrict__ rec)
+// Sorted entries as 16-byte records (job, rank, lo | hi << 8, 0): one load per entry.
+__global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__restrict__ ekey, KeyRecords out)
 {
     const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i >= *n_ptr) return;
-    const unsigned long long k = ekey[i];
-    const int2 ja = ranked[(k >> kEntryLaneBits) & ((1ull << rank_bits) - 1ull)];
-    const unsigned int lo = unsigned(k) & 63u, hi = unsigned(k >> 6) & 127u;
-    rec[i] = make_uint4(uint32_t(ja.x), uint32_t(ja.y), lo | (hi << 8), 0u);
+    out.rec[i] = key_record(out, ekey[i]);
 }
 
 // One round for one list block (one wave, one lane per gap position).  First
@@ -316,7 +314,7 @@ __global__ void k_list_pack(const int32_t *n_ptr, const unsigned long long *__re
 // claim word has won (the grant is final), otherwise it lost.  Then, if
 // `propose`, every lane that still needs a job walks on from its own pointer to
 // the first entry that covers it and whose job is not held, and claims it.
-// st = (pointer, candidate job, candidate atom, flag) with flag 0 = active,
+// st = (pointer, candidate job, rank of the candidate atom, flag) with flag 0 = active,
 // 1 = granted, 2 = no candidate left (in memory the flag shares its word with
 // the gap index).
 //
@@ -657,9 +655,11 @@ __global__ __launch_bounds__(1024) void k_count_open(int lb_cap, const int32_t *
 }
 
 // After the last round: the grants themselves.  A granted position still holds
-// its winning (job, atom) in its state.
+// its winning job and the rank of the winning atom in its state; `ranked` turns
+// the rank into the atom.
 __global__ void k_grant_finish(int lb_cap, PolicyDev pol, const int32_t *__restrict__ plan,
-                               const int4 *__restrict__ state, const int64_t *__restrict__ seg_off,
+                               const int4 *__restrict__ state, const int2 *__restrict__ ranked,
+                               const int64_t *__restrict__ seg_off,
                                const int2 *__restrict__ atom_dp, const int2 *__restrict__ atom_db,
                                const long long *__restrict__ atom_area,
                                const int32_t *__restrict__ wait, const uint8_t *__restrict__ sla_class,
@@ -671,13 +671,14 @@ __global__ void k_grant_finish(int lb_cap, PolicyDev pol, const int32_t *__restr
     const int4 st = state[slot];
     if ((st.w & 3) != 1) return;
     const int g = st.w >> 2, j = st.y;
+    const int atom = ranked[st.z].y;
     const int64_t base = seg_off[j];
-    const int2 v = atom_dp[base + st.z];
+    const int2 v = atom_dp[base + atom];
     unsigned long long mult, tier;
     job_policy(pol, wait, sla_class, j, mult, tier);
     grant_job[g] = j;
-    grant_cut[g] = atom_db[base + st.z].y;
-    const unsigned long long F = atom_area ? (unsigned long long)atom_area[base + st.z]
+    grant_cut[g] = atom_db[base + atom].y;
+    const unsigned long long F = atom_area ? (unsigned long long)atom_area[base + atom]
                                            : (unsigned long long)v.x * (unsigned long long)v.y;
     grant_score[g] = int64_t(F * mult);
     job_gap[j] = g;

@@ -114,7 +114,8 @@ __device__ __forceinline__ unsigned long long digit_peers(unsigned d, bool valid
 }
 
 __global__ __launch_bounds__(256) void k_keys_hist(const unsigned long long *__restrict__ keys,
-                                                   const int32_t *n_ptr, int shift, int32_t *hist, int n_tiles)
+                                                   const int32_t *n_ptr, int shift, unsigned digit_mask, int32_t *hist,
+                                                   int n_tiles)
 {
     __shared__ int s_h[256];
     const int64_t n = *n_ptr;
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(256) void k_keys_hist(const unsigned long long *__r
     for (int r = 0; r < kKeyTile / 256; ++r) {
         const int64_t i = base + r * 256 + tid;
         const bool valid = i < n;
-        const unsigned d = valid ? unsigned(keys[i] >> shift) & 255u : 0u;
+        const unsigned d = valid ? unsigned(keys[i] >> shift) & digit_mask : 0u;
         const unsigned long long peers = digit_peers(d, valid);
         if (valid && (peers & ((1ull << lane) - 1ull)) == 0) atomicAdd(&s_h[d], __popcll(peers));
     }
@@ -135,13 +136,22 @@ __global__ __launch_bounds__(256) void k_keys_hist(const unsigned long long *__r
 }
 
 // What the last pass over list entries writes instead of the keys themselves: 16-byte records
-// (job, atom, lo | hi << 8, 0), the (job, atom) looked up by the key's rank field, lo (6 bits) and
-// hi (7 bits) its lowest lane_bits bits.
+// (job, rank, lo | hi << 8, 0); rank is the key's rank field, lo (6 bits) and hi (7 bits) its
+// lowest lane_bits bits, and the job either rides in the key above job_shift (no pass sorts by
+// those bits) or, with job_shift < 0, is looked up through the rank (one gather per key).
 struct KeyRecords {
     const int2 *ranked;
     uint4 *rec;
-    int lane_bits, rank_bits;
+    int lane_bits, rank_bits, job_shift;
 };
+
+__device__ __forceinline__ uint4 key_record(const KeyRecords &out, unsigned long long v)
+{
+    const uint32_t rank = uint32_t((v >> out.lane_bits) & ((1ull << out.rank_bits) - 1ull));
+    const uint32_t job = out.job_shift >= 0 ? uint32_t(v >> out.job_shift) : uint32_t(out.ranked[rank].x);
+    const unsigned int lo = unsigned(v) & 63u, hi = unsigned(v >> 6) & 127u;
+    return make_uint4(job, rank, lo | (hi << 8), 0u);
+}
 
 // PAY: every key carries a 32-bit payload that moves with it.  REC: the sorted keys are not
 // written at all, their records are (the pass that finishes the order of the list entries).
@@ -150,8 +160,8 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
                                                       unsigned long long *__restrict__ dst,
                                                       const uint32_t *__restrict__ pay_src,
                                                       uint32_t *__restrict__ pay_dst, const int32_t *n_ptr,
-                                                      int shift, const int32_t *__restrict__ hist, int n_tiles,
-                                                      KeyRecords out = KeyRecords{})
+                                                      int shift, unsigned digit_mask, const int32_t *__restrict__ hist,
+                                                      int n_tiles, KeyRecords out = KeyRecords{})
 {
     __shared__ unsigned long long s_key[kKeyTile];
     __shared__ uint32_t s_pay[PAY ? kKeyTile : 1];
@@ -181,7 +191,7 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
 #pragma unroll
     for (int c = 0; c < kKeyChunks; ++c) {
         const bool valid = wbase + c * kWave < n;
-        const unsigned d = unsigned(key[c] >> shift) & 255u;
+        const unsigned d = unsigned(key[c] >> shift) & digit_mask;
         const unsigned long long peers = digit_peers(d, valid);
         const int before = __popcll(peers & ((1ull << lane) - 1ull));
         const int prev = cnt[d];
@@ -212,7 +222,7 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
 #pragma unroll
     for (int c = 0; c < kKeyChunks; ++c) {
         if (wbase + c * kWave < n) {
-            const unsigned d = unsigned(key[c] >> shift) & 255u;
+            const unsigned d = unsigned(key[c] >> shift) & digit_mask;
             const int slot = s_start[d] + s_cnt[wave][d] + pos[c];
             s_key[slot] = key[c];
             if (PAY) s_pay[slot] = pay[c];
@@ -222,12 +232,10 @@ __global__ __launch_bounds__(256) void k_keys_scatter(const unsigned long long *
     const int count = int(n - base < kKeyTile ? n - base : kKeyTile);
     for (int k = tid; k < count; k += 256) {
         const unsigned long long v = s_key[k];
-        const unsigned d = unsigned(v >> shift) & 255u;
+        const unsigned d = unsigned(v >> shift) & digit_mask;
         const int64_t o = int64_t(s_goff[d]) + (k - s_start[d]);
         if (REC) {
-            const int2 ja = out.ranked[(v >> out.lane_bits) & ((1ull << out.rank_bits) - 1ull)];
-            const unsigned int lo = unsigned(v) & 63u, hi = unsigned(v >> 6) & 127u;
-            out.rec[o] = make_uint4(uint32_t(ja.x), uint32_t(ja.y), lo | (hi << 8), 0u);
+            out.rec[o] = key_record(out, v);
         } else {
             dst[o] = v;
         }

@@ -163,8 +163,11 @@ int launch_select(sja_ctx *ctx, hipStream_t st, const sja_params *params, const 
 // needs no pass).
 int radix_sort_keys(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t *n_dev, int64_t n_host,
                     unsigned byte_mask, int bit_offset, bool &flip, unsigned long long *const buf[2],
-                    uint32_t *const pay[2], const KeyRecords *records = nullptr, bool *records_written = nullptr)
+                    uint32_t *const pay[2], const KeyRecords *records = nullptr, bool *records_written = nullptr,
+                    int sorted_bits = 64)
 {
+    // sorted_bits: bits above bit_offset + sorted_bits are not part of the order (a rider) and are masked
+    // out of the last digit
     if (records_written) *records_written = false;
     if (n_host <= 0) return SJA_OK;
     int last_byte = -1;         // the pass that finishes the order: with `records` it writes those instead of keys
@@ -179,21 +182,24 @@ int radix_sort_keys(sja_ctx *ctx, hipStream_t st, const Layout &L, const int32_t
         if (shift >= 64) break;
         const unsigned long long *src = buf[flip ? 1 : 0];
         unsigned long long *dst = buf[flip ? 0 : 1];
-        hipLaunchKernelGGL(k_keys_hist, dim3(n_tiles), dim3(256), 0, st, src, n_dev, shift, hist, n_tiles);
+        const int live = sorted_bits - 8 * b;                   // bits of this digit that belong to the order
+        if (live <= 0) break;
+        const unsigned digit_mask = live >= 8 ? 255u : (1u << live) - 1u;
+        hipLaunchKernelGGL(k_keys_hist, dim3(n_tiles), dim3(256), 0, st, src, n_dev, shift, digit_mask, hist, n_tiles);
         SJA_HIP(hipGetLastError(), "k_keys_hist launch");
         SJA_HIP(enqueue_scan(st, hist, int64_t(256) * n_tiles, tmp, nullptr), "radix scan launch");
         if (pay)
             hipLaunchKernelGGL((k_keys_scatter<true, false>), dim3(n_tiles), dim3(256), 0, st, src, dst, pay[flip ? 1 : 0],
-                               pay[flip ? 0 : 1], n_dev, shift, hist, n_tiles, KeyRecords{});
+                               pay[flip ? 0 : 1], n_dev, shift, digit_mask, hist, n_tiles, KeyRecords{});
         else if (records && b == last_byte) {
             hipLaunchKernelGGL((k_keys_scatter<false, true>), dim3(n_tiles), dim3(256), 0, st, src, dst,
                                static_cast<const uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), n_dev, shift,
-                               hist, n_tiles, *records);
+                               digit_mask, hist, n_tiles, *records);
             if (records_written) *records_written = true;
         } else
             hipLaunchKernelGGL((k_keys_scatter<false, false>), dim3(n_tiles), dim3(256), 0, st, src, dst,
                                static_cast<const uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), n_dev, shift,
-                               hist, n_tiles, KeyRecords{});
+                               digit_mask, hist, n_tiles, KeyRecords{});
         SJA_HIP(hipGetLastError(), "k_keys_scatter launch");
         flip = !flip;
     }
@@ -310,8 +316,13 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     // 3. list entries (one pass, counted as they are written), then sorted by (block, rank)
     const int rank_bits = bits_for(n_atoms > 1 ? n_atoms : 2);
     const int sub_bits = bits_for(n_subs > 1 ? n_subs : 2);
+    // the job of an entry rides in its key above the sorted bits when the key has room for it:
+    // then the pass that writes the records need not look it up through the rank
+    const int job_bits = bits_for(J > 1 ? J : 2);
+    const bool ride = ctx->resolve_mode != SJA_RESOLVE_LISTS_LOOKUP && kEntryLaneBits + rank_bits + sub_bits + job_bits <= 64;
+    const int job_shift = ride ? kEntryLaneBits + rank_bits + sub_bits : -1;
     const dim3 emit_grid((J + 256 * kEmitTiles - 1) / (256 * kEmitTiles), lb_bound);
-    hipLaunchKernelGGL(k_list_emit, emit_grid, dim3(256), 0, st, J, rank_bits, lb_bound, (long long)L.entry_cap, plan,
+    hipLaunchKernelGGL(k_list_emit, emit_grid, dim3(256), 0, st, J, rank_bits, job_shift, lb_bound, (long long)L.entry_cap, plan,
                        lb_begin, lb_end, lb_sub, sub_class, gap_w, ctx->seg_off, atom_dp, sub_tab, ncap_tab, abase, rank,
                        list_off, reinterpret_cast<unsigned long long *>(counters), ekey[0]);
     SJA_HIP(hipGetLastError(), "k_list_emit launch");
@@ -322,18 +333,18 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
     SJA_HIP(enqueue_scan(st, list_off, int64_t(lb_bound) + 2, tmp, nullptr), "list offset scan launch");
     bool eflip = false, packed = false;
     uint4 *rec = ws_ptr<uint4>(ctx, L.g_rec);
+    const KeyRecords records{ranked, rec, kEntryLaneBits, rank_bits, job_shift};
     if (n_entries > 0) {
         // the pass that finishes the order writes the 16-byte records straight away
         const int key_bytes = (rank_bits + sub_bits + 7) / 8;
-        const KeyRecords records{ranked, rec, kEntryLaneBits, rank_bits};
         int rc = radix_sort_keys(ctx, st, L, counters, n_entries, (1u << key_bytes) - 1u, kEntryLaneBits, eflip, ekey,
-                                 nullptr, &records, &packed);
+                                 nullptr, &records, &packed, rank_bits + sub_bits);
         if (rc != SJA_OK) return rc;
     }
     const int fb = eflip ? 1 : 0;
     if (n_entries > 0 && !packed) {
         hipLaunchKernelGGL(k_list_pack, dim3(unsigned((n_entries + 255) / 256)), dim3(256), 0, st, counters, ekey[fb],
-                           rank_bits, ranked, rec);
+                           records);
         SJA_HIP(hipGetLastError(), "k_list_pack launch");
     }
 
@@ -399,7 +410,7 @@ int resolve_with_lists(sja_ctx *ctx, hipStream_t st, const Layout &L, const sja_
         }
     }
     hipLaunchKernelGGL(k_grant_finish, dim3(unsigned((int64_t(n_subs) * kWave + 255) / 256)), dim3(256), 0, st, lb_bound, pol,
-                       plan, state, ctx->seg_off, atom_dp, atom_db, atom_area_of(ctx, L), wait, sla_class, grant_job,
+                       plan, state, ranked, ctx->seg_off, atom_dp, atom_db, atom_area_of(ctx, L), wait, sla_class, grant_job,
                        grant_cut, grant_score,
                        job_gap);
     SJA_HIP(hipGetLastError(), "k_grant_finish launch");
@@ -703,7 +714,7 @@ int sja_enable_timing(sja_ctx *ctx, int on)
 int sja_set_resolve_mode(sja_ctx *ctx, int mode)
 {
     if (!ctx) return SJA_ERR_NULL;
-    if (mode != SJA_RESOLVE_LISTS && mode != SJA_RESOLVE_MATRIX)
+    if (mode != SJA_RESOLVE_LISTS && mode != SJA_RESOLVE_MATRIX && mode != SJA_RESOLVE_LISTS_LOOKUP)
         return fail(ctx, SJA_ERR_SIZE, "sja_set_resolve_mode: unknown mode");
     ctx->resolve_mode = mode;
     return SJA_OK;

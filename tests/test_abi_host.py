@@ -92,6 +92,7 @@ def test_resolve_mode_validation(lib):
     try:
         assert lib.sja_set_resolve_mode(h, 0) == 0
         assert lib.sja_set_resolve_mode(h, 1) == 0
+        assert lib.sja_set_resolve_mode(h, 2) == 0
         assert lib.sja_status_string(lib.sja_set_resolve_mode(h, 7)) == b"SJA_ERR_SIZE"
         assert lib.sja_status_string(lib.sja_set_resolve_mode(None, 0)) == b"SJA_ERR_NULL"
     finally:

@@ -29,7 +29,7 @@ def _oracle_params(O, wl, policy=None, max_rounds=None):
                          wl.class0_override, wl.max_rounds if max_rounds is None else max_rounds)
 
 
-def full_tick_check(engine, oracle, wl, policies=None, check_resolve=True, resolve_modes=(0, 1)):
+def full_tick_check(engine, oracle, wl, policies=None, check_resolve=True, resolve_modes=(0, 1, 2)):
     """prepare, fit, select (each policy), resolve: every output equals the oracle's.
     Resolve runs once per mode (candidate lists / matrix-scanning rounds): each
     must reproduce the oracle's rounds exactly."""
