@@ -128,8 +128,18 @@ __global__ __launch_bounds__(256) void k_keys_hist(const unsigned long long *__r
         const int64_t i = base + r * 256 + tid;
         const bool valid = i < n;
         const unsigned d = valid ? unsigned(keys[i] >> shift) & digit_mask : 0u;
-        const unsigned long long peers = digit_peers(d, valid);
-        if (valid && (peers & ((1ull << lane) - 1ull)) == 0) atomicAdd(&s_h[d], __popcll(peers));
+        // counting needs no order: a wave whose keys all carry one digit (the block digits, and
+        // any digit of keys that the earlier passes have brought together) adds its count once,
+        // any other wave lets every lane add its own one (finding each lane's peers first, as
+        // the scatter has to, made this kernel bound by the instructions of that search)
+        const unsigned long long live = __ballot(valid);
+        if (live == 0) continue;
+        const unsigned d0 = unsigned(__builtin_amdgcn_readlane(int(d), __ffsll((long long)live) - 1));
+        if (__ballot(valid && d != d0) == 0) {
+            if (lane == 0) atomicAdd(&s_h[d0], __popcll(live));
+        } else if (valid) {
+            atomicAdd(&s_h[d], 1);
+        }
     }
     __syncthreads();
     hist[int64_t(tid) * n_tiles + blockIdx.x] = s_h[tid];
