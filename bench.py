@@ -53,8 +53,8 @@ def secondary_rates(wl, n_atoms_total, call_ms, rounds):
 FIT_TRAFFIC = {
     "workload": ("stress", 0),
     "sources_sha256": "c8e03b40c653190bbaddc66b9dce349b1f4f729e9d9c9efb8aebfc76fe43d981",
-    "fetch_kib": 51523.7, "fetch_scale": 2.0,
-    "write_kib": 8391605.0, "write_scale": 1.0,
+    "fetch_kib": 51530.1, "fetch_scale": 2.0,
+    "write_kib": 8391936.0, "write_scale": 1.0,
 }
 
 
