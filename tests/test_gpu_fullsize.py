@@ -281,15 +281,24 @@ def test_grants_match_the_oracle_digests(name):
     gw = torch.arange(1, wl.n_gaps + 1, dtype=torch.int64, device="cuda:0")
     jw = torch.arange(1, wl.n_jobs + 1, dtype=torch.int64, device="cuda:0")
     assert gold.get("resolve")
-    for cap, want in gold["resolve"].items():
-        t.resolve(P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, int(cap)))
-        rounds, stable = t.rounds.cpu().tolist()
-        got_r = {"rounds": rounds, "stable": stable, "grants": int((t.grant_job >= 0).sum().item()),
-                 "grant_job": int((t.grant_job.to(torch.int64) * gw).sum().item()),
-                 "grant_cut": int((t.grant_cut.to(torch.int64) * gw).sum().item()),
-                 "grant_score": int(t.grant_score.sum().item()),
-                 "job_gap": int((t.job_gap.to(torch.int64) * jw).sum().item())}
-        assert got_r == want, f"round cap {cap}"
+    # mode 0: the lists as they are built by default; mode 2: the form in which the records' jobs
+    # are looked up through their ranks (what very large batches get by themselves)
+    try:
+        for mode in (0, 2):
+            eng.sja_set_resolve_mode(mode)
+            for cap, want in gold["resolve"].items():
+                for out in (t.grant_job, t.grant_cut, t.grant_score, t.job_gap, t.rounds):
+                    out.fill_(-5)
+                t.resolve(P.Params.make(wl.policy, wl.wait_scale, wl.sla_weight, wl.class0_override, int(cap)))
+                rounds, stable = t.rounds.cpu().tolist()
+                got_r = {"rounds": rounds, "stable": stable, "grants": int((t.grant_job >= 0).sum().item()),
+                         "grant_job": int((t.grant_job.to(torch.int64) * gw).sum().item()),
+                         "grant_cut": int((t.grant_cut.to(torch.int64) * gw).sum().item()),
+                         "grant_score": int(t.grant_score.sum().item()),
+                         "job_gap": int((t.job_gap.to(torch.int64) * jw).sum().item())}
+                assert got_r == want, f"round cap {cap}, mode {mode}"
+    finally:
+        eng.sja_set_resolve_mode(0)
 
 
 def test_beyond_stress_64bit_indexing(oracle):
