@@ -27,6 +27,7 @@ __device__ __forceinline__ int dpp_from(int identity, int v)
 }
 constexpr int kDppRowShr1 = 0x111, kDppRowShr2 = 0x112, kDppRowShr4 = 0x114, kDppRowShr8 = 0x118;
 constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
+constexpr int kDppWaveShr1 = 0x138;       // lane i receives lane i - 1 across the whole wave; lane 0 keeps `identity`
 
 // Inclusive scans over the 64 lanes of a wave: four shifts inside each row of
 // 16, then the row totals handed on to the rows after them.
@@ -381,8 +382,8 @@ __device__ __forceinline__ void prepare_job_wide(
         int ts = wave_scan_add(s[PER - 1]), tm = wave_scan_max_dpp(m[PER - 1]), tl = wave_scan_max_dpp(l[PER - 1]);
         const int tot_s = lane_value(ts, kWave - 1), tot_m = lane_value(tm, kWave - 1), tot_l = lane_value(tl, kWave - 1);
         // exclusive over lanes = inclusive of the lane before
-        int es = __shfl_up(ts, 1, kWave), em = __shfl_up(tm, 1, kWave), el = __shfl_up(tl, 1, kWave);
-        if (lane == 0) { es = 0; em = INT32_MIN; el = -1; }
+        int es = dpp_from<kDppWaveShr1, 0xf>(0, ts), em = dpp_from<kDppWaveShr1, 0xf>(INT32_MIN, tm);
+        int el = dpp_from<kDppWaveShr1, 0xf>(-1, tl);
         es += carry_sum;
         em = max(em, carry_peak);
         el = max(el, carry_last);
