@@ -412,10 +412,11 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
         }
         // claim words only of records that cover some lane still looking
         const int all_lo = __ffsll((long long)need) - 1, all_hi = 63 - __clzll((long long)need);
-        unsigned long long cw[SW];
+        unsigned long long cw[HELD ? 1 : SW];      // the claim words; HELD asks the bitmap instead
+        bool open_job[HELD ? SW : 1];
         if (HELD) {
 #pragma unroll
-            for (int k = 0; k < SW; ++k) cw[k] = held_bit(s_held, rr[k].x) ? ~0ull : 0ull;
+            for (int k = 0; k < SW; ++k) open_job[k] = !held_bit(s_held, rr[k].x);
         } else {
             // every lane loads (the others word 0, one request per wave) so that the loads of all
             // chunks are issued back to back: a load that may be skipped makes the next one wait for it
@@ -441,9 +442,9 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
             // records worth a look: free, and covering some lane that can take one here
             const int need_lo = __ffsll((long long)still) - 1;
             const int need_hi = 63 - __clzll((long long)still);
-            const uint32_t stamp = uint32_t(cw[k] >> 32);
-            const bool free_rec = c0 + k * kWave + lane < list_end &&
-                                  (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu)) &&
+            const uint32_t stamp = HELD ? 0u : uint32_t(cw[HELD ? 0 : k] >> 32);
+            const bool not_held = HELD ? open_job[HELD ? k : 0] : (stamp == 0 || (stamp >= uint32_t(round) && stamp != 0xffffffffu));
+            const bool free_rec = c0 + k * kWave + lane < list_end && not_held &&
                                   int(rr[k].z & 255u) <= need_hi && int(rr[k].z >> 8) > need_lo;
             unsigned long long fm = __ballot(free_rec);
             int hk = -1;
@@ -456,8 +457,9 @@ __device__ __forceinline__ void grant_step(int round, bool propose, int lane, in
                 if (__any(h)) {
                     // record t's job, atom and claim word straight from lane t's registers
                     const int tj = __builtin_amdgcn_readlane(int(rr[k].x), t), ta = __builtin_amdgcn_readlane(int(rr[k].y), t);
-                    const unsigned int t_lo = __builtin_amdgcn_readlane(int(uint32_t(cw[k])), t);
-                    const unsigned int t_hi = __builtin_amdgcn_readlane(int(uint32_t(cw[k] >> 32)), t);
+                    // (with HELD the claim word of the record a lane settles on is fetched afterwards)
+                    const unsigned int t_lo = HELD ? 0u : __builtin_amdgcn_readlane(int(uint32_t(cw[HELD ? 0 : k])), t);
+                    const unsigned int t_hi = HELD ? 0u : __builtin_amdgcn_readlane(int(uint32_t(cw[HELD ? 0 : k] >> 32)), t);
                     if (h) { hk = t; hit = k * kWave + t; hj = tj; ha = ta; hw_lo = t_lo; hw_hi = t_hi; }
                 }
                 if (!__any(elig && hk < 0)) break;
